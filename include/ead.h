@@ -1,0 +1,214 @@
+/*
+ * ead.h -- C ABI of the Entropy Adaptive Decoding library for AMD MI355X (gfx950).
+ *
+ * Entropy Adaptive Decoding (Section 3 of the paper) generates text with a pair of
+ * decoder-only language models that share one vocabulary, a small one M_S and a
+ * large one M_L.  After every generated token the Shannon entropy H_t of the
+ * active model's next-token distribution (Eq. 1-2, taken on the raw logits) is
+ * pushed into a rolling window of w entries; the window mean (Eq. 3) is compared
+ * with a threshold tau, and the active model changes when the mean crosses tau
+ * and the current model has produced at least d_min tokens (Eq. 4, Algorithm 1).
+ *
+ * Conventions
+ *  - Plain C11.  Every function returns an ead_status; nothing throws or aborts.
+ *  - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *    memory on the GPU that was current when the handle was created.
+ *  - Weights are BORROWED only for the duration of ead_create(): the library
+ *    copies them into its own streaming layout, after which the caller may free
+ *    them.  Everything else the library needs (KV caches, gate state, scratch)
+ *    it allocates in ead_create() and frees in ead_destroy().
+ *  - Outputs are caller-owned host buffers unless the name ends in _dev.
+ *  - A handle serves one call at a time (calls are not re-entrant).  Work is
+ *    queued on ead_params.hip_stream and every call returns after its results
+ *    have reached the host buffers.
+ *  - Decoding is greedy (token = arg max of the raw logits, lowest index on a
+ *    tie); Algorithm 1's temperature-sampling step is not implemented.
+ *  - Models: pre-norm decoders with RMSNorm, rotary position embedding
+ *    ("rotate-half" pairing, angle pos * theta^(-2i/head_dim)), grouped-query
+ *    attention (query head h reads KV head h / (n_heads / n_kv_heads)) and a
+ *    SwiGLU feed-forward block; no biases.
+ *  - Shape limits: d_model, d_ffn multiples of 32; vocab and n_heads*head_dim
+ *    multiples of 16; head_dim one of 32, 64, 128.
+ */
+#ifndef EAD_H
+#define EAD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EAD_OK = 0,
+    EAD_ERR_INVALID_ARG = 1,    /* null pointer, negative size, w < 1, d_min < 1, NaN tau ... */
+    EAD_ERR_SHAPE = 2,          /* model shape outside the limits above */
+    EAD_ERR_VOCAB_MISMATCH = 3, /* the two models do not share one vocabulary size */
+    EAD_ERR_OOM = 4,            /* device or host allocation failed */
+    EAD_ERR_SEQ_OVERFLOW = 5,   /* prompt + new tokens exceed max_seq, or batch > max_batch */
+    EAD_ERR_NONFINITE = 6,      /* an entropy came out NaN/Inf (non-finite logits) */
+    EAD_ERR_DEVICE = 7,         /* a HIP call failed; see ead_last_error() */
+    EAD_ERR_NO_DEVICE = 8,      /* no usable GPU */
+    EAD_ERR_STATE = 9           /* call order violated (e.g. ead_decode before ead_begin) */
+} ead_status;
+
+typedef enum { EAD_F32 = 0, EAD_BF16 = 1 } ead_dtype;
+typedef enum { EAD_MODEL_SMALL = 0, EAD_MODEL_LARGE = 1 } ead_model_id;
+typedef enum { EAD_NATS = 0, EAD_BITS = 1 } ead_unit;   /* Eq. 2 is written in bits */
+
+/* One decoder.  All pointers are DEVICE pointers; matrices are row-major
+ * [out_features, in_features] in `dtype`; the norm gains are always float32. */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    float rms_eps, rope_theta;
+    int32_t dtype;                       /* ead_dtype of the matrices */
+    const void *embed;                   /* [vocab, d_model]                      */
+    const void *const *wq;               /* host array of n_layers device pointers, each [n_heads*head_dim, d_model] */
+    const void *const *wk;               /* ... each [n_kv_heads*head_dim, d_model] */
+    const void *const *wv;               /* ... each [n_kv_heads*head_dim, d_model] */
+    const void *const *wo;               /* ... each [d_model, n_heads*head_dim]    */
+    const void *const *w_gate;           /* ... each [d_ffn, d_model]               */
+    const void *const *w_up;             /* ... each [d_ffn, d_model]               */
+    const void *const *w_down;           /* ... each [d_model, d_ffn]               */
+    const float *const *norm_attn;       /* ... each [d_model] float32              */
+    const float *const *norm_ffn;        /* ... each [d_model] float32              */
+    const float *norm_final;             /* [d_model] float32                       */
+    const void *lm_head;                 /* [vocab, d_model]                        */
+} ead_model_desc;
+
+/* Inputs of Algorithm 1 other than the prompt and the models. */
+typedef struct {
+    int32_t window;        /* w >= 1; the paper's experiments use 5                         */
+    float tau;             /* threshold on the window mean, in `unit`                        */
+    int32_t d_min;         /* minimum tokens by one model before a switch, >= 1; paper: 10   */
+    int32_t unit;          /* ead_unit of tau and of every reported entropy                  */
+    int32_t max_batch;     /* sequences decoded together, >= 1                               */
+    int32_t max_seq;       /* prompt + generated tokens per sequence                         */
+    int32_t eos_id;        /* stop a sequence after this token; -1 = never                   */
+    void *hip_stream;      /* hipStream_t to queue work on (borrowed); NULL = default stream */
+} ead_params;
+
+typedef struct ead_handle ead_handle;
+
+/* Counters since ead_begin() (or the last ead_reset_stats()). */
+typedef struct {
+    int64_t tokens_small, tokens_large;    /* generated tokens by model                      */
+    int64_t switches;                      /* model changes summed over sequences            */
+    int64_t steps_small, steps_large;      /* forward passes that emitted tokens             */
+    int64_t catchup_rows_small, catchup_rows_large; /* extra positions a model had to consume
+                                              because the other model had produced them      */
+    int64_t host_syncs;                    /* times the host waited for a gate decision      */
+    double algorithmic_bytes;              /* weights streamed + KV read, by the byte model:
+                                              per pass, the model's weight bytes plus, per
+                                              token row, kv_bytes_per_position * keys read   */
+    double large_share;                    /* tokens_large / (tokens_small + tokens_large)   */
+    double param_ratio;                    /* Table 1 footnote: (a*P_S + b*P_L) / P_L        */
+} ead_stats;
+
+/* ---- life cycle ---------------------------------------------------------------- */
+
+/* Build a handle for a model pair (Algorithm 1's M_S, M_L, tau, w, d_min).
+ * Copies both models into the library's layout and allocates KV caches for
+ * max_batch x max_seq positions per model.  Errors: INVALID_ARG, SHAPE,
+ * VOCAB_MISMATCH, OOM, NO_DEVICE, DEVICE.  *out is NULL on error. */
+ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *large_model,
+                      const ead_params *params, ead_handle **out);
+void ead_destroy(ead_handle *h);
+/* Message of the last failed call on this handle (handle-owned string); with
+ * h == NULL, the message of the last failed ead_create() on this thread. */
+const char *ead_last_error(const ead_handle *h);
+/* Change tau / d_min / window / unit / eos_id between runs (max_* and the stream stay). */
+ead_status ead_set_gate(ead_handle *h, int32_t window, float tau, int32_t d_min, int32_t unit,
+                        int32_t eos_id);
+
+/* ---- Algorithm 1 --------------------------------------------------------------- */
+
+/* Whole algorithm for `batch` independent sequences (each row is its own instance
+ * of Algorithm 1: own window, counter and current model).
+ *   prompt_tokens  host, the prompts concatenated, sum(prompt_lens) entries
+ *   prompt_lens    host [batch], each >= 1
+ *   out_tokens     host [batch, max_new_tokens]   generated tokens y
+ *   out_model_id   host [batch, max_new_tokens]   model that produced each token (0 = M_S)
+ *   out_entropy    host [batch, max_new_tokens]   H_t of the logits the token came from
+ *   out_window_mean host [batch, max_new_tokens]  window mean after H_t (nullable)
+ *   out_lens       host [batch]                   tokens generated per row (eos may cut it)
+ * Equivalent to ead_begin + ead_decode(max_new_tokens) + ead_fetch. */
+ead_status ead_generate(ead_handle *h, const int32_t *prompt_tokens, const int32_t *prompt_lens,
+                        int32_t batch, int32_t max_new_tokens, int32_t *out_tokens,
+                        uint8_t *out_model_id, float *out_entropy, float *out_window_mean,
+                        int32_t *out_lens);
+
+/* Start a run: reset all state, load the prompts, and let BOTH models consume
+ * every prompt token but the last (so that no entropy is recorded yet and the
+ * first decode step produces the first token).  max_new_tokens bounds the run. */
+ead_status ead_begin(ead_handle *h, const int32_t *prompt_tokens, const int32_t *prompt_lens,
+                     int32_t batch, int32_t max_new_tokens);
+/* Run n_steps iterations of Algorithm 1's loop for every unfinished row
+ * (one token per row per step, including any catch-up the active model needs).
+ * Returns after the last step's work has finished on the GPU. */
+ead_status ead_decode(ead_handle *h, int32_t n_steps);
+/* Copy what has been generated so far to host buffers laid out as in
+ * ead_generate with row stride `stride` (>= tokens generated). Any pointer may be NULL. */
+ead_status ead_fetch(ead_handle *h, int32_t stride, int32_t *out_tokens, uint8_t *out_model_id,
+                     float *out_entropy, float *out_window_mean, int32_t *out_lens);
+
+/* ---- teacher-forced entry points (parity tests) --------------------------------- */
+
+/* One model over one token sequence: logits, entropy and arg max at every
+ * position (position i predicts token i+1).
+ *   tokens host [len]; out_logits host [len, vocab] float32 (nullable);
+ *   out_entropy host [len] (nullable); out_argmax host [len] (nullable). */
+ead_status ead_score(ead_handle *h, int32_t which_model, const int32_t *tokens, int32_t len,
+                     float *out_logits, float *out_entropy, int32_t *out_argmax);
+
+/* Algorithm 1 along a GIVEN trajectory: at generated position i the logits come
+ * from model forced_model_id[row, i] (with whatever catch-up that model needs), the
+ * token appended is forced_tokens[row, i], and the library reports what it computed:
+ *   out_argmax [batch, n_new], out_entropy, out_window_mean as in ead_generate,
+ *   out_decision [batch, n_new]: the model Eq. 4 selects for the next token when the
+ *   current model is forced_model_id[row, i] and the dwell counter follows the forced ids.
+ * All arrays are host memory; prompts as in ead_generate. */
+ead_status ead_replay(ead_handle *h, const int32_t *prompt_tokens, const int32_t *prompt_lens,
+                      int32_t batch, int32_t n_new, const int32_t *forced_tokens,
+                      const uint8_t *forced_model_id, int32_t *out_argmax, float *out_entropy,
+                      float *out_window_mean, uint8_t *out_decision);
+
+/* ---- the entropy / gate epilogue on its own (Eq. 1-4) ---------------------------- */
+
+/* Row-wise entropy (Eq. 1-2) and arg max of a logits matrix already in device memory.
+ *   logits_dev [rows, vocab] of `dtype`, row-major; H_dev [rows] float32 in `unit`;
+ *   argmax_dev [rows] int32 (nullable).  Asynchronous on `hip_stream`.
+ * Uses an internal scratch buffer that the first call on a device allocates. */
+ead_status ead_entropy_argmax(const void *logits_dev, int32_t dtype, int32_t rows, int32_t vocab,
+                              int32_t unit, float *H_dev, int32_t *argmax_dev, void *hip_stream);
+
+/* Rolling window + switch rule (Eq. 3-4) for `rows` independent sequences, state on device. */
+typedef struct ead_gate ead_gate;
+ead_status ead_gate_create(int32_t rows, int32_t window, float tau, int32_t d_min, void *hip_stream,
+                           ead_gate **out);
+/* Feed one entropy per row (H_dev [rows] float32, already in the unit of tau).
+ * Writes, all nullable device pointers: model_id_dev [rows] uint8 = model that was
+ * current for this token, window_mean_dev [rows] float32, next_model_dev [rows] uint8. */
+ead_status ead_gate_step(ead_gate *g, const float *H_dev, uint8_t *model_id_dev,
+                         float *window_mean_dev, uint8_t *next_model_dev);
+/* Entropy + arg max of logits_dev [rows, vocab] followed by the gate step, in one call. */
+ead_status ead_gate_step_logits(ead_gate *g, const void *logits_dev, int32_t dtype, int32_t vocab,
+                                int32_t unit, float *H_dev, int32_t *argmax_dev,
+                                uint8_t *model_id_dev, float *window_mean_dev,
+                                uint8_t *next_model_dev);
+ead_status ead_gate_reset(ead_gate *g);
+void ead_gate_destroy(ead_gate *g);
+
+/* ---- bookkeeping ----------------------------------------------------------------- */
+ead_status ead_get_stats(ead_handle *h, ead_stats *out);
+ead_status ead_reset_stats(ead_handle *h);
+/* Run only one model for every row (0 / 1), or follow the gate (-1, the default).
+ * Used to time small-only and large-only decoding on the same prompts. */
+ead_status ead_force_model(ead_handle *h, int32_t which_model_or_minus1);
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t ead_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EAD_H */

@@ -1,0 +1,133 @@
+// Shared device helpers: storage types, 8-element tile loads, wave64 reductions,
+// and the tiled weight layout every linear kernel streams.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ead {
+
+constexpr int kWave = 64;
+constexpr int kTileRows = 16;   // weight rows per tile (the M of a 16x16x32 MFMA)
+constexpr int kTileK = 32;      // contraction elements per tile
+constexpr int kLaneElems = 8;   // elements one lane holds of a tile
+
+struct bf16_t { uint16_t u; };
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4e_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
+// round-to-nearest-even; finite inputs and infinities
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v.u); }
+template <typename T> __device__ __forceinline__ T from_f32(float f);
+template <> __device__ __forceinline__ float from_f32<float>(float f) { return f; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) { bf16_t r; r.u = f32_to_bf16(f); return r; }
+
+// Eight consecutive elements of type T held by one lane.
+template <typename T> struct Vec8;
+template <> struct Vec8<bf16_t> {
+    u32x4_t raw;
+    __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const u32x4_t *>(p); }
+    __device__ __forceinline__ void load_stream(const bf16_t *p) {
+        raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    }
+    __device__ __forceinline__ void unpack(float (&f)[8]) const {
+        f[0] = __uint_as_float(raw.x << 16); f[1] = __uint_as_float(raw.x & 0xFFFF0000u);
+        f[2] = __uint_as_float(raw.y << 16); f[3] = __uint_as_float(raw.y & 0xFFFF0000u);
+        f[4] = __uint_as_float(raw.z << 16); f[5] = __uint_as_float(raw.z & 0xFFFF0000u);
+        f[6] = __uint_as_float(raw.w << 16); f[7] = __uint_as_float(raw.w & 0xFFFF0000u);
+    }
+    __device__ __forceinline__ void zero() { raw = u32x4_t{0u, 0u, 0u, 0u}; }
+};
+template <> struct Vec8<float> {
+    f32x4e_t lo, hi;
+    __device__ __forceinline__ void load(const float *p) {
+        lo = *reinterpret_cast<const f32x4e_t *>(p); hi = *reinterpret_cast<const f32x4e_t *>(p + 4);
+    }
+    __device__ __forceinline__ void load_stream(const float *p) {
+        lo = __builtin_nontemporal_load(reinterpret_cast<const f32x4e_t *>(p));
+        hi = __builtin_nontemporal_load(reinterpret_cast<const f32x4e_t *>(p + 4));
+    }
+    __device__ __forceinline__ void unpack(float (&f)[8]) const {
+        f[0] = lo.x; f[1] = lo.y; f[2] = lo.z; f[3] = lo.w; f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
+    }
+    __device__ __forceinline__ void zero() { lo = f32x4e_t{0.f, 0.f, 0.f, 0.f}; hi = lo; }
+};
+
+template <typename T> __device__ __forceinline__ void store8(T *p, const float (&f)[8]);
+template <> __device__ __forceinline__ void store8<float>(float *p, const float (&f)[8]) {
+    *reinterpret_cast<float4 *>(p) = make_float4(f[0], f[1], f[2], f[3]);
+    *reinterpret_cast<float4 *>(p + 4) = make_float4(f[4], f[5], f[6], f[7]);
+}
+template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t *p, const float (&f)[8]) {
+    uint4 r;
+    r.x = (uint32_t)f32_to_bf16(f[0]) | ((uint32_t)f32_to_bf16(f[1]) << 16);
+    r.y = (uint32_t)f32_to_bf16(f[2]) | ((uint32_t)f32_to_bf16(f[3]) << 16);
+    r.z = (uint32_t)f32_to_bf16(f[4]) | ((uint32_t)f32_to_bf16(f[5]) << 16);
+    r.w = (uint32_t)f32_to_bf16(f[6]) | ((uint32_t)f32_to_bf16(f[7]) << 16);
+    *reinterpret_cast<uint4 *>(p) = r;
+}
+
+// ---- wave64 reductions -------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+
+// ---- tiled weight layout -------------------------------------------------------------
+// A matrix with Np rows (multiple of 16) and K columns (multiple of 32) is stored as
+// tiles of 16 rows x 32 columns.  Tile (rb, kc) occupies 512 consecutive elements at
+// (rb * K/32 + kc) * 512; inside it, lane l of a wave owns the 8 elements
+//   row rb*16 + (l & 15), columns kc*32 + (l >> 4)*8 .. +8
+// at offset l*8.  This is the register layout of the A operand of the 16x16x32 MFMA,
+// so a wave reads a whole row block as one contiguous, fully coalesced stream whether
+// it feeds the matrix cores or plain FMAs.
+__host__ __device__ __forceinline__ size_t tile_offset(int rb, int kc, int KC) {
+    return ((size_t)rb * (size_t)KC + (size_t)kc) * 512;
+}
+
+// ---- online soft-max statistics for the entropy (Eq. 1-2) ------------------------------
+// For a set of logits: m = max, Z = sum exp(l-m), S = sum exp(l-m)(l-m), plus the arg max
+// (lowest index on ties).  H = ln Z - S/Z.  merge() combines two disjoint sets.
+struct EntStat {
+    float m, Z, S;
+    int idx;
+    __device__ __forceinline__ void init() { m = -INFINITY; Z = 0.f; S = 0.f; idx = 0x7FFFFFFF; }
+    __device__ __forceinline__ void merge(const EntStat &o) {
+        if (o.Z == 0.f) return;                      // empty set
+        if (Z == 0.f) { *this = o; return; }
+        float M = fmaxf(m, o.m);
+        float da = m - M, db = o.m - M;              // <= 0
+        float ea = __expf(da), eb = __expf(db);
+        float nS = ea * (S + da * Z) + eb * (o.S + db * o.Z);
+        float nZ = ea * Z + eb * o.Z;
+        if (o.m > m || (o.m == m && o.idx < idx)) idx = o.idx;
+        m = M; Z = nZ; S = nS;
+    }
+};
+__device__ __forceinline__ EntStat wave_merge(EntStat s) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        EntStat t;
+        t.m = __shfl_xor(s.m, o, kWave); t.Z = __shfl_xor(s.Z, o, kWave);
+        t.S = __shfl_xor(s.S, o, kWave); t.idx = __shfl_xor(s.idx, o, kWave);
+        s.merge(t);
+    }
+    return s;
+}
+
+}  // namespace ead

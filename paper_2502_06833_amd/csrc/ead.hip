@@ -1,0 +1,1046 @@
+// Host side of the Entropy Adaptive Decoding library: handle, weight re-tiling, the
+// per-step scheduler (Algorithm 1's loop over a batch of independent sequences) and
+// the C ABI declared in include/ead.h.  All arithmetic of the method runs in the
+// kernels of linear.hpp / attention.hpp / entropy.hpp and the small kernels below.
+#include "../../include/ead.h"
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <string>
+#include <type_traits>
+#include <vector>
+
+#include "attention.hpp"
+#include "common.hpp"
+#include "entropy.hpp"
+#include "linear.hpp"
+
+using namespace ead;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+// ======================================================================================
+// small kernels: weight re-tiling, plan, embedding gather, LM-head finalisation
+// ======================================================================================
+enum PackMode { PACK_PLAIN = 0, PACK_QKV = 1, PACK_GATEUP = 2 };
+
+// Row-major [N, K] sources -> tiled layout (see common.hpp).  One thread per 8 elements.
+//  PACK_QKV     rows = [q; k; v]; inside every q/k head, packed rows (2i, 2i+1) are the
+//               rotary pair (i, i + hd/2) so that a lane pair holds both halves.
+//  PACK_GATEUP  packed rows (2i, 2i+1) = (gate row i, up row i).
+template <typename WT>
+__global__ __launch_bounds__(256) void k_pack_weights(const WT *s0, const WT *s1, const WT *s2, WT *dst,
+                                                      int Np, int K, int mode, int hd, int NQ, int NK) {
+    const int KC = K >> 5;
+    const size_t chunk = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (chunk >= (size_t)Np * K / 8) return;
+    const size_t tile = chunk >> 6;
+    const int l = (int)(chunk & 63);
+    const int rb = (int)(tile / KC), kc = (int)(tile % KC);
+    const int p = rb * 16 + (l & 15), k = kc * 32 + (l >> 4) * 8;
+    const WT *src;
+    if (mode == PACK_PLAIN) src = s0 + (size_t)p * K;
+    else if (mode == PACK_GATEUP) src = ((p & 1) ? s1 : s0) + (size_t)(p >> 1) * K;
+    else {
+        if (p < NQ + NK) {
+            const int pp = p < NQ ? p : p - NQ;
+            const int head = pp / hd, r = pp % hd, dim = (r >> 1) + (r & 1) * (hd >> 1);
+            src = (p < NQ ? s0 : s1) + (size_t)(head * hd + dim) * K;
+        } else src = s2 + (size_t)(p - NQ - NK) * K;
+    }
+    Vec8<WT> v; v.load(src + k);
+    float f[8]; v.unpack(f);
+    store8<WT>(dst + chunk * 8, f);
+}
+
+template <typename WT>
+__global__ __launch_bounds__(256) void k_copy(const WT *src, WT *dst, size_t n) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+// Per-sequence decoding state, all device arrays indexed by sequence.
+struct SeqState {
+    int *tokens;            // [max_batch][max_seq] prompt + generated
+    int *len;               // tokens present
+    int *kvlen;             // [2][max_batch] positions each model has consumed
+    int *model, *c, *ngen, *done, *last_step;
+    float *ring;            // [max_batch][w_cap]
+    int *out_tok; uint8_t *out_mid; float *out_H; float *out_Hbar; uint8_t *out_dec;   // [max_batch][cap]
+    int *forced_tok; uint8_t *forced_mid;                                              // replay, [max_batch][cap]
+    int *err;
+    int max_batch, max_seq, cap;
+};
+
+struct Plan { int *hdr; int *row_seq, *row_pos, *lm_row, *lm_seq; };
+
+struct PlanArgs {
+    SeqState s; Plan p;
+    int batch, m, budget, limit_off, lm_mode, ignore_model, step;
+};
+
+// Rows of one forward pass of model m: for every sequence that m serves, the positions
+// m has not consumed yet (one in steady decoding, more right after a switch).
+// lm_mode 0: no logits; 1: last row of sequences whose chunk reaches the end; 2: every row.
+__global__ __launch_bounds__(256) void k_plan(PlanArgs a) {
+    extern __shared__ int sm[];
+    int *s_off = sm, *s_n = sm + a.batch, *s_have = sm + 2 * a.batch;
+    const int tid = threadIdx.x;
+    if (tid == 0) {
+        int off = 0, nlm = 0;
+        for (int b = 0; b < a.batch; ++b) {
+            const bool active = !a.s.done[b] && (a.ignore_model || a.s.model[b] == a.m) &&
+                                (a.step < 0 || a.s.last_step[b] != a.step);
+            const int target = a.s.len[b] - a.limit_off, have = a.s.kvlen[a.m * a.s.max_batch + b];
+            int n = active ? max(0, target - have) : 0;
+            n = min(n, a.budget - off);
+            s_off[b] = off; s_n[b] = n; s_have[b] = have;
+            if (a.lm_mode == 1 && n > 0 && have + n == target) { a.p.lm_row[nlm] = off + n - 1; a.p.lm_seq[nlm] = b; ++nlm; }
+            off += n;
+        }
+        a.p.hdr[0] = off;
+        a.p.hdr[1] = a.lm_mode == 2 ? off : nlm;
+    }
+    __syncthreads();
+    for (int b = 0; b < a.batch; ++b) {
+        const int off = s_off[b], n = s_n[b], have = s_have[b];
+        for (int j = tid; j < n; j += 256) {
+            a.p.row_seq[off + j] = b; a.p.row_pos[off + j] = have + j;
+            if (a.lm_mode == 2) { a.p.lm_row[off + j] = off + j; a.p.lm_seq[off + j] = b; }
+        }
+    }
+    for (int b = tid; b < a.batch; b += 256) a.s.kvlen[a.m * a.s.max_batch + b] = s_have[b] + s_n[b];
+}
+
+template <typename WT>
+__global__ __launch_bounds__(256) void k_embed(const WT *embed, const int *tokens, const int *hdr, const int *row_seq,
+                                               const int *row_pos, int max_seq, int d, float *x) {
+    const int t = blockIdx.x;
+    if (t >= hdr[0]) return;
+    const int tok = tokens[(size_t)row_seq[t] * max_seq + row_pos[t]];
+    const WT *src = embed + (size_t)tok * d;
+    for (int k = threadIdx.x * 8; k < d; k += 2048) {
+        Vec8<WT> v; v.load(src + k);
+        float f[8]; v.unpack(f);
+        store8<float>(x + (size_t)t * d + k, f);
+    }
+}
+
+struct FinArgs {
+    SeqState s; Plan p; GateCfg cfg;
+    const EntPartial *partials; int n_part; int unit;
+    int score_mode; float *sc_H; int *sc_arg;      // score: indexed by position
+    int model_id, max_new, eos_id, replay, n_new, force_model, step;
+};
+
+// One wave per sequence that gets logits this pass: finish entropy and arg max from the
+// LM-head partials, then run Algorithm 1's bookkeeping for that sequence: record the
+// token, its model and entropy, push the window, apply the switch rule, append the token.
+__global__ __launch_bounds__(64) void k_lm_finalize(FinArgs a) {
+    const int i = blockIdx.x;
+    if (i >= a.p.hdr[1]) return;
+    const EntStat st = merge_partials(a.partials + (size_t)i * a.n_part, a.n_part);
+    const float H = entropy_from(st, a.unit);
+    if (threadIdx.x != 0) return;
+    const int b = a.p.lm_seq[i];
+    if (a.score_mode) {
+        const int pos = a.p.row_pos[a.p.lm_row[i]];
+        a.sc_H[pos] = H; a.sc_arg[pos] = st.idx;
+        return;
+    }
+    const int n = a.s.ngen[b], cur = a.model_id;
+    int next = cur, c = a.s.c[b];
+    const float hb = gate_update(a.s.ring + (size_t)b * a.cfg.w, n, H, a.cfg, &next, &c);
+    const size_t o = (size_t)b * a.s.cap + n;
+    a.s.out_tok[o] = st.idx; a.s.out_mid[o] = (uint8_t)cur; a.s.out_H[o] = H; a.s.out_Hbar[o] = hb;
+    a.s.out_dec[o] = (uint8_t)next;
+    int tok = st.idx;
+    if (a.replay) {
+        tok = a.s.forced_tok[o];
+        const int nxt = (n + 1 < a.n_new) ? a.s.forced_mid[o + 1] : cur;
+        if (nxt != cur) c = 0;
+        next = nxt;
+    }
+    if (a.force_model >= 0) next = a.force_model;
+    const int L = a.s.len[b];
+    a.s.tokens[(size_t)b * a.s.max_seq + L] = tok;
+    a.s.len[b] = L + 1; a.s.ngen[b] = n + 1;
+    a.s.done[b] = (n + 1 >= a.max_new) || (a.eos_id >= 0 && tok == a.eos_id);
+    a.s.model[b] = next; a.s.c[b] = c; a.s.last_step[b] = a.step;
+    if (!isfinite(H)) atomicOr(a.s.err, 1);
+}
+
+// entropy-only finalisation for ead_entropy_argmax
+__global__ __launch_bounds__(64) void k_entropy_finalize(const EntPartial *partials, int n_part, int rows, int unit,
+                                                         float *H, int *argmax) {
+    const int r = blockIdx.x;
+    if (r >= rows) return;
+    const EntStat st = merge_partials(partials + (size_t)r * n_part, n_part);
+    if (threadIdx.x == 0) { H[r] = entropy_from(st, unit); if (argmax) argmax[r] = st.idx; }
+}
+
+// ======================================================================================
+// host structures
+// ======================================================================================
+struct Layer { void *wqkv, *wo, *wgu, *wdown; float *g_attn, *g_ffn; void *kcache, *vcache; };
+
+struct Model {
+    int L, d, H, KV, hd, F, V, dtype;
+    float eps, theta;
+    void *embed, *lm_head; float *g_final; float2 *rope;
+    std::vector<Layer> layers;
+    double weight_bytes_nolm, lm_bytes, kv_bytes_per_pos, n_params;
+    size_t esz() const { return dtype == EAD_BF16 ? 2 : 4; }
+};
+
+struct HostSeq { int len, kvlen[2], model, c, ngen, done, last_step; };
+
+}  // namespace
+
+struct ead_handle {
+    Model mdl[2];
+    ead_params prm;
+    hipStream_t stream;
+    int Tmax, items_max, lm_grid, score_rows;
+    SeqState s; Plan plan; GateCfg cfg;
+    // scratch
+    float *x, *q, *o, *hbuf; bf16_t *xp_a, *xp_o, *xp_h;
+    float *part_o; float2 *part_ml; EntPartial *lm_part; float *logits_dump; float *sc_H; int *sc_arg;
+    int *h_model, *h_done;   // pinned
+    std::vector<void *> allocs;
+    std::vector<HostSeq> hs;
+    int batch, max_new, began, replay, n_new, force_model, step;
+    ead_stats stats;
+    std::string err;
+};
+
+namespace {
+
+ead_status fail(ead_handle *h, ead_status st, const char *fmt, ...) {
+    char buf[512];
+    va_list ap; va_start(ap, fmt); vsnprintf(buf, sizeof buf, fmt, ap); va_end(ap);
+    if (h) h->err = buf; else g_create_error = buf;
+    return st;
+}
+
+#define HIP_TRY(h, expr)                                                                         \
+    do { hipError_t e_ = (expr);                                                                 \
+         if (e_ != hipSuccess)                                                                   \
+             return fail(h, e_ == hipErrorOutOfMemory ? EAD_ERR_OOM : EAD_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+template <typename T>
+ead_status dmalloc(ead_handle *h, T **p, size_t n) {
+    void *v = nullptr;
+    hipError_t e = hipMalloc(&v, std::max<size_t>(n * sizeof(T), 256));
+    if (e != hipSuccess) return fail(h, EAD_ERR_OOM, "hipMalloc of %zu bytes failed: %s", n * sizeof(T), hipGetErrorString(e));
+    h->allocs.push_back(v);
+    *p = (T *)v;
+    return EAD_OK;
+}
+#define TRY(expr) do { ead_status s_ = (expr); if (s_ != EAD_OK) return s_; } while (0)
+
+ead_status check_model(const ead_model_desc *m, const char *name) {
+    if (!m) return fail(nullptr, EAD_ERR_INVALID_ARG, "%s model is null", name);
+    if (m->n_layers < 1 || m->d_model < 1 || m->n_heads < 1 || m->n_kv_heads < 1 || m->head_dim < 1 || m->d_ffn < 1 || m->vocab < 1)
+        return fail(nullptr, EAD_ERR_INVALID_ARG, "%s model: non-positive dimension", name);
+    if (m->dtype != EAD_F32 && m->dtype != EAD_BF16) return fail(nullptr, EAD_ERR_INVALID_ARG, "%s model: unknown dtype", name);
+    if (m->d_model % 32 || m->d_ffn % 32 || m->vocab % 16 || (m->n_heads * m->head_dim) % 32)
+        return fail(nullptr, EAD_ERR_SHAPE, "%s model: d_model, d_ffn, n_heads*head_dim must be multiples of 32 and vocab of 16", name);
+    if (m->head_dim != 32 && m->head_dim != 64 && m->head_dim != 128)
+        return fail(nullptr, EAD_ERR_SHAPE, "%s model: head_dim must be 32, 64 or 128", name);
+    if (m->n_heads % m->n_kv_heads) return fail(nullptr, EAD_ERR_SHAPE, "%s model: n_heads not a multiple of n_kv_heads", name);
+    const int G = m->n_heads / m->n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 5 && G != 7 && G != 8)
+        return fail(nullptr, EAD_ERR_SHAPE, "%s model: n_heads/n_kv_heads must be one of 1, 2, 4, 5, 7, 8", name);
+    if (m->dtype == EAD_F32 && (m->d_model > 4096 || m->d_ffn > 4096))
+        return fail(nullptr, EAD_ERR_SHAPE, "%s model: float32 weights are supported up to width 4096", name);
+    if (m->d_ffn > 15360 || m->d_model > 15360) return fail(nullptr, EAD_ERR_SHAPE, "%s model: width above 15360", name);
+    if (!m->embed || !m->wq || !m->wk || !m->wv || !m->wo || !m->w_gate || !m->w_up || !m->w_down || !m->norm_attn ||
+        !m->norm_ffn || !m->norm_final || !m->lm_head)
+        return fail(nullptr, EAD_ERR_INVALID_ARG, "%s model: null weight pointer", name);
+    for (int l = 0; l < m->n_layers; ++l)
+        if (!m->wq[l] || !m->wk[l] || !m->wv[l] || !m->wo[l] || !m->w_gate[l] || !m->w_up[l] || !m->w_down[l] ||
+            !m->norm_attn[l] || !m->norm_ffn[l])
+            return fail(nullptr, EAD_ERR_INVALID_ARG, "%s model: null weight pointer in layer %d", name, l);
+    return EAD_OK;
+}
+
+template <typename WT>
+ead_status pack_matrix(ead_handle *h, const void *s0, const void *s1, const void *s2, void **dst, int Np, int K,
+                       int mode, int hd, int NQ, int NK) {
+    WT *d = nullptr;
+    TRY(dmalloc(h, &d, (size_t)Np * K));
+    const size_t chunks = (size_t)Np * K / 8;
+    hipLaunchKernelGGL(k_pack_weights<WT>, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, h->stream,
+                       (const WT *)s0, (const WT *)s1, (const WT *)s2, d, Np, K, mode, hd, NQ, NK);
+    *dst = d;
+    return EAD_OK;
+}
+
+template <typename WT>
+ead_status build_model(ead_handle *h, const ead_model_desc *src, Model *m, int max_batch, int max_seq) {
+    m->L = src->n_layers; m->d = src->d_model; m->H = src->n_heads; m->KV = src->n_kv_heads; m->hd = src->head_dim;
+    m->F = src->d_ffn; m->V = src->vocab; m->dtype = src->dtype; m->eps = src->rms_eps; m->theta = src->rope_theta;
+    const int d = m->d, hd = m->hd, NQ = m->H * hd, NK = m->KV * hd;
+    WT *e = nullptr;
+    TRY(dmalloc(h, &e, (size_t)m->V * d));
+    HIP_TRY(h, hipMemcpyAsync(e, src->embed, (size_t)m->V * d * sizeof(WT), hipMemcpyDeviceToDevice, h->stream));
+    m->embed = e;
+    TRY(pack_matrix<WT>(h, src->lm_head, nullptr, nullptr, &m->lm_head, m->V, d, PACK_PLAIN, 0, 0, 0));
+    TRY(dmalloc(h, &m->g_final, (size_t)d));
+    HIP_TRY(h, hipMemcpyAsync(m->g_final, src->norm_final, d * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
+    m->layers.resize(m->L);
+    const size_t cache_elems = (size_t)max_batch * m->KV * max_seq * hd;
+    for (int l = 0; l < m->L; ++l) {
+        Layer &ly = m->layers[l];
+        TRY(pack_matrix<WT>(h, src->wq[l], src->wk[l], src->wv[l], &ly.wqkv, NQ + 2 * NK, d, PACK_QKV, hd, NQ, NK));
+        TRY(pack_matrix<WT>(h, src->wo[l], nullptr, nullptr, &ly.wo, d, NQ, PACK_PLAIN, 0, 0, 0));
+        TRY(pack_matrix<WT>(h, src->w_gate[l], src->w_up[l], nullptr, &ly.wgu, 2 * m->F, d, PACK_GATEUP, 0, 0, 0));
+        TRY(pack_matrix<WT>(h, src->w_down[l], nullptr, nullptr, &ly.wdown, d, m->F, PACK_PLAIN, 0, 0, 0));
+        TRY(dmalloc(h, &ly.g_attn, (size_t)d)); TRY(dmalloc(h, &ly.g_ffn, (size_t)d));
+        HIP_TRY(h, hipMemcpyAsync(ly.g_attn, src->norm_attn[l], d * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
+        HIP_TRY(h, hipMemcpyAsync(ly.g_ffn, src->norm_ffn[l], d * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
+        WT *kc = nullptr, *vc = nullptr;
+        TRY(dmalloc(h, &kc, cache_elems)); TRY(dmalloc(h, &vc, cache_elems));
+        ly.kcache = kc; ly.vcache = vc;
+    }
+    // rotary table in double precision: angle = pos * theta^(-2i/hd)
+    std::vector<float2> tab((size_t)max_seq * (hd / 2));
+    for (int i = 0; i < hd / 2; ++i) {
+        const double inv = pow((double)m->theta, -2.0 * (double)i / (double)hd);
+        for (int p = 0; p < max_seq; ++p) {
+            const double ang = (double)p * inv;
+            tab[(size_t)p * (hd / 2) + i] = make_float2((float)cos(ang), (float)sin(ang));
+        }
+    }
+    TRY(dmalloc(h, &m->rope, tab.size()));
+    HIP_TRY(h, hipMemcpyAsync(m->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));   // tab goes out of scope
+    const double per_layer = (double)d * (NQ + 2 * NK) + (double)NQ * d + 3.0 * (double)d * m->F;
+    m->n_params = m->L * (per_layer + 2.0 * d) + d + (double)m->V * d;
+    m->weight_bytes_nolm = (m->L * per_layer) * sizeof(WT) + (2.0 * m->L + 1) * d * 4.0;
+    m->lm_bytes = (double)m->V * d * sizeof(WT);
+    m->kv_bytes_per_pos = 2.0 * m->L * NK * sizeof(WT);
+    return EAD_OK;
+}
+
+// ======================================================================================
+// one forward pass of one model over the rows of the current plan
+// ======================================================================================
+template <typename WT, int EPI>
+void launch_valu(ead_handle *h, LinArgs<WT> &a, int T, int grid) {
+    const int KC = a.K / 32;
+    const size_t budget = 60 * 1024;
+    int TC = 4;
+    while (TC > 1 && ((size_t)TC * a.K * 4 + 8 * TC * 16 * 4 > budget || TC / 2 >= T)) TC >>= 1;
+    const bool wide = std::is_same<WT, bf16_t>::value && KC >= 64;
+    const int NW = wide ? 8 : 4;
+    const size_t lds = (size_t)TC * a.K * 4 + (size_t)NW * TC * 16 * 4;
+#define EAD_LV(TC_, NW_) hipLaunchKernelGGL((k_linear_valu<WT, TC_, NW_, EPI>), dim3(grid), dim3(NW_ * 64), lds, h->stream, a)
+    if constexpr (std::is_same<WT, bf16_t>::value) {
+        if (wide) { if (TC == 4) EAD_LV(4, 8); else if (TC == 2) EAD_LV(2, 8); else EAD_LV(1, 8); }
+        else { if (TC == 4) EAD_LV(4, 4); else if (TC == 2) EAD_LV(2, 4); else EAD_LV(1, 4); }
+    } else {
+        if (TC == 4) EAD_LV(4, 4); else if (TC == 2) EAD_LV(2, 4); else EAD_LV(1, 4);
+    }
+#undef EAD_LV
+}
+
+template <int EPI>
+void launch_mfma(ead_handle *h, LinArgs<bf16_t> &a, int grid) {
+    if (a.K / 32 >= 64) hipLaunchKernelGGL((k_linear_mfma<8, EPI>), dim3(grid), dim3(512), 0, h->stream, a);
+    else hipLaunchKernelGGL((k_linear_mfma<4, EPI>), dim3(grid), dim3(256), 0, h->stream, a);
+}
+
+template <typename KT, int HD>
+void launch_attn(ead_handle *h, AttnArgs<KT> &a, int G, int T) {
+    dim3 grid(a.max_splits, a.n_kv_heads, T);
+#define EAD_LA(G_) hipLaunchKernelGGL((k_attn_partial<KT, HD, G_>), grid, dim3(64), 0, h->stream, a)
+    switch (G) { case 1: EAD_LA(1); break; case 2: EAD_LA(2); break; case 4: EAD_LA(4); break;
+                 case 5: EAD_LA(5); break; case 7: EAD_LA(7); break; default: EAD_LA(8); break; }
+#undef EAD_LA
+    hipLaunchKernelGGL((k_attn_combine<KT, HD>), dim3(a.n_heads, T), dim3(HD), 0, h->stream, a);
+}
+
+// T, n_lm, ctx_max: the host's copy of what k_plan wrote to the device plan.
+template <typename WT>
+ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, bool dump_logits) {
+    Model &m = h->mdl[mi];
+    const int d = m.d, hd = m.hd, NQ = m.H * hd, NK = m.KV * hd, F = m.F;
+    constexpr bool is_bf16 = std::is_same<WT, bf16_t>::value;
+    const bool mfma = is_bf16 && T > 4;
+    hipStream_t st = h->stream;
+    const int *cnt = h->plan.hdr;
+    const int T16 = (T + 15) & ~15;
+
+    hipLaunchKernelGGL(k_embed<WT>, dim3(T), dim3(256), 0, st, (const WT *)m.embed, h->s.tokens, cnt, h->plan.row_seq,
+                       h->plan.row_pos, h->s.max_seq, d, h->x);
+    // attention split: enough waves to fill the chip, bounded scratch
+    int chunk = 32;
+    while ((long)ctx_max * T * m.KV / chunk > 4096 && chunk < 4096) chunk <<= 1;
+    while ((long)T * ((ctx_max + chunk - 1) / chunk) > h->items_max) chunk <<= 1;
+    const int max_splits = (ctx_max + chunk - 1) / chunk;
+
+    for (int l = 0; l < m.L; ++l) {
+        Layer &ly = m.layers[l];
+        // ---- RMSNorm + QKV + rotary + KV append ----
+        LinArgs<WT> a{};
+        a.W = (const WT *)ly.wqkv; a.Np = NQ + 2 * NK; a.K = d; a.count = cnt; a.out = h->q; a.ldo = NQ;
+        a.kcache = (WT *)ly.kcache; a.vcache = (WT *)ly.vcache; a.row_seq = h->plan.row_seq; a.row_pos = h->plan.row_pos;
+        a.rope = m.rope; a.n_heads = m.H; a.n_kv_heads = m.KV; a.hd = hd; a.max_seq = h->s.max_seq;
+        if (mfma) {
+            if constexpr (is_bf16) {
+                PackArgs pa{h->x, d, cnt, nullptr, ly.g_attn, m.eps, h->xp_a, d};
+                hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa);
+                a.xp = h->xp_a;
+                launch_mfma<EPI_QKV>(h, a, a.Np / 16);
+            }
+        } else {
+            a.x = h->x; a.ldx = d; a.gain = ly.g_attn; a.eps = m.eps;
+            launch_valu<WT, EPI_QKV>(h, a, T, a.Np / 16);
+        }
+        // ---- attention ----
+        AttnArgs<WT> at{};
+        at.q = h->q; at.kcache = (const WT *)ly.kcache; at.vcache = (const WT *)ly.vcache; at.count = cnt;
+        at.row_seq = h->plan.row_seq; at.row_pos = h->plan.row_pos; at.n_heads = m.H; at.n_kv_heads = m.KV;
+        at.max_seq = h->s.max_seq; at.chunk = chunk; at.max_splits = max_splits; at.scale = 1.0f / sqrtf((float)hd);
+        at.part_o = h->part_o; at.part_ml = h->part_ml;
+        if (mfma) at.out_tiles = h->xp_o; else at.out = h->o;
+        if (hd == 32) launch_attn<WT, 32>(h, at, m.H / m.KV, T);
+        else if (hd == 64) launch_attn<WT, 64>(h, at, m.H / m.KV, T);
+        else launch_attn<WT, 128>(h, at, m.H / m.KV, T);
+        // ---- output projection + residual ----
+        LinArgs<WT> b{};
+        b.W = (const WT *)ly.wo; b.Np = d; b.K = NQ; b.count = cnt; b.out = h->x; b.ldo = d;
+        if (mfma) { if constexpr (is_bf16) { b.xp = h->xp_o; launch_mfma<EPI_RES>(h, b, d / 16); } }
+        else { b.x = h->o; b.ldx = NQ; launch_valu<WT, EPI_RES>(h, b, T, d / 16); }
+        // ---- RMSNorm + gate/up + SwiGLU ----
+        LinArgs<WT> c{};
+        c.W = (const WT *)ly.wgu; c.Np = 2 * F; c.K = d; c.count = cnt; c.ldo = F;
+        if (mfma) {
+            if constexpr (is_bf16) {
+                PackArgs pa{h->x, d, cnt, nullptr, ly.g_ffn, m.eps, h->xp_a, d};
+                hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa);
+                c.xp = h->xp_a; c.out_tiles = h->xp_h; c.out_KC = F / 32;
+                launch_mfma<EPI_SWIGLU>(h, c, c.Np / 16);
+            }
+        } else {
+            c.x = h->x; c.ldx = d; c.gain = ly.g_ffn; c.eps = m.eps; c.out = h->hbuf;
+            launch_valu<WT, EPI_SWIGLU>(h, c, T, c.Np / 16);
+        }
+        // ---- down projection + residual ----
+        LinArgs<WT> e{};
+        e.W = (const WT *)ly.wdown; e.Np = d; e.K = F; e.count = cnt; e.out = h->x; e.ldo = d;
+        if (mfma) { if constexpr (is_bf16) { e.xp = h->xp_h; launch_mfma<EPI_RES>(h, e, d / 16); } }
+        else { e.x = h->hbuf; e.ldx = F; launch_valu<WT, EPI_RES>(h, e, T, d / 16); }
+    }
+    if (n_lm > 0) {
+        // ---- final RMSNorm + LM head with the entropy statistics folded in ----
+        LinArgs<WT> g{};
+        g.W = (const WT *)m.lm_head; g.Np = m.V; g.K = d; g.count = cnt + 1; g.rowmap = h->plan.lm_row;
+        g.partials = h->lm_part; g.logits = dump_logits ? h->logits_dump : nullptr;
+        const int grid = std::min(m.V / 16, h->lm_grid);
+        if (is_bf16 && n_lm > 4) {
+            if constexpr (is_bf16) {
+                PackArgs pa{h->x, d, cnt + 1, h->plan.lm_row, m.g_final, m.eps, h->xp_a, d};
+                hipLaunchKernelGGL(k_pack_act, dim3((n_lm + 15) & ~15), dim3(256), 0, st, pa);
+                g.xp = h->xp_a;
+                launch_mfma<EPI_LOGITS>(h, g, grid);
+            }
+        } else {
+            g.x = h->x; g.ldx = d; g.gain = m.g_final; g.eps = m.eps;
+            launch_valu<WT, EPI_LOGITS>(h, g, n_lm, grid);
+        }
+    }
+    HIP_TRY(h, hipGetLastError());
+    return EAD_OK;
+}
+
+ead_status run_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, bool dump) {
+    return h->mdl[mi].dtype == EAD_BF16 ? forward_pass<bf16_t>(h, mi, T, n_lm, ctx_max, dump)
+                                        : forward_pass<float>(h, mi, T, n_lm, ctx_max, dump);
+}
+
+// Host copy of k_plan: which rows the pass will hold.  Returns T; fills n_lm, ctx_max and,
+// per sequence, how many rows it got and whether its chunk reaches the end.
+int host_plan(ead_handle *h, int m, int budget, int limit_off, int lm_mode, bool ignore_model, int step, int *n_lm,
+              int *ctx_max, std::vector<int> *rows, std::vector<char> *complete) {
+    int off = 0, nlm = 0, cm = 0;
+    rows->assign(h->batch, 0); complete->assign(h->batch, 0);
+    for (int b = 0; b < h->batch; ++b) {
+        HostSeq &s = h->hs[b];
+        const bool active = !s.done && (ignore_model || s.model == m) && (step < 0 || s.last_step != step);
+        const int target = s.len - limit_off, have = s.kvlen[m];
+        int n = active ? std::max(0, target - have) : 0;
+        n = std::min(n, budget - off);
+        (*rows)[b] = n;
+        if (n > 0) {
+            cm = std::max(cm, have + n);
+            if (have + n == target) { (*complete)[b] = 1; if (lm_mode == 1) ++nlm; }
+        }
+        off += n;
+    }
+    *n_lm = lm_mode == 2 ? off : nlm;
+    *ctx_max = cm;
+    return off;
+}
+
+void launch_plan(ead_handle *h, int m, int budget, int limit_off, int lm_mode, bool ignore_model, int step) {
+    PlanArgs pa{h->s, h->plan, h->batch, m, budget, limit_off, lm_mode, ignore_model ? 1 : 0, step};
+    hipLaunchKernelGGL(k_plan, dim3(1), dim3(256), 3 * h->batch * sizeof(int), h->stream, pa);
+}
+
+void launch_finalize(ead_handle *h, int m, int n_lm, bool score) {
+    FinArgs fa{};
+    fa.s = h->s; fa.p = h->plan; fa.cfg = h->cfg; fa.partials = h->lm_part;
+    fa.n_part = std::min(h->mdl[m].V / 16, h->lm_grid); fa.unit = h->prm.unit;
+    fa.score_mode = score ? 1 : 0; fa.sc_H = h->sc_H; fa.sc_arg = h->sc_arg;
+    fa.model_id = m; fa.max_new = h->max_new; fa.eos_id = h->prm.eos_id; fa.replay = h->replay; fa.n_new = h->n_new;
+    fa.force_model = h->force_model; fa.step = h->step;
+    hipLaunchKernelGGL(k_lm_finalize, dim3(n_lm), dim3(64), 0, h->stream, fa);
+}
+
+void account_pass(ead_handle *h, int m, const std::vector<int> &rows, bool with_lm) {
+    Model &md = h->mdl[m];
+    double bytes = md.weight_bytes_nolm + (with_lm ? md.lm_bytes : 0.0);
+    for (int b = 0; b < h->batch; ++b) {
+        const int n = rows[b];
+        if (!n) continue;
+        const int have = h->hs[b].kvlen[m];
+        // row j reads have + j + 1 keys
+        bytes += md.kv_bytes_per_pos * ((double)n * have + (double)n * (n + 1) / 2.0);
+    }
+    h->stats.algorithmic_bytes += bytes;
+}
+
+ead_status validate_prompts(ead_handle *h, const int32_t *toks, const int32_t *lens, int batch, int max_new) {
+    if (!toks || !lens) return fail(h, EAD_ERR_INVALID_ARG, "null prompt pointer");
+    if (batch < 1 || max_new < 1) return fail(h, EAD_ERR_INVALID_ARG, "batch and max_new_tokens must be >= 1");
+    if (batch > h->prm.max_batch) return fail(h, EAD_ERR_SEQ_OVERFLOW, "batch %d exceeds max_batch %d", batch, h->prm.max_batch);
+    if (max_new > h->s.cap) return fail(h, EAD_ERR_SEQ_OVERFLOW, "max_new_tokens %d exceeds max_seq %d", max_new, h->s.cap);
+    size_t off = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (lens[b] < 1) return fail(h, EAD_ERR_INVALID_ARG, "prompt %d is empty", b);
+        if ((long)lens[b] + max_new > h->prm.max_seq)
+            return fail(h, EAD_ERR_SEQ_OVERFLOW, "prompt %d: %d + %d tokens exceed max_seq %d", b, lens[b], max_new, h->prm.max_seq);
+        for (int i = 0; i < lens[b]; ++i)
+            if (toks[off + i] < 0 || toks[off + i] >= h->mdl[0].V)
+                return fail(h, EAD_ERR_INVALID_ARG, "prompt %d token %d out of range", b, i);
+        off += lens[b];
+    }
+    return EAD_OK;
+}
+
+ead_status begin_impl(ead_handle *h, const int32_t *toks, const int32_t *lens, int batch, int max_new) {
+    TRY(validate_prompts(h, toks, lens, batch, max_new));
+    hipStream_t st = h->stream;
+    const int MB = h->s.max_batch, MS = h->s.max_seq;
+    h->batch = batch; h->max_new = max_new; h->began = 0; h->step = 0;
+    h->hs.assign(batch, HostSeq{});
+    std::vector<int> tok((size_t)batch * MS, 0), len(MB, 0), zeros(MB * 2, 0), model(MB, 0), neg(MB, -1);
+    size_t off = 0;
+    for (int b = 0; b < batch; ++b) {
+        memcpy(&tok[(size_t)b * MS], toks + off, sizeof(int) * lens[b]);
+        off += lens[b];
+        len[b] = lens[b];
+        HostSeq &s = h->hs[b];
+        s.len = lens[b]; s.kvlen[0] = s.kvlen[1] = 0; s.c = 0; s.ngen = 0; s.done = 0; s.last_step = -1;
+        s.model = h->force_model >= 0 ? h->force_model : (h->replay ? -1 : 0);
+        model[b] = std::max(s.model, 0);
+    }
+    HIP_TRY(h, hipMemcpyAsync(h->s.tokens, tok.data(), tok.size() * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.len, len.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.kvlen, zeros.data(), 2 * MB * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.model, model.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.c, zeros.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.ngen, zeros.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.done, zeros.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.last_step, neg.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.err, zeros.data(), sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipStreamSynchronize(st));
+    // both models consume every prompt token but the last
+    std::vector<int> rows; std::vector<char> complete;
+    for (int m = 0; m < 2; ++m) {
+        for (;;) {
+            int n_lm, ctx_max;
+            const int T = host_plan(h, m, h->Tmax, 1, 0, true, -1, &n_lm, &ctx_max, &rows, &complete);
+            if (T == 0) break;
+            launch_plan(h, m, h->Tmax, 1, 0, true, -1);
+            TRY(run_pass(h, m, T, 0, ctx_max, false));
+            for (int b = 0; b < batch; ++b) h->hs[b].kvlen[m] += rows[b];
+        }
+    }
+    HIP_TRY(h, hipStreamSynchronize(st));
+    memset(&h->stats, 0, sizeof h->stats);
+    h->began = 1;
+    return EAD_OK;
+}
+
+ead_status decode_impl(ead_handle *h, int n_steps) {
+    if (!h->began) return fail(h, EAD_ERR_STATE, "ead_decode before ead_begin");
+    hipStream_t st = h->stream;
+    std::vector<int> rows; std::vector<char> complete, emitted(h->batch);
+    for (int it = 0; it < n_steps; ++it) {
+        const int step = h->step;
+        std::fill(emitted.begin(), emitted.end(), 0);
+        bool any = false;
+        for (int m = 0; m < 2; ++m) {
+            for (;;) {
+                int n_lm, ctx_max;
+                const int T = host_plan(h, m, h->Tmax, 0, 1, false, step, &n_lm, &ctx_max, &rows, &complete);
+                if (T == 0) break;
+                any = true;
+                launch_plan(h, m, h->Tmax, 0, 1, false, step);
+                TRY(run_pass(h, m, T, n_lm, ctx_max, false));
+                if (n_lm > 0) launch_finalize(h, m, n_lm, false);
+                account_pass(h, m, rows, n_lm > 0);
+                if (n_lm > 0) (m ? h->stats.steps_large : h->stats.steps_small)++;
+                for (int b = 0; b < h->batch; ++b) {
+                    HostSeq &s = h->hs[b];
+                    if (!rows[b]) continue;
+                    const int extra = rows[b] - (complete[b] ? 1 : 0);
+                    (m ? h->stats.catchup_rows_large : h->stats.catchup_rows_small) += extra;
+                    s.kvlen[m] += rows[b];
+                    if (complete[b]) {
+                        emitted[b] = 1; s.last_step = step;
+                        (m ? h->stats.tokens_large : h->stats.tokens_small)++;
+                    }
+                }
+            }
+        }
+        if (!any) break;
+        // advance the host's copy of the per-sequence state
+        bool need_sync = h->prm.eos_id >= 0;
+        for (int b = 0; b < h->batch; ++b) {
+            if (!emitted[b]) continue;
+            HostSeq &s = h->hs[b];
+            s.len++; s.ngen++; s.c++;
+            if (s.ngen >= h->max_new) s.done = 1;
+            if (h->replay || h->force_model >= 0) continue;
+            if (s.c >= h->cfg.d_min && !s.done) need_sync = true;
+        }
+        if (h->replay) {
+            // the next model is dictated: read it from the host copy of the forced ids
+            for (int b = 0; b < h->batch; ++b) {
+                HostSeq &s = h->hs[b];
+                if (!emitted[b] || s.done) continue;
+                const int nxt = h->h_model[(size_t)b * h->s.cap + s.ngen];   // forced ids staged by ead_replay
+                if (nxt != s.model) { s.model = nxt; s.c = 0; h->stats.switches++; }
+            }
+        } else if (need_sync && h->force_model < 0) {
+            HIP_TRY(h, hipMemcpyAsync(h->h_model, h->s.model, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
+            HIP_TRY(h, hipMemcpyAsync(h->h_done, h->s.done, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
+            HIP_TRY(h, hipStreamSynchronize(st));
+            h->stats.host_syncs++;
+            for (int b = 0; b < h->batch; ++b) {
+                HostSeq &s = h->hs[b];
+                if (!emitted[b]) continue;
+                if (h->h_done[b]) s.done = 1;
+                if (h->h_model[b] != s.model) { s.model = h->h_model[b]; s.c = 0; h->stats.switches++; }
+            }
+        } else if (need_sync) {
+            HIP_TRY(h, hipMemcpyAsync(h->h_done, h->s.done, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
+            HIP_TRY(h, hipStreamSynchronize(st));
+            for (int b = 0; b < h->batch; ++b) if (h->h_done[b]) h->hs[b].done = 1;
+        }
+        h->step++;
+    }
+    HIP_TRY(h, hipStreamSynchronize(st));
+    int err = 0;
+    HIP_TRY(h, hipMemcpy(&err, h->s.err, sizeof(int), hipMemcpyDeviceToHost));
+    if (err) return fail(h, EAD_ERR_NONFINITE, "a non-finite entropy was produced (non-finite logits)");
+    return EAD_OK;
+}
+
+ead_status fetch_impl(ead_handle *h, int stride, int32_t *tok, uint8_t *mid, float *H, float *Hbar, uint8_t *dec,
+                      int32_t *lens) {
+    if (!h->began) return fail(h, EAD_ERR_STATE, "nothing to fetch: call ead_begin first");
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    const int cap = h->s.cap;
+    std::vector<int> ngen(h->batch);
+    HIP_TRY(h, hipMemcpy(ngen.data(), h->s.ngen, h->batch * sizeof(int), hipMemcpyDeviceToHost));
+    for (int b = 0; b < h->batch; ++b) {
+        const int n = ngen[b];
+        if (n > stride) return fail(h, EAD_ERR_INVALID_ARG, "stride %d smaller than %d generated tokens", stride, n);
+        if (lens) lens[b] = n;
+        if (!n) continue;
+        if (tok) HIP_TRY(h, hipMemcpy(tok + (size_t)b * stride, h->s.out_tok + (size_t)b * cap, n * sizeof(int), hipMemcpyDeviceToHost));
+        if (mid) HIP_TRY(h, hipMemcpy(mid + (size_t)b * stride, h->s.out_mid + (size_t)b * cap, n, hipMemcpyDeviceToHost));
+        if (H) HIP_TRY(h, hipMemcpy(H + (size_t)b * stride, h->s.out_H + (size_t)b * cap, n * sizeof(float), hipMemcpyDeviceToHost));
+        if (Hbar) HIP_TRY(h, hipMemcpy(Hbar + (size_t)b * stride, h->s.out_Hbar + (size_t)b * cap, n * sizeof(float), hipMemcpyDeviceToHost));
+        if (dec) HIP_TRY(h, hipMemcpy(dec + (size_t)b * stride, h->s.out_dec + (size_t)b * cap, n, hipMemcpyDeviceToHost));
+    }
+    return EAD_OK;
+}
+
+// ---- stand-alone entropy: per-device scratch for the partials -------------------------
+constexpr int kEntMaxRows = 4096, kEntMaxChunks = 64;
+EntPartial *g_ent_scratch[16] = {nullptr};
+
+template <typename T>
+void launch_entropy_partial(const void *logits, int rows, int V, EntPartial *part, int *n_chunks, hipStream_t st) {
+    const int nvec = V / 8;
+    int chunks = std::max(1, std::min(kEntMaxChunks, 2048 / std::max(rows, 1)));
+    chunks = std::min(chunks, std::max(1, nvec / 256));
+    int per = (std::max(nvec, 1) + chunks - 1) / chunks;
+    while (per > 8 * 256) { ++chunks; per = (nvec + chunks - 1) / chunks; }    // rows this long get more chunks
+    *n_chunks = chunks;
+    EntArgs<T> a{(const T *)logits, V, per, part};
+    dim3 grid(chunks, rows);
+    if (per <= 256) hipLaunchKernelGGL((k_entropy_partial<T, 1>), grid, dim3(256), 0, st, a);
+    else if (per <= 512) hipLaunchKernelGGL((k_entropy_partial<T, 2>), grid, dim3(256), 0, st, a);
+    else if (per <= 1024) hipLaunchKernelGGL((k_entropy_partial<T, 4>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((k_entropy_partial<T, 8>), grid, dim3(256), 0, st, a);
+}
+
+ead_status entropy_scratch(EntPartial **out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(nullptr, EAD_ERR_NO_DEVICE, "no HIP device");
+    if (dev < 0 || dev >= 16) return fail(nullptr, EAD_ERR_DEVICE, "device index %d out of range", dev);
+    if (!g_ent_scratch[dev]) {
+        void *p = nullptr;
+        // chunks can exceed kEntMaxChunks only for rows longer than 64*2048*8 elements
+        if (hipMalloc(&p, sizeof(EntPartial) * (size_t)kEntMaxRows * kEntMaxChunks * 4) != hipSuccess)
+            return fail(nullptr, EAD_ERR_OOM, "scratch allocation failed");
+        g_ent_scratch[dev] = (EntPartial *)p;
+    }
+    *out = g_ent_scratch[dev];
+    return EAD_OK;
+}
+
+ead_status entropy_partials(const void *logits, int dtype, int rows, int vocab, hipStream_t st, EntPartial **part,
+                            int *chunks) {
+    if (!logits) return fail(nullptr, EAD_ERR_INVALID_ARG, "null logits pointer");
+    if (rows < 1 || rows > kEntMaxRows) return fail(nullptr, EAD_ERR_INVALID_ARG, "rows must be in 1..%d", kEntMaxRows);
+    if (vocab < 1) return fail(nullptr, EAD_ERR_INVALID_ARG, "vocab must be >= 1");
+    if (dtype != EAD_F32 && dtype != EAD_BF16) return fail(nullptr, EAD_ERR_INVALID_ARG, "unknown dtype");
+    if (vocab % 8) return fail(nullptr, EAD_ERR_SHAPE, "vocab must be a multiple of 8");
+    if ((long)vocab > 64L * 2048 * 8 * 4) return fail(nullptr, EAD_ERR_SHAPE, "vocab too large");
+    TRY(entropy_scratch(part));
+    if (dtype == EAD_BF16) launch_entropy_partial<bf16_t>(logits, rows, vocab, *part, chunks, st);
+    else launch_entropy_partial<float>(logits, rows, vocab, *part, chunks, st);
+    return EAD_OK;
+}
+
+}  // namespace
+
+struct ead_gate {
+    GateState st; GateCfg cfg; int rows; hipStream_t stream;
+    std::vector<void *> allocs;
+};
+
+// ======================================================================================
+// C ABI
+// ======================================================================================
+extern "C" {
+
+int32_t ead_version(void) { return 100; }
+
+const char *ead_last_error(const ead_handle *h) { return h ? h->err.c_str() : g_create_error.c_str(); }
+
+void ead_destroy(ead_handle *h) {
+    if (!h) return;
+    (void)hipStreamSynchronize(h->stream);
+    for (void *p : h->allocs) (void)hipFree(p);
+    if (h->h_model) (void)hipHostFree(h->h_model);
+    if (h->h_done) (void)hipHostFree(h->h_done);
+    delete h;
+}
+
+ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *large_model, const ead_params *p,
+                      ead_handle **out) {
+    if (!out) return fail(nullptr, EAD_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (!p) return fail(nullptr, EAD_ERR_INVALID_ARG, "params is null");
+    TRY(check_model(small_model, "small"));
+    TRY(check_model(large_model, "large"));
+    if (small_model->vocab != large_model->vocab)
+        return fail(nullptr, EAD_ERR_VOCAB_MISMATCH, "vocab sizes differ: %d vs %d", small_model->vocab, large_model->vocab);
+    if (p->window < 1 || p->d_min < 1 || !(p->tau == p->tau) || p->max_batch < 1 || p->max_seq < 2 ||
+        (p->unit != EAD_NATS && p->unit != EAD_BITS))
+        return fail(nullptr, EAD_ERR_INVALID_ARG, "need window >= 1, d_min >= 1, tau not NaN, max_batch >= 1, max_seq >= 2, unit 0/1");
+    if (p->window > 4096) return fail(nullptr, EAD_ERR_INVALID_ARG, "window above 4096");
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(nullptr, EAD_ERR_NO_DEVICE, "no HIP device available");
+
+    ead_handle *h = new (std::nothrow) ead_handle();
+    if (!h) return fail(nullptr, EAD_ERR_OOM, "host allocation failed");
+    h->prm = *p; h->stream = (hipStream_t)p->hip_stream; h->force_model = -1;
+    h->cfg = GateCfg{p->window, p->tau, p->d_min};
+    ead_status rc = EAD_OK;
+    auto body = [&]() -> ead_status {
+        const int MB = p->max_batch, MS = p->max_seq;
+        TRY(small_model->dtype == EAD_BF16 ? build_model<bf16_t>(h, small_model, &h->mdl[0], MB, MS)
+                                           : build_model<float>(h, small_model, &h->mdl[0], MB, MS));
+        TRY(large_model->dtype == EAD_BF16 ? build_model<bf16_t>(h, large_model, &h->mdl[1], MB, MS)
+                                           : build_model<float>(h, large_model, &h->mdl[1], MB, MS));
+        const long total = (long)MB * MS;
+        h->Tmax = (int)std::min<long>(std::max<long>(MB, 1024), std::max<long>(total, MB));
+        h->Tmax = (h->Tmax + 15) & ~15;
+        h->items_max = std::max(h->Tmax, 2048);
+        h->lm_grid = 1024;
+        h->score_rows = 64;
+        SeqState &s = h->s;
+        s.max_batch = MB; s.max_seq = MS; s.cap = MS;
+        TRY(dmalloc(h, &s.tokens, (size_t)MB * MS)); TRY(dmalloc(h, &s.len, (size_t)MB)); TRY(dmalloc(h, &s.kvlen, (size_t)2 * MB));
+        TRY(dmalloc(h, &s.model, (size_t)MB)); TRY(dmalloc(h, &s.c, (size_t)MB)); TRY(dmalloc(h, &s.ngen, (size_t)MB));
+        TRY(dmalloc(h, &s.done, (size_t)MB)); TRY(dmalloc(h, &s.last_step, (size_t)MB));
+        TRY(dmalloc(h, &s.ring, (size_t)MB * 4096)); TRY(dmalloc(h, &s.err, (size_t)1));
+        TRY(dmalloc(h, &s.out_tok, (size_t)MB * MS)); TRY(dmalloc(h, &s.out_mid, (size_t)MB * MS));
+        TRY(dmalloc(h, &s.out_H, (size_t)MB * MS)); TRY(dmalloc(h, &s.out_Hbar, (size_t)MB * MS));
+        TRY(dmalloc(h, &s.out_dec, (size_t)MB * MS));
+        TRY(dmalloc(h, &s.forced_tok, (size_t)MB * MS)); TRY(dmalloc(h, &s.forced_mid, (size_t)MB * MS));
+        TRY(dmalloc(h, &h->plan.hdr, (size_t)4)); TRY(dmalloc(h, &h->plan.row_seq, (size_t)h->Tmax));
+        TRY(dmalloc(h, &h->plan.row_pos, (size_t)h->Tmax));
+        TRY(dmalloc(h, &h->plan.lm_row, (size_t)h->Tmax)); TRY(dmalloc(h, &h->plan.lm_seq, (size_t)h->Tmax));
+        const Model &a = h->mdl[0], &b = h->mdl[1];
+        const size_t dmax = std::max(a.d, b.d), qmax = std::max(a.H * a.hd, b.H * b.hd), fmax_ = std::max(a.F, b.F);
+        const size_t T = h->Tmax;
+        TRY(dmalloc(h, &h->x, T * dmax)); TRY(dmalloc(h, &h->q, T * qmax)); TRY(dmalloc(h, &h->o, T * qmax));
+        TRY(dmalloc(h, &h->hbuf, T * fmax_));
+        TRY(dmalloc(h, &h->xp_a, T * dmax)); TRY(dmalloc(h, &h->xp_o, T * qmax)); TRY(dmalloc(h, &h->xp_h, T * fmax_));
+        HIP_TRY(h, hipMemsetAsync(h->xp_a, 0, T * dmax * 2, h->stream));
+        HIP_TRY(h, hipMemsetAsync(h->xp_o, 0, T * qmax * 2, h->stream));
+        HIP_TRY(h, hipMemsetAsync(h->xp_h, 0, T * fmax_ * 2, h->stream));
+        TRY(dmalloc(h, &h->part_o, (size_t)h->items_max * qmax)); TRY(dmalloc(h, &h->part_ml, (size_t)h->items_max * std::max(a.H, b.H)));
+        TRY(dmalloc(h, &h->lm_part, (size_t)std::max<size_t>(MB, h->score_rows) * h->lm_grid));
+        TRY(dmalloc(h, &h->logits_dump, (size_t)h->score_rows * a.V));
+        TRY(dmalloc(h, &h->sc_H, (size_t)MS)); TRY(dmalloc(h, &h->sc_arg, (size_t)MS));
+        HIP_TRY(h, hipHostMalloc((void **)&h->h_model, std::max<size_t>((size_t)MB * MS, 64) * sizeof(int), hipHostMallocDefault));
+        HIP_TRY(h, hipHostMalloc((void **)&h->h_done, std::max<size_t>(MB, 64) * sizeof(int), hipHostMallocDefault));
+        HIP_TRY(h, hipStreamSynchronize(h->stream));
+        HIP_TRY(h, hipGetLastError());
+        return EAD_OK;
+    };
+    rc = body();
+    if (rc != EAD_OK) { g_create_error = h->err; ead_destroy(h); return rc; }
+    *out = h;
+    return EAD_OK;
+}
+
+ead_status ead_set_gate(ead_handle *h, int32_t window, float tau, int32_t d_min, int32_t unit, int32_t eos_id) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    if (window < 1 || window > 4096 || d_min < 1 || !(tau == tau) || (unit != EAD_NATS && unit != EAD_BITS))
+        return fail(h, EAD_ERR_INVALID_ARG, "need 1 <= window <= 4096, d_min >= 1, tau not NaN, unit 0/1");
+    h->prm.window = window; h->prm.tau = tau; h->prm.d_min = d_min; h->prm.unit = unit; h->prm.eos_id = eos_id;
+    h->cfg = GateCfg{window, tau, d_min};
+    h->began = 0;
+    return EAD_OK;
+}
+
+ead_status ead_force_model(ead_handle *h, int32_t which) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    if (which < -1 || which > 1) return fail(h, EAD_ERR_INVALID_ARG, "model must be -1, 0 or 1");
+    h->force_model = which; h->began = 0;
+    return EAD_OK;
+}
+
+ead_status ead_begin(ead_handle *h, const int32_t *prompt_tokens, const int32_t *prompt_lens, int32_t batch,
+                     int32_t max_new_tokens) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    h->replay = 0; h->n_new = 0;
+    return begin_impl(h, prompt_tokens, prompt_lens, batch, max_new_tokens);
+}
+
+ead_status ead_decode(ead_handle *h, int32_t n_steps) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    if (n_steps < 0) return fail(h, EAD_ERR_INVALID_ARG, "n_steps < 0");
+    return decode_impl(h, n_steps);
+}
+
+ead_status ead_fetch(ead_handle *h, int32_t stride, int32_t *out_tokens, uint8_t *out_model_id, float *out_entropy,
+                     float *out_window_mean, int32_t *out_lens) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    return fetch_impl(h, stride, out_tokens, out_model_id, out_entropy, out_window_mean, nullptr, out_lens);
+}
+
+ead_status ead_generate(ead_handle *h, const int32_t *prompt_tokens, const int32_t *prompt_lens, int32_t batch,
+                        int32_t max_new_tokens, int32_t *out_tokens, uint8_t *out_model_id, float *out_entropy,
+                        float *out_window_mean, int32_t *out_lens) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    if (!out_tokens || !out_model_id || !out_entropy || !out_lens) return fail(h, EAD_ERR_INVALID_ARG, "null output pointer");
+    TRY(ead_begin(h, prompt_tokens, prompt_lens, batch, max_new_tokens));
+    TRY(decode_impl(h, max_new_tokens));
+    return fetch_impl(h, max_new_tokens, out_tokens, out_model_id, out_entropy, out_window_mean, nullptr, out_lens);
+}
+
+ead_status ead_replay(ead_handle *h, const int32_t *prompt_tokens, const int32_t *prompt_lens, int32_t batch,
+                      int32_t n_new, const int32_t *forced_tokens, const uint8_t *forced_model_id, int32_t *out_argmax,
+                      float *out_entropy, float *out_window_mean, uint8_t *out_decision) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    if (!forced_tokens || !forced_model_id) return fail(h, EAD_ERR_INVALID_ARG, "null forced trajectory");
+    TRY(validate_prompts(h, prompt_tokens, prompt_lens, batch, n_new));
+    for (size_t i = 0; i < (size_t)batch * n_new; ++i) {
+        if (forced_model_id[i] > 1) return fail(h, EAD_ERR_INVALID_ARG, "forced_model_id must be 0 or 1");
+        if (forced_tokens[i] < 0 || forced_tokens[i] >= h->mdl[0].V) return fail(h, EAD_ERR_INVALID_ARG, "forced token out of range");
+    }
+    const int cap = h->s.cap;
+    // stage the forced trajectory with the device row stride; keep the ids on the host too
+    std::vector<int> ft((size_t)batch * cap, 0); std::vector<uint8_t> fm((size_t)batch * cap, 0);
+    for (int b = 0; b < batch; ++b)
+        for (int i = 0; i < n_new; ++i) {
+            ft[(size_t)b * cap + i] = forced_tokens[(size_t)b * n_new + i];
+            fm[(size_t)b * cap + i] = forced_model_id[(size_t)b * n_new + i];
+            h->h_model[(size_t)b * cap + i] = forced_model_id[(size_t)b * n_new + i];
+        }
+    HIP_TRY(h, hipMemcpyAsync(h->s.forced_tok, ft.data(), ft.size() * sizeof(int), hipMemcpyHostToDevice, h->stream));
+    HIP_TRY(h, hipMemcpyAsync(h->s.forced_mid, fm.data(), fm.size(), hipMemcpyHostToDevice, h->stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    const int saved_force = h->force_model;
+    h->force_model = -1; h->replay = 1; h->n_new = n_new;
+    ead_status rc = begin_impl(h, prompt_tokens, prompt_lens, batch, n_new);
+    if (rc == EAD_OK) {
+        // the first token's model is dictated as well
+        std::vector<int> model(h->s.max_batch, 0);
+        for (int b = 0; b < batch; ++b) { h->hs[b].model = forced_model_id[(size_t)b * n_new]; model[b] = h->hs[b].model; }
+        hipError_t e = hipMemcpy(h->s.model, model.data(), model.size() * sizeof(int), hipMemcpyHostToDevice);
+        if (e != hipSuccess) rc = fail(h, EAD_ERR_DEVICE, "hipMemcpy: %s", hipGetErrorString(e));
+    }
+    if (rc == EAD_OK) rc = decode_impl(h, n_new);
+    if (rc == EAD_OK) rc = fetch_impl(h, n_new, out_argmax, nullptr, out_entropy, out_window_mean, out_decision, nullptr);
+    h->replay = 0; h->force_model = saved_force; h->began = 0;
+    return rc;
+}
+
+ead_status ead_score(ead_handle *h, int32_t which, const int32_t *tokens, int32_t len, float *out_logits,
+                     float *out_entropy, int32_t *out_argmax) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    if (which != 0 && which != 1) return fail(h, EAD_ERR_INVALID_ARG, "model must be 0 or 1");
+    if (!tokens || len < 1) return fail(h, EAD_ERR_INVALID_ARG, "need tokens and len >= 1");
+    if (len > h->prm.max_seq) return fail(h, EAD_ERR_SEQ_OVERFLOW, "len %d exceeds max_seq %d", len, h->prm.max_seq);
+    Model &m = h->mdl[which];
+    for (int i = 0; i < len; ++i)
+        if (tokens[i] < 0 || tokens[i] >= m.V) return fail(h, EAD_ERR_INVALID_ARG, "token %d out of range", i);
+    hipStream_t st = h->stream;
+    h->began = 0; h->batch = 1; h->replay = 0;
+    h->hs.assign(1, HostSeq{});
+    HostSeq &s = h->hs[0];
+    s.len = len; s.model = which; s.last_step = -1;
+    const int zero = 0, one_len = len, neg = -1;
+    HIP_TRY(h, hipMemcpyAsync(h->s.tokens, tokens, len * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.len, &one_len, sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.kvlen + which * h->s.max_batch, &zero, sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.model, &which, sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.done, &zero, sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.last_step, &neg, sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipStreamSynchronize(st));
+    std::vector<int> rows; std::vector<char> complete;
+    for (;;) {
+        int n_lm, ctx_max;
+        const int first = s.kvlen[which];
+        const int T = host_plan(h, which, h->score_rows, 0, 2, false, -1, &n_lm, &ctx_max, &rows, &complete);
+        if (T == 0) break;
+        launch_plan(h, which, h->score_rows, 0, 2, false, -1);
+        TRY(run_pass(h, which, T, n_lm, ctx_max, out_logits != nullptr));
+        launch_finalize(h, which, n_lm, true);
+        s.kvlen[which] += T;
+        if (out_logits) {
+            HIP_TRY(h, hipMemcpyAsync(out_logits + (size_t)first * m.V, h->logits_dump, (size_t)T * m.V * sizeof(float),
+                                      hipMemcpyDeviceToHost, st));
+            HIP_TRY(h, hipStreamSynchronize(st));
+        }
+    }
+    HIP_TRY(h, hipStreamSynchronize(st));
+    if (out_entropy) HIP_TRY(h, hipMemcpy(out_entropy, h->sc_H, len * sizeof(float), hipMemcpyDeviceToHost));
+    if (out_argmax) HIP_TRY(h, hipMemcpy(out_argmax, h->sc_arg, len * sizeof(int), hipMemcpyDeviceToHost));
+    return EAD_OK;
+}
+
+ead_status ead_get_stats(ead_handle *h, ead_stats *out) {
+    if (!h || !out) return EAD_ERR_INVALID_ARG;
+    *out = h->stats;
+    const double n = (double)(h->stats.tokens_small + h->stats.tokens_large);
+    out->large_share = n > 0 ? h->stats.tokens_large / n : 0.0;
+    out->param_ratio = ((1.0 - out->large_share) * h->mdl[0].n_params + out->large_share * h->mdl[1].n_params) / h->mdl[1].n_params;
+    return EAD_OK;
+}
+
+ead_status ead_reset_stats(ead_handle *h) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    memset(&h->stats, 0, sizeof h->stats);
+    return EAD_OK;
+}
+
+// ---- entropy / gate on their own ---------------------------------------------------------
+ead_status ead_entropy_argmax(const void *logits_dev, int32_t dtype, int32_t rows, int32_t vocab, int32_t unit,
+                              float *H_dev, int32_t *argmax_dev, void *hip_stream) {
+    if (!H_dev) return fail(nullptr, EAD_ERR_INVALID_ARG, "H_dev is null");
+    if (unit != EAD_NATS && unit != EAD_BITS) return fail(nullptr, EAD_ERR_INVALID_ARG, "unit must be 0 or 1");
+    EntPartial *part = nullptr; int chunks = 0;
+    TRY(entropy_partials(logits_dev, dtype, rows, vocab, (hipStream_t)hip_stream, &part, &chunks));
+    hipLaunchKernelGGL(k_entropy_finalize, dim3(rows), dim3(64), 0, (hipStream_t)hip_stream, part, chunks, rows, unit,
+                       H_dev, argmax_dev);
+    if (hipGetLastError() != hipSuccess) return fail(nullptr, EAD_ERR_DEVICE, "kernel launch failed");
+    return EAD_OK;
+}
+
+ead_status ead_gate_create(int32_t rows, int32_t window, float tau, int32_t d_min, void *hip_stream, ead_gate **out) {
+    if (!out) return fail(nullptr, EAD_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (rows < 1 || rows > kEntMaxRows || window < 1 || window > 4096 || d_min < 1 || !(tau == tau))
+        return fail(nullptr, EAD_ERR_INVALID_ARG, "need 1 <= rows <= %d, 1 <= window <= 4096, d_min >= 1, tau not NaN", kEntMaxRows);
+    ead_gate *g = new (std::nothrow) ead_gate();
+    if (!g) return fail(nullptr, EAD_ERR_OOM, "host allocation failed");
+    g->rows = rows; g->cfg = GateCfg{window, tau, d_min}; g->stream = (hipStream_t)hip_stream;
+    void *p[4] = {nullptr, nullptr, nullptr, nullptr};
+    const size_t sz[4] = {(size_t)rows * window * 4, (size_t)rows * 4, (size_t)rows * 4, (size_t)rows * 4};
+    for (int i = 0; i < 4; ++i) {
+        if (hipMalloc(&p[i], sz[i]) != hipSuccess) { for (int j = 0; j < i; ++j) (void)hipFree(p[j]); delete g; return fail(nullptr, EAD_ERR_OOM, "hipMalloc failed"); }
+        g->allocs.push_back(p[i]);
+    }
+    g->st.ring = (float *)p[0]; g->st.n = (int *)p[1]; g->st.c = (int *)p[2]; g->st.model = (int *)p[3];
+    *out = g;
+    return ead_gate_reset(g);
+}
+
+ead_status ead_gate_reset(ead_gate *g) {
+    if (!g) return EAD_ERR_INVALID_ARG;
+    (void)hipMemsetAsync(g->st.ring, 0, (size_t)g->rows * g->cfg.w * 4, g->stream);
+    (void)hipMemsetAsync(g->st.n, 0, (size_t)g->rows * 4, g->stream);
+    (void)hipMemsetAsync(g->st.c, 0, (size_t)g->rows * 4, g->stream);
+    (void)hipMemsetAsync(g->st.model, 0, (size_t)g->rows * 4, g->stream);
+    return hipGetLastError() == hipSuccess ? EAD_OK : EAD_ERR_DEVICE;
+}
+
+void ead_gate_destroy(ead_gate *g) {
+    if (!g) return;
+    (void)hipStreamSynchronize(g->stream);
+    for (void *p : g->allocs) (void)hipFree(p);
+    delete g;
+}
+
+ead_status ead_gate_step(ead_gate *g, const float *H_dev, uint8_t *model_id_dev, float *window_mean_dev,
+                         uint8_t *next_model_dev) {
+    if (!g || !H_dev) return EAD_ERR_INVALID_ARG;
+    GateStepArgs a{};
+    a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.H = H_dev;
+    a.model_id_out = model_id_dev; a.Hbar_out = window_mean_dev; a.next_out = next_model_dev;
+    hipLaunchKernelGGL(k_gate_step, dim3(g->rows), dim3(64), 0, g->stream, a);
+    return hipGetLastError() == hipSuccess ? EAD_OK : EAD_ERR_DEVICE;
+}
+
+ead_status ead_gate_step_logits(ead_gate *g, const void *logits_dev, int32_t dtype, int32_t vocab, int32_t unit,
+                                float *H_dev, int32_t *argmax_dev, uint8_t *model_id_dev, float *window_mean_dev,
+                                uint8_t *next_model_dev) {
+    if (!g) return EAD_ERR_INVALID_ARG;
+    if (unit != EAD_NATS && unit != EAD_BITS) return fail(nullptr, EAD_ERR_INVALID_ARG, "unit must be 0 or 1");
+    EntPartial *part = nullptr; int chunks = 0;
+    TRY(entropy_partials(logits_dev, dtype, g->rows, vocab, g->stream, &part, &chunks));
+    GateStepArgs a{};
+    a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.partials = part; a.n_part = chunks; a.unit = unit;
+    a.H_out = H_dev; a.argmax_out = argmax_dev;
+    a.model_id_out = model_id_dev; a.Hbar_out = window_mean_dev; a.next_out = next_model_dev;
+    hipLaunchKernelGGL(k_gate_step, dim3(g->rows), dim3(64), 0, g->stream, a);
+    return hipGetLastError() == hipSuccess ? EAD_OK : EAD_ERR_DEVICE;
+}
+
+}  // extern "C"
