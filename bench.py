@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Throughput of entropy-adaptive decoding on one MI355X.
+
+A "step" is one iteration of Algorithm 1's loop for every sequence of the batch: the
+active model's forward pass over the KV cache (plus any catch-up it owes), the fused
+LM-head entropy / arg-max epilogue, the rolling window and the switch rule.  Prompt
+prefill is outside the timed region; all inputs are resident in HBM when timing starts.
+
+Prints ONE JSON line: tokens/s (whole job), the decode path's algorithmic HBM rate,
+the large-model token share, a roofline entry for the dominant kernel (HIP-event
+timing of its launches on the library's stream) and the CPU oracle's rate on a bounded
+sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import synth_inputs as si  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E peak
+
+WORKLOADS = {
+    # name: (pair, batch, prompt_lo, prompt_hi, default_steps, target_large_share, d_min)
+    "llama_1b_8b_b1": ("llama", 1, 512, 512, 1024, 0.40, 10),
+    "qwen_05b_14b_b32": ("qwen", 32, 256, 256, 256, 0.25, 10),
+    "qwen_05b_14b_b64": ("qwen", 64, 128, 1024, 128, 0.25, 10),
+    "tiny_fp32_b1": ("tiny", 1, 16, 16, 64, 0.40, 10),
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def make_prompts(seed, batch, lo, hi, vocab):
+    lens = si.prompt_lengths(seed, batch, lo, hi) if hi > lo else np.full(batch, lo, np.int32)
+    return [si.prompt_np(seed, f"row{b}", int(lens[b]), vocab) for b in range(batch)]
+
+
+def calibrate_tau(e, prompts, n_tokens, w, d_min, target):
+    """Bisection on free-running calibration runs: tau such that about `target` of the
+    tokens come from the large model (the percentile of the small model's windowed
+    entropy is only the starting bracket, because the window is shared across switches)."""
+    e.set_gate(w, 1e30, d_min)
+    probe = e.generate(prompts, n_tokens)
+    hb = probe["Hbar"].ravel()
+    lo, hi = float(hb.min()) - 1.0, float(hb.max()) + 1e-3
+    best = (2.0, hi)
+    for _ in range(12):
+        tau = 0.5 * (lo + hi)
+        e.set_gate(w, tau, d_min)
+        share = float(e.generate(prompts, n_tokens)["model_id"].mean())
+        if abs(share - target) < abs(best[0] - target):
+            best = (share, tau)
+        if share > target:
+            lo = tau            # too many large tokens: raise the threshold
+        else:
+            hi = tau
+        if abs(share - target) < 0.02:
+            break
+    return best[1], best[0]
+
+
+def cpu_baseline(pair_shapes, Ws, Wl, prompts, w, tau, d_min):
+    """The oracle as it stands, timed on this host: Algorithm 1 on a bounded sample (first
+    row, prompt cut to 16 tokens, 24 generated tokens); prompt handling is subtracted by
+    timing a 1-token run."""
+    import oracle
+    ss, sl = pair_shapes
+    t0 = time.time()
+    os_ = oracle.Model(ss, {k: v.float().cpu().numpy() for k, v in Ws.items()})
+    ol = oracle.Model(sl, {k: v.float().cpu().numpy() for k, v in Wl.items()})
+    log(f"[cpu_baseline] weights on host in {time.time() - t0:.1f}s")
+    prompt = prompts[0][:16]
+    n = 24
+    t0 = time.time(); oracle.generate(os_, ol, prompt, 1, w, tau, d_min); t1 = time.time()
+    out = oracle.generate(os_, ol, prompt, n + 1, w, tau, d_min); t2 = time.time()
+    dt = max((t2 - t1) - (t1 - t0), 1e-9)
+    return {"value": n / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"row 0, prompt cut to 16 tokens, {n} generated tokens after the first, batch 1, "
+                      f"same w/tau/d_min; large share in sample {float(out['model_id'][1:].mean()):.2f}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="llama_1b_8b_b1", choices=sorted(WORKLOADS))
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-single-model", action="store_true", help="skip the small-only / large-only runs")
+    ap.add_argument("--profile-steps", type=int, default=64)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (sequences are independent, so more GPUs "
+                 "would each run this same program on their share of the batch); use --gpus 1")
+
+    import torch
+    import paper_2502_06833_amd as ead
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    pair, batch, plo, phi, dsteps, target, d_min = WORKLOADS[args.workload]
+    steps = args.steps or dsteps
+    warmup = args.warmup
+    w = 5
+    ss, sl = si.PAIRS[pair]
+    t0 = time.time()
+    Ws = si.model_weights_torch(ss, args.seed, "cuda")
+    Wl = si.model_weights_torch(sl, args.seed, "cuda")
+    torch.cuda.synchronize()
+    log(f"[bench] weights generated in {time.time() - t0:.1f}s")
+    prompts = make_prompts(args.seed, batch, plo, phi, ss.vocab)
+    max_seq = max(len(p) for p in prompts) + warmup + steps + 8
+    e = ead.EAD(ss, Ws, sl, Wl, window=w, tau=0.0, d_min=d_min, max_batch=batch, max_seq=max_seq)
+    if args.no_cpu_baseline:
+        del Ws, Wl
+        torch.cuda.empty_cache()
+    log(f"[bench] handle created at {time.time() - t0:.1f}s")
+
+    n_cal = min(256, warmup + steps)
+    tau, share_cal = calibrate_tau(e, prompts, n_cal, w, d_min, target)
+    log(f"[bench] tau={tau:.6f} nats -> large share {share_cal:.3f} over {n_cal} calibration tokens "
+        f"at {time.time() - t0:.1f}s")
+
+    def timed(force):
+        e.force_model(force)
+        e.set_gate(w, tau, d_min)
+        e.begin(prompts, warmup + steps)
+        e.decode(warmup)
+        e.reset_stats()
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        e.decode(steps)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - a
+        st = e.stats()
+        e.force_model(-1)
+        return dt, st
+
+    dt, st = timed(-1)
+    n_tok = st["tokens_small"] + st["tokens_large"]
+    tok_s = n_tok / dt
+    algo_gbs = st["algorithmic_bytes"] / dt / 1e9
+    log(f"[bench] EAD: {tok_s:.1f} tok/s, {algo_gbs:.0f} GB/s algorithmic ({algo_gbs / HBM_PEAK_GBS:.1%} of peak), "
+        f"large share {st['large_share']:.3f}, switches {st['switches']}, host syncs {st['host_syncs']}")
+    extra = {}
+    if not args.no_single_model:
+        for name, which in (("small_only", 0), ("large_only", 1)):
+            d2, s2 = timed(which)
+            n2 = s2["tokens_small"] + s2["tokens_large"]
+            extra[name] = {"tokens_per_s": n2 / d2, "hbm_frac": s2["algorithmic_bytes"] / d2 / 1e9 / HBM_PEAK_GBS}
+            log(f"[bench] {name}: {n2 / d2:.1f} tok/s, {extra[name]['hbm_frac']:.1%} of HBM peak")
+
+    # ---- per-kernel HIP-event timing on a separate, untimed run ----
+    e.set_gate(w, tau, d_min)
+    e.begin(prompts, warmup + args.profile_steps)
+    e.decode(warmup)
+    e.profile(True)
+    e.decode(args.profile_steps)
+    prof = e.profile_read()
+    e.profile(False)
+    by_kind = {}
+    for r in prof:
+        k = r["name"].split("/")[0]
+        a = by_kind.setdefault(k, {"launches": 0, "total_ms": 0.0, "bytes": 0.0})
+        a["launches"] += r["launches"]; a["total_ms"] += r["total_ms"]; a["bytes"] += r["bytes"]
+    for r in sorted(prof, key=lambda r: -r["total_ms"]):
+        gbs = r["bytes"] / max(r["total_ms"], 1e-9) / 1e6
+        log(f"[prof] {r['name']:<28s} n={r['launches']:<6d} avg {1e3 * r['total_ms'] / r['launches']:8.2f} us  "
+            f"{gbs:8.0f} GB/s")
+    dom = max(by_kind, key=lambda k: by_kind[k]["total_ms"])
+    d = by_kind[dom]
+    achieved = d["bytes"] / d["total_ms"] / 1e6
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "avg_launch_us": 1e3 * d["total_ms"] / d["launches"],
+                "bytes_per_launch": d["bytes"] / d["launches"], "launches": d["launches"]}
+
+    out = {
+        "metric": "generated tokens/s at 1 GPU", "value": tok_s, "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": 1e3 * dt / steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if ss.bf16 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "small": ss.name, "large": sl.name, "batch": batch,
+                   "prompt_len": [int(plo), int(phi)], "window": w, "d_min": d_min, "tau_nats": tau,
+                   "vocab": ss.vocab},
+        "decode_hbm_gbs": algo_gbs, "decode_hbm_frac_of_peak": algo_gbs / HBM_PEAK_GBS,
+        "large_token_share": st["large_share"], "param_ratio": st["param_ratio"], "switches": st["switches"],
+        "host_syncs": st["host_syncs"], **extra, "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline((ss, sl), Ws, Wl, prompts, w, tau, d_min)
+    e.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -205,6 +205,27 @@ ead_status ead_reset_stats(ead_handle *h);
 /* Run only one model for every row (0 / 1), or follow the gate (-1, the default).
  * Used to time small-only and large-only decoding on the same prompts. */
 ead_status ead_force_model(ead_handle *h, int32_t which_model_or_minus1);
+/* Single-row decode steps can run as ONE persistent kernel per step (grid barriers
+ * instead of kernel boundaries, weight prefetch across them) instead of the per-layer
+ * kernels that wider batches use.  Off by default; on = 1 selects it for the shapes it
+ * is built for (the per-layer kernels are used regardless for any other shape).  Both
+ * paths compute the same thing; tests compare them. */
+ead_status ead_set_fused(ead_handle *h, int32_t on);
+
+/* Per-kernel timing for roofline reports.  While enabled, every kernel launch of the
+ * decode path is bracketed by HIP events on the handle's stream (this slows decoding
+ * down: use it on a separate, untimed run).  ead_profile_read() waits for the stream,
+ * then returns one entry per kernel kind and model with the summed event time and the
+ * algorithmic bytes of those launches (weight bytes of the matrix for linear layers,
+ * K/V bytes read for attention, 0 for bookkeeping kernels). */
+typedef struct {
+    char name[48];          /* e.g. "linear_fma_swiglu/large" */
+    int64_t launches;
+    double total_ms;
+    double bytes;
+} ead_kernel_profile;
+ead_status ead_profile_enable(ead_handle *h, int32_t on);   /* also clears what was collected */
+ead_status ead_profile_read(ead_handle *h, ead_kernel_profile *out, int32_t capacity, int32_t *n_out);
 /* Library version as major*10000 + minor*100 + patch. */
 int32_t ead_version(void);
 

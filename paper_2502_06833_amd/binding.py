@@ -7,7 +7,7 @@ import os
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libead.so")
+LIB_PATH = os.environ.get("EAD_LIBRARY") or os.path.join(HERE, "libead.so")
 
 NATS, BITS = 0, 1
 SMALL, LARGE = 0, 1
@@ -50,6 +50,10 @@ class Stats(C.Structure):
                 ("large_share", C.c_double), ("param_ratio", C.c_double)]
 
 
+class KernelProfile(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("total_ms", C.c_double), ("bytes", C.c_double)]
+
+
 _I32P, _U8P, _F32P = C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.POINTER(C.c_float)
 
 # name -> (restype, argtypes); also the list of symbols include/ead.h declares
@@ -75,6 +79,9 @@ _SIGNATURES = {
     "ead_get_stats": (C.c_int, [C.c_void_p, C.POINTER(Stats)]),
     "ead_reset_stats": (C.c_int, [C.c_void_p]),
     "ead_force_model": (C.c_int, [C.c_void_p, C.c_int32]),
+    "ead_set_fused": (C.c_int, [C.c_void_p, C.c_int32]),
+    "ead_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),
+    "ead_profile_read": (C.c_int, [C.c_void_p, C.POINTER(KernelProfile), C.c_int32, _I32P]),
 }
 
 
@@ -240,6 +247,19 @@ class EAD:
         s = Stats()
         self._check(lib().ead_get_stats(self._h, C.byref(s)))
         return {k: getattr(s, k) for k, _ in Stats._fields_}
+
+    def set_fused(self, on: bool):
+        self._check(lib().ead_set_fused(self._h, 1 if on else 0))
+
+    def profile(self, on: bool):
+        self._check(lib().ead_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self) -> list:
+        arr = (KernelProfile * 64)()
+        n = C.c_int32(0)
+        self._check(lib().ead_profile_read(self._h, arr, 64, C.byref(n)))
+        return [{"name": arr[i].name.decode(), "launches": arr[i].launches, "total_ms": arr[i].total_ms,
+                 "bytes": arr[i].bytes} for i in range(n.value)]
 
     def reset_stats(self):
         self._check(lib().ead_reset_stats(self._h))

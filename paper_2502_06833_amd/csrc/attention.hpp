@@ -4,7 +4,7 @@
 // once and serves all G = n_heads / n_kv_heads query heads that share the KV head.
 // hd/8 lanes cover one key (8 elements = one 16-byte load each for bf16), so a wave
 // works on 64/(hd/8) keys per iteration, each lane group keeping its own online
-// soft-max state; groups are merged at the end.  Key ranges (splits) are merged by
+// soft-max state; groups are merged at the end, and key ranges (splits) are merged by
 // k_attn_combine.  Causality comes from the cache itself: row t reads keys 0..pos_t.
 #pragma once
 #include "common.hpp"
@@ -28,10 +28,26 @@ struct AttnArgs {
 
 constexpr float kNegBig = -1e30f;
 
+template <int HD>
+__device__ __forceinline__ void attn_store(float *out, bf16_t *out_tiles, int t, int H,
+                                           int col, float r) {
+    if (out) out[(size_t)t * H * HD + col] = r;
+    if (out_tiles) {
+        const int KC = (H * HD) >> 5;
+        const size_t off = tile_offset(t >> 4, col >> 5, KC) + (size_t)(((t & 15) + 16 * ((col & 31) >> 3)) * 8 + (col & 7));
+        out_tiles[off].u = f32_to_bf16(r);
+    }
+}
+
+// Keys are taken in chunks of NI * (64 / LPK): all K and V loads of a chunk are issued
+// before any arithmetic, scores of the chunk are formed, one rescale is applied per chunk
+// and then the values are accumulated.  A row whose whole context fits one split is
+// finished here; otherwise k_attn_combine merges the splits.
 template <typename KT, int HD, int G>
-__global__ __launch_bounds__(64) void k_attn_partial(AttnArgs<KT> a) {
+__global__ __launch_bounds__(64) void k_attn(AttnArgs<KT> a) {
     constexpr int LPK = HD / 8;        // lanes per key
-    constexpr int KPI = 64 / LPK;      // keys per iteration
+    constexpr int KPI = 64 / LPK;      // keys per load instruction
+    constexpr int NI = 8;              // load instructions per chunk
     const int t = blockIdx.z;
     if (t >= *a.count) return;
     const int kvh = blockIdx.y, split = blockIdx.x;
@@ -39,6 +55,7 @@ __global__ __launch_bounds__(64) void k_attn_partial(AttnArgs<KT> a) {
     const int k0 = split * a.chunk;
     if (k0 >= nkeys) return;
     const int k1 = min(k0 + a.chunk, nkeys);
+    const int nsplit = (nkeys + a.chunk - 1) / a.chunk;
     const int lane = threadIdx.x, slot = lane / LPK, dl = lane % LPK;
     const int H = a.n_heads;
 
@@ -60,29 +77,56 @@ __global__ __launch_bounds__(64) void k_attn_partial(AttnArgs<KT> a) {
     const size_t base = ((size_t)a.row_seq[t] * a.n_kv_heads + kvh) * (size_t)a.max_seq * HD;
     const KT *kb = a.kcache + base + dl * 8, *vb = a.vcache + base + dl * 8;
 
-    for (int kk0 = k0; kk0 < k1; kk0 += KPI) {
-        const int kk = kk0 + slot;
-        const bool valid = kk < k1;
-        Vec8<KT> kx, vx;
-        if (valid) { kx.load(kb + (size_t)kk * HD); vx.load(vb + (size_t)kk * HD); }
-        else { kx.zero(); vx.zero(); }
-        float kf[8], vf[8];
-        kx.unpack(kf); vx.unpack(vf);
+    for (int c0 = k0; c0 < k1; c0 += NI * KPI) {
+        Vec8<KT> kx[NI], vx[NI];
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int kk = c0 + i * KPI + slot;
+            if (kk < k1) { kx[i].load(kb + (size_t)kk * HD); vx[i].load(vb + (size_t)kk * HD); }
+            else { kx[i].zero(); vx[i].zero(); }
+        }
+        float s[NI][G];
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            float kf[8];
+            kx[i].unpack(kf);
+            const bool valid = c0 + i * KPI + slot < k1;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float d = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d += qv[g][e] * kf[e];
+#pragma unroll
+                for (int off = 1; off < LPK; off <<= 1) d += __shfl_xor(d, off, kWave);
+                s[i][g] = valid ? d : kNegBig;
+            }
+        }
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            float s = 0.f;
+            float mc = s[0][g];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s += qv[g][e] * kf[e];
-#pragma unroll
-            for (int off = 1; off < LPK; off <<= 1) s += __shfl_xor(s, off, kWave);
-            if (!valid) s = kNegBig;
-            const float mn = fmaxf(m[g], s);
+            for (int i = 1; i < NI; ++i) mc = fmaxf(mc, s[i][g]);
+            const float mn = fmaxf(m[g], mc);
             const float corr = __expf(m[g] - mn);
-            const float p = valid ? __expf(s - mn) : 0.f;
-            l[g] = l[g] * corr + p;
+            l[g] *= corr;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[g][e] = o[g][e] * corr + p * vf[e];
+            for (int e = 0; e < 8; ++e) o[g][e] *= corr;
             m[g] = mn;
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const bool valid = c0 + i * KPI + slot < k1;
+                const float p = valid ? __expf(s[i][g] - mn) : 0.f;
+                l[g] += p; s[i][g] = p;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            float vf[8];
+            vx[i].unpack(vf);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[g][e] += s[i][g] * vf[e];
         }
     }
     // merge the key slots of the wave
@@ -102,6 +146,17 @@ __global__ __launch_bounds__(64) void k_attn_partial(AttnArgs<KT> a) {
             m[g] = M;
         }
     }
+    if (nsplit == 1) {                     // whole context in one split: finish here
+        if (slot == 0) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float r = 1.f / l[g];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) attn_store<HD>(a.out, a.out_tiles, t, H, (kvh * G + g) * HD + dl * 8 + e, o[g][e] * r);
+            }
+        }
+        return;
+    }
     if (slot == 0) {
 #pragma unroll
         for (int g = 0; g < G; ++g) {
@@ -114,13 +169,15 @@ __global__ __launch_bounds__(64) void k_attn_partial(AttnArgs<KT> a) {
     }
 }
 
-// One workgroup of HD threads per (head, token row): merge the splits.
+// One workgroup of HD threads per (head, token row): merge the splits (rows whose context
+// fits one split were finished by k_attn itself).
 template <typename KT, int HD>
 __global__ __launch_bounds__(HD) void k_attn_combine(AttnArgs<KT> a) {
     const int t = blockIdx.y;
     if (t >= *a.count) return;
     const int h = blockIdx.x, d = threadIdx.x, H = a.n_heads;
     const int nsplit = (a.row_pos[t] + a.chunk) / a.chunk;       // ceil((pos+1)/chunk)
+    if (nsplit == 1) return;
     const size_t item0 = ((size_t)t * H + h) * a.max_splits;
     float M = kNegBig;
     for (int s = 0; s < nsplit; ++s) M = fmaxf(M, a.part_ml[item0 + s].x);
@@ -131,14 +188,7 @@ __global__ __launch_bounds__(HD) void k_attn_combine(AttnArgs<KT> a) {
         L += ml.y * c;
         acc += a.part_o[(item0 + s) * HD + d] * c;
     }
-    const float r = acc / L;
-    const int col = h * HD + d;
-    if (a.out) a.out[(size_t)t * H * HD + col] = r;
-    if (a.out_tiles) {
-        const int KC = (H * HD) >> 5;
-        const size_t off = tile_offset(t >> 4, col >> 5, KC) + (size_t)(((t & 15) + 16 * ((col & 31) >> 3)) * 8 + (col & 7));
-        a.out_tiles[off].u = f32_to_bf16(r);
-    }
+    attn_store<HD>(a.out, a.out_tiles, t, H, h * HD + d, acc / L);
 }
 
 }  // namespace ead

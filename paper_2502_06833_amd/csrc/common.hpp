@@ -31,14 +31,16 @@ template <typename T> __device__ __forceinline__ T from_f32(float f);
 template <> __device__ __forceinline__ float from_f32<float>(float f) { return f; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) { bf16_t r; r.u = f32_to_bf16(f); return r; }
 
+template <typename V> using gptr = const V __attribute__((address_space(1))) *;
+
 // Eight consecutive elements of type T held by one lane.
 template <typename T> struct Vec8;
 template <> struct Vec8<bf16_t> {
     u32x4_t raw;
-    __device__ __forceinline__ void load(const bf16_t *p) { raw = *reinterpret_cast<const u32x4_t *>(p); }
-    __device__ __forceinline__ void load_stream(const bf16_t *p) {
-        raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
-    }
+    // all sources are device-global memory: say so, or pointers that went through LDS or
+    // a struct become flat loads
+    __device__ __forceinline__ void load(const bf16_t *p) { raw = *(gptr<u32x4_t>)p; }
+    __device__ __forceinline__ void load_stream(const bf16_t *p) { raw = __builtin_nontemporal_load((gptr<u32x4_t>)p); }
     __device__ __forceinline__ void unpack(float (&f)[8]) const {
         f[0] = __uint_as_float(raw.x << 16); f[1] = __uint_as_float(raw.x & 0xFFFF0000u);
         f[2] = __uint_as_float(raw.y << 16); f[3] = __uint_as_float(raw.y & 0xFFFF0000u);
@@ -49,12 +51,10 @@ template <> struct Vec8<bf16_t> {
 };
 template <> struct Vec8<float> {
     f32x4e_t lo, hi;
-    __device__ __forceinline__ void load(const float *p) {
-        lo = *reinterpret_cast<const f32x4e_t *>(p); hi = *reinterpret_cast<const f32x4e_t *>(p + 4);
-    }
+    __device__ __forceinline__ void load(const float *p) { lo = *(gptr<f32x4e_t>)p; hi = *(gptr<f32x4e_t>)(p + 4); }
     __device__ __forceinline__ void load_stream(const float *p) {
-        lo = __builtin_nontemporal_load(reinterpret_cast<const f32x4e_t *>(p));
-        hi = __builtin_nontemporal_load(reinterpret_cast<const f32x4e_t *>(p + 4));
+        lo = __builtin_nontemporal_load((gptr<f32x4e_t>)p);
+        hi = __builtin_nontemporal_load((gptr<f32x4e_t>)(p + 4));
     }
     __device__ __forceinline__ void unpack(float (&f)[8]) const {
         f[0] = lo.x; f[1] = lo.y; f[2] = lo.z; f[3] = lo.w; f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
@@ -75,6 +75,28 @@ template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t *p, const floa
     r.w = (uint32_t)f32_to_bf16(f[6]) | ((uint32_t)f32_to_bf16(f[7]) << 16);
     *reinterpret_cast<uint4 *>(p) = r;
 }
+
+// ---- device-coherent scalar accesses -----------------------------------------------------
+// Relaxed agent-scope atomics: the store is written through to memory and the load is
+// served coherently across the chip's L2 slices, so data handed between workgroups inside
+// one kernel needs no cache write-back / invalidate, only completion of the stores
+// (wait_stores) before the hand-over is signalled.
+__device__ __forceinline__ float ld_coherent(const float *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int ld_coherent(const int *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coherent(float *p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coherent(int *p, int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coherent(bf16_t *p, bf16_t v) {
+    __hip_atomic_store(&p->u, v.u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // ---- wave64 reductions -------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {

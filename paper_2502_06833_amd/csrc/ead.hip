@@ -20,6 +20,8 @@
 #include "common.hpp"
 #include "entropy.hpp"
 #include "linear.hpp"
+#include "state.hpp"
+#include "fused.hpp"
 
 using namespace ead;
 
@@ -66,21 +68,6 @@ __global__ __launch_bounds__(256) void k_copy(const WT *src, WT *dst, size_t n) 
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n) dst[i] = src[i];
 }
-
-// Per-sequence decoding state, all device arrays indexed by sequence.
-struct SeqState {
-    int *tokens;            // [max_batch][max_seq] prompt + generated
-    int *len;               // tokens present
-    int *kvlen;             // [2][max_batch] positions each model has consumed
-    int *model, *c, *ngen, *done, *last_step;
-    float *ring;            // [max_batch][w_cap]
-    int *out_tok; uint8_t *out_mid; float *out_H; float *out_Hbar; uint8_t *out_dec;   // [max_batch][cap]
-    int *forced_tok; uint8_t *forced_mid;                                              // replay, [max_batch][cap]
-    int *err;
-    int max_batch, max_seq, cap;
-};
-
-struct Plan { int *hdr; int *row_seq, *row_pos, *lm_row, *lm_seq; };
 
 struct PlanArgs {
     SeqState s; Plan p;
@@ -134,50 +121,6 @@ __global__ __launch_bounds__(256) void k_embed(const WT *embed, const int *token
     }
 }
 
-struct FinArgs {
-    SeqState s; Plan p; GateCfg cfg;
-    const EntPartial *partials; int n_part; int unit;
-    int score_mode; float *sc_H; int *sc_arg;      // score: indexed by position
-    int model_id, max_new, eos_id, replay, n_new, force_model, step;
-};
-
-// One wave per sequence that gets logits this pass: finish entropy and arg max from the
-// LM-head partials, then run Algorithm 1's bookkeeping for that sequence: record the
-// token, its model and entropy, push the window, apply the switch rule, append the token.
-__global__ __launch_bounds__(64) void k_lm_finalize(FinArgs a) {
-    const int i = blockIdx.x;
-    if (i >= a.p.hdr[1]) return;
-    const EntStat st = merge_partials(a.partials + (size_t)i * a.n_part, a.n_part);
-    const float H = entropy_from(st, a.unit);
-    if (threadIdx.x != 0) return;
-    const int b = a.p.lm_seq[i];
-    if (a.score_mode) {
-        const int pos = a.p.row_pos[a.p.lm_row[i]];
-        a.sc_H[pos] = H; a.sc_arg[pos] = st.idx;
-        return;
-    }
-    const int n = a.s.ngen[b], cur = a.model_id;
-    int next = cur, c = a.s.c[b];
-    const float hb = gate_update(a.s.ring + (size_t)b * a.cfg.w, n, H, a.cfg, &next, &c);
-    const size_t o = (size_t)b * a.s.cap + n;
-    a.s.out_tok[o] = st.idx; a.s.out_mid[o] = (uint8_t)cur; a.s.out_H[o] = H; a.s.out_Hbar[o] = hb;
-    a.s.out_dec[o] = (uint8_t)next;
-    int tok = st.idx;
-    if (a.replay) {
-        tok = a.s.forced_tok[o];
-        const int nxt = (n + 1 < a.n_new) ? a.s.forced_mid[o + 1] : cur;
-        if (nxt != cur) c = 0;
-        next = nxt;
-    }
-    if (a.force_model >= 0) next = a.force_model;
-    const int L = a.s.len[b];
-    a.s.tokens[(size_t)b * a.s.max_seq + L] = tok;
-    a.s.len[b] = L + 1; a.s.ngen[b] = n + 1;
-    a.s.done[b] = (n + 1 >= a.max_new) || (a.eos_id >= 0 && tok == a.eos_id);
-    a.s.model[b] = next; a.s.c[b] = c; a.s.last_step[b] = a.step;
-    if (!isfinite(H)) atomicOr(a.s.err, 1);
-}
-
 // entropy-only finalisation for ead_entropy_argmax
 __global__ __launch_bounds__(64) void k_entropy_finalize(const EntPartial *partials, int n_part, int rows, int unit,
                                                          float *H, int *argmax) {
@@ -198,6 +141,7 @@ struct Model {
     void *embed, *lm_head; float *g_final; float2 *rope;
     std::vector<Layer> layers;
     double weight_bytes_nolm, lm_bytes, kv_bytes_per_pos, n_params;
+    void *fused_mats = nullptr, *fused_layers = nullptr; int n_mats = 0; bool fused_ok = false;
     size_t esz() const { return dtype == EAD_BF16 ? 2 : 4; }
 };
 
@@ -215,11 +159,21 @@ struct ead_handle {
     float *x, *q, *o, *hbuf; bf16_t *xp_a, *xp_o, *xp_h;
     float *part_o; float2 *part_ml; EntPartial *lm_part; float *logits_dump; float *sc_H; int *sc_arg;
     int *h_model, *h_done;   // pinned
+    // fused single-row decode
+    long long *trace = nullptr;
+    float *att_o; float2 *att_ml; unsigned *bar_mem; int *abort_flag; unsigned bar_epoch = 0; int fused_on = 0, fused_grid = 0;
     std::vector<void *> allocs;
     std::vector<HostSeq> hs;
     int batch, max_new, began, replay, n_new, force_model, step;
     ead_stats stats;
     std::string err;
+    // optional per-kernel event timing
+    int prof_on = 0;
+    struct ProfRec { int cls; hipEvent_t a, b; double bytes; };
+    std::vector<ProfRec> prof_recs;
+    std::vector<hipEvent_t> ev_pool;
+    double prof_ms[64] = {0}, prof_bytes[64] = {0};
+    int64_t prof_n[64] = {0};
 };
 
 namespace {
@@ -229,6 +183,39 @@ ead_status fail(ead_handle *h, ead_status st, const char *fmt, ...) {
     va_list ap; va_start(ap, fmt); vsnprintf(buf, sizeof buf, fmt, ap); va_end(ap);
     if (h) h->err = buf; else g_create_error = buf;
     return st;
+}
+
+enum ProfKind { PK_EMBED = 0, PK_PACK_ACT, PK_FMA_QKV, PK_FMA_RES, PK_FMA_SWIGLU, PK_FMA_LOGITS, PK_MFMA_QKV,
+                PK_MFMA_RES, PK_MFMA_SWIGLU, PK_MFMA_LOGITS, PK_ATTN_PARTIAL, PK_ATTN_COMBINE, PK_PLAN, PK_FINALIZE,
+                PK_FUSED, PK_COUNT };
+const char *const kProfNames[PK_COUNT] = {"embed", "pack_act", "linear_fma_qkv", "linear_fma_res", "linear_fma_swiglu",
+                                          "linear_fma_logits", "linear_mfma_qkv", "linear_mfma_res", "linear_mfma_swiglu",
+                                          "linear_mfma_logits", "attention", "attn_combine", "plan", "lm_finalize",
+                                          "decode_fused"};
+
+// Brackets the launches made during its lifetime with two events (profiling mode only).
+struct ProfScope {
+    ead_handle *h; bool on;
+    ProfScope(ead_handle *h_, int kind, int model, double bytes) : h(h_), on(h_->prof_on != 0) {
+        if (!on) return;
+        hipEvent_t ev[2];
+        for (auto &e : ev) {
+            if (!h->ev_pool.empty()) { e = h->ev_pool.back(); h->ev_pool.pop_back(); }
+            else if (hipEventCreate(&e) != hipSuccess) { on = false; return; }
+        }
+        (void)hipEventRecord(ev[0], h->stream);
+        h->prof_recs.push_back({kind * 2 + model, ev[0], ev[1], bytes});
+    }
+    ~ProfScope() { if (on) (void)hipEventRecord(h->prof_recs.back().b, h->stream); }
+};
+
+void prof_collect(ead_handle *h) {
+    for (auto &r : h->prof_recs) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) { h->prof_ms[r.cls] += ms; h->prof_bytes[r.cls] += r.bytes; h->prof_n[r.cls]++; }
+        h->ev_pool.push_back(r.a); h->ev_pool.push_back(r.b);
+    }
+    h->prof_recs.clear();
 }
 
 #define HIP_TRY(h, expr)                                                                         \
@@ -325,6 +312,26 @@ ead_status build_model(ead_handle *h, const ead_model_desc *src, Model *m, int m
     TRY(dmalloc(h, &m->rope, tab.size()));
     HIP_TRY(h, hipMemcpyAsync(m->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, h->stream));
     HIP_TRY(h, hipStreamSynchronize(h->stream));   // tab goes out of scope
+    // tables for the fused single-row decode kernel
+    {
+        std::vector<FusedMat<WT>> mats;
+        std::vector<FusedLayer<WT>> lys;
+        for (int l = 0; l < m->L; ++l) {
+            const Layer &ly = m->layers[l];
+            mats.push_back({(const WT *)ly.wqkv, (NQ + 2 * NK) / 16, d / 32, 1});
+            mats.push_back({(const WT *)ly.wo, d / 16, NQ / 32, 0});
+            mats.push_back({(const WT *)ly.wgu, 2 * m->F / 16, d / 32, 0});
+            mats.push_back({(const WT *)ly.wdown, d / 16, m->F / 32, 0});
+            lys.push_back({ly.g_attn, ly.g_ffn, (WT *)ly.kcache, (WT *)ly.vcache});
+        }
+        mats.push_back({(const WT *)m->lm_head, m->V / 16, d / 32, 0});
+        m->n_mats = (int)mats.size();
+        FusedMat<WT> *dm = nullptr; FusedLayer<WT> *dl = nullptr;
+        TRY(dmalloc(h, &dm, mats.size())); TRY(dmalloc(h, &dl, lys.size()));
+        HIP_TRY(h, hipMemcpy(dm, mats.data(), mats.size() * sizeof(mats[0]), hipMemcpyHostToDevice));
+        HIP_TRY(h, hipMemcpy(dl, lys.data(), lys.size() * sizeof(lys[0]), hipMemcpyHostToDevice));
+        m->fused_mats = dm; m->fused_layers = dl;
+    }
     const double per_layer = (double)d * (NQ + 2 * NK) + (double)NQ * d + 3.0 * (double)d * m->F;
     m->n_params = m->L * (per_layer + 2.0 * d) + d + (double)m->V * d;
     m->weight_bytes_nolm = (m->L * per_layer) * sizeof(WT) + (2.0 * m->L + 1) * d * 4.0;
@@ -337,7 +344,8 @@ ead_status build_model(ead_handle *h, const ead_model_desc *src, Model *m, int m
 // one forward pass of one model over the rows of the current plan
 // ======================================================================================
 template <typename WT, int EPI>
-void launch_valu(ead_handle *h, LinArgs<WT> &a, int T, int grid) {
+void launch_valu(ead_handle *h, int mi, LinArgs<WT> &a, int T, int grid) {
+    ProfScope ps(h, PK_FMA_QKV + EPI, mi, (double)a.Np * a.K * sizeof(WT));
     const int KC = a.K / 32;
     const size_t budget = 60 * 1024;
     int TC = 4;
@@ -356,24 +364,31 @@ void launch_valu(ead_handle *h, LinArgs<WT> &a, int T, int grid) {
 }
 
 template <int EPI>
-void launch_mfma(ead_handle *h, LinArgs<bf16_t> &a, int grid) {
+void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int grid) {
+    ProfScope ps(h, PK_MFMA_QKV + EPI, mi, (double)a.Np * a.K * 2.0);
     if (a.K / 32 >= 64) hipLaunchKernelGGL((k_linear_mfma<8, EPI>), dim3(grid), dim3(512), 0, h->stream, a);
     else hipLaunchKernelGGL((k_linear_mfma<4, EPI>), dim3(grid), dim3(256), 0, h->stream, a);
 }
 
 template <typename KT, int HD>
-void launch_attn(ead_handle *h, AttnArgs<KT> &a, int G, int T) {
+void launch_attn(ead_handle *h, int mi, AttnArgs<KT> &a, int G, int T, double kv_bytes) {
     dim3 grid(a.max_splits, a.n_kv_heads, T);
-#define EAD_LA(G_) hipLaunchKernelGGL((k_attn_partial<KT, HD, G_>), grid, dim3(64), 0, h->stream, a)
-    switch (G) { case 1: EAD_LA(1); break; case 2: EAD_LA(2); break; case 4: EAD_LA(4); break;
-                 case 5: EAD_LA(5); break; case 7: EAD_LA(7); break; default: EAD_LA(8); break; }
+    {
+        ProfScope ps(h, PK_ATTN_PARTIAL, mi, kv_bytes);
+#define EAD_LA(G_) hipLaunchKernelGGL((k_attn<KT, HD, G_>), grid, dim3(64), 0, h->stream, a)
+        switch (G) { case 1: EAD_LA(1); break; case 2: EAD_LA(2); break; case 4: EAD_LA(4); break;
+                     case 5: EAD_LA(5); break; case 7: EAD_LA(7); break; default: EAD_LA(8); break; }
 #undef EAD_LA
-    hipLaunchKernelGGL((k_attn_combine<KT, HD>), dim3(a.n_heads, T), dim3(HD), 0, h->stream, a);
+    }
+    if (a.max_splits > 1) {
+        ProfScope ps(h, PK_ATTN_COMBINE, mi, 0.0);
+        hipLaunchKernelGGL((k_attn_combine<KT, HD>), dim3(a.n_heads, T), dim3(HD), 0, h->stream, a);
+    }
 }
 
 // T, n_lm, ctx_max: the host's copy of what k_plan wrote to the device plan.
 template <typename WT>
-ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, bool dump_logits) {
+ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, bool dump_logits, double keys_read) {
     Model &m = h->mdl[mi];
     const int d = m.d, hd = m.hd, NQ = m.H * hd, NK = m.KV * hd, F = m.F;
     constexpr bool is_bf16 = std::is_same<WT, bf16_t>::value;
@@ -382,10 +397,14 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
     const int *cnt = h->plan.hdr;
     const int T16 = (T + 15) & ~15;
 
-    hipLaunchKernelGGL(k_embed<WT>, dim3(T), dim3(256), 0, st, (const WT *)m.embed, h->s.tokens, cnt, h->plan.row_seq,
-                       h->plan.row_pos, h->s.max_seq, d, h->x);
+    {
+        ProfScope ps(h, PK_EMBED, mi, 0.0);
+        hipLaunchKernelGGL(k_embed<WT>, dim3(T), dim3(256), 0, st, (const WT *)m.embed, h->s.tokens, cnt, h->plan.row_seq,
+                           h->plan.row_pos, h->s.max_seq, d, h->x);
+    }
+    const double attn_bytes = keys_read * 2.0 * NK * sizeof(WT);
     // attention split: enough waves to fill the chip, bounded scratch
-    int chunk = 32;
+    int chunk = 8 * (64 / (hd / 8));          // one register-resident chunk of keys per wave at least
     while ((long)ctx_max * T * m.KV / chunk > 4096 && chunk < 4096) chunk <<= 1;
     while ((long)T * ((ctx_max + chunk - 1) / chunk) > h->items_max) chunk <<= 1;
     const int max_splits = (ctx_max + chunk - 1) / chunk;
@@ -400,13 +419,13 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         if (mfma) {
             if constexpr (is_bf16) {
                 PackArgs pa{h->x, d, cnt, nullptr, ly.g_attn, m.eps, h->xp_a, d};
-                hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa);
+                { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa); }
                 a.xp = h->xp_a;
-                launch_mfma<EPI_QKV>(h, a, a.Np / 16);
+                launch_mfma<EPI_QKV>(h, mi, a, a.Np / 16);
             }
         } else {
             a.x = h->x; a.ldx = d; a.gain = ly.g_attn; a.eps = m.eps;
-            launch_valu<WT, EPI_QKV>(h, a, T, a.Np / 16);
+            launch_valu<WT, EPI_QKV>(h, mi, a, T, a.Np / 16);
         }
         // ---- attention ----
         AttnArgs<WT> at{};
@@ -415,33 +434,33 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         at.max_seq = h->s.max_seq; at.chunk = chunk; at.max_splits = max_splits; at.scale = 1.0f / sqrtf((float)hd);
         at.part_o = h->part_o; at.part_ml = h->part_ml;
         if (mfma) at.out_tiles = h->xp_o; else at.out = h->o;
-        if (hd == 32) launch_attn<WT, 32>(h, at, m.H / m.KV, T);
-        else if (hd == 64) launch_attn<WT, 64>(h, at, m.H / m.KV, T);
-        else launch_attn<WT, 128>(h, at, m.H / m.KV, T);
+        if (hd == 32) launch_attn<WT, 32>(h, mi, at, m.H / m.KV, T, attn_bytes);
+        else if (hd == 64) launch_attn<WT, 64>(h, mi, at, m.H / m.KV, T, attn_bytes);
+        else launch_attn<WT, 128>(h, mi, at, m.H / m.KV, T, attn_bytes);
         // ---- output projection + residual ----
         LinArgs<WT> b{};
         b.W = (const WT *)ly.wo; b.Np = d; b.K = NQ; b.count = cnt; b.out = h->x; b.ldo = d;
-        if (mfma) { if constexpr (is_bf16) { b.xp = h->xp_o; launch_mfma<EPI_RES>(h, b, d / 16); } }
-        else { b.x = h->o; b.ldx = NQ; launch_valu<WT, EPI_RES>(h, b, T, d / 16); }
+        if (mfma) { if constexpr (is_bf16) { b.xp = h->xp_o; launch_mfma<EPI_RES>(h, mi, b, d / 16); } }
+        else { b.x = h->o; b.ldx = NQ; launch_valu<WT, EPI_RES>(h, mi, b, T, d / 16); }
         // ---- RMSNorm + gate/up + SwiGLU ----
         LinArgs<WT> c{};
         c.W = (const WT *)ly.wgu; c.Np = 2 * F; c.K = d; c.count = cnt; c.ldo = F;
         if (mfma) {
             if constexpr (is_bf16) {
                 PackArgs pa{h->x, d, cnt, nullptr, ly.g_ffn, m.eps, h->xp_a, d};
-                hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa);
+                { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa); }
                 c.xp = h->xp_a; c.out_tiles = h->xp_h; c.out_KC = F / 32;
-                launch_mfma<EPI_SWIGLU>(h, c, c.Np / 16);
+                launch_mfma<EPI_SWIGLU>(h, mi, c, c.Np / 16);
             }
         } else {
             c.x = h->x; c.ldx = d; c.gain = ly.g_ffn; c.eps = m.eps; c.out = h->hbuf;
-            launch_valu<WT, EPI_SWIGLU>(h, c, T, c.Np / 16);
+            launch_valu<WT, EPI_SWIGLU>(h, mi, c, T, c.Np / 16);
         }
         // ---- down projection + residual ----
         LinArgs<WT> e{};
         e.W = (const WT *)ly.wdown; e.Np = d; e.K = F; e.count = cnt; e.out = h->x; e.ldo = d;
-        if (mfma) { if constexpr (is_bf16) { e.xp = h->xp_h; launch_mfma<EPI_RES>(h, e, d / 16); } }
-        else { e.x = h->hbuf; e.ldx = F; launch_valu<WT, EPI_RES>(h, e, T, d / 16); }
+        if (mfma) { if constexpr (is_bf16) { e.xp = h->xp_h; launch_mfma<EPI_RES>(h, mi, e, d / 16); } }
+        else { e.x = h->hbuf; e.ldx = F; launch_valu<WT, EPI_RES>(h, mi, e, T, d / 16); }
     }
     if (n_lm > 0) {
         // ---- final RMSNorm + LM head with the entropy statistics folded in ----
@@ -452,22 +471,90 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         if (is_bf16 && n_lm > 4) {
             if constexpr (is_bf16) {
                 PackArgs pa{h->x, d, cnt + 1, h->plan.lm_row, m.g_final, m.eps, h->xp_a, d};
-                hipLaunchKernelGGL(k_pack_act, dim3((n_lm + 15) & ~15), dim3(256), 0, st, pa);
+                { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3((n_lm + 15) & ~15), dim3(256), 0, st, pa); }
                 g.xp = h->xp_a;
-                launch_mfma<EPI_LOGITS>(h, g, grid);
+                launch_mfma<EPI_LOGITS>(h, mi, g, grid);
             }
         } else {
             g.x = h->x; g.ldx = d; g.gain = m.g_final; g.eps = m.eps;
-            launch_valu<WT, EPI_LOGITS>(h, g, n_lm, grid);
+            launch_valu<WT, EPI_LOGITS>(h, mi, g, n_lm, grid);
         }
     }
     HIP_TRY(h, hipGetLastError());
     return EAD_OK;
 }
 
-ead_status run_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, bool dump) {
-    return h->mdl[mi].dtype == EAD_BF16 ? forward_pass<bf16_t>(h, mi, T, n_lm, ctx_max, dump)
-                                        : forward_pass<float>(h, mi, T, n_lm, ctx_max, dump);
+// keys read by the pass the host just planned (kvlen not yet advanced): row j of a sequence
+// that had `have` positions reads have + j + 1 keys
+double keys_in_pass(ead_handle *h, int mi, const std::vector<int> &rows) {
+    double k = 0.0;
+    for (int b = 0; b < h->batch; ++b)
+        if (rows[b]) k += (double)rows[b] * h->hs[b].kvlen[mi] + (double)rows[b] * (rows[b] + 1) / 2.0;
+    return k;
+}
+
+ead_status run_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, bool dump, const std::vector<int> &rows) {
+    const double keys = keys_in_pass(h, mi, rows);
+    return h->mdl[mi].dtype == EAD_BF16 ? forward_pass<bf16_t>(h, mi, T, n_lm, ctx_max, dump, keys)
+                                        : forward_pass<float>(h, mi, T, n_lm, ctx_max, dump, keys);
+}
+
+// ---- fused single-row decode step ---------------------------------------------------------
+template <typename WT, int HD, int G>
+void *fused_kernel_ptr() { return (void *)k_decode_fused<WT, HD, G>; }
+
+// the (dtype, head_dim, heads per KV head) combinations the fused kernel is built for
+void *fused_kernel_for(const Model &m) {
+    const int G = m.H / m.KV;
+    if (m.dtype == EAD_F32) {
+        if (m.hd == 32 && G == 1) return fused_kernel_ptr<float, 32, 1>();
+        if (m.hd == 32 && G == 2) return fused_kernel_ptr<float, 32, 2>();
+        return nullptr;
+    }
+    if (m.hd == 64 && G == 4) return fused_kernel_ptr<bf16_t, 64, 4>();
+    if (m.hd == 128 && G == 4) return fused_kernel_ptr<bf16_t, 128, 4>();
+    if (m.hd == 64 && G == 7) return fused_kernel_ptr<bf16_t, 64, 7>();
+    if (m.hd == 128 && G == 5) return fused_kernel_ptr<bf16_t, 128, 5>();
+    return nullptr;
+}
+
+size_t fused_lds_bytes(const Model &m) {
+    const size_t kmax = std::max(std::max(m.d, m.F), m.H * m.hd);
+    const size_t G = m.H / m.KV;
+    const size_t attn = (size_t)kFusedWaves * m.hd + 2 * kFusedWaves + 0 * G;
+    return std::max(kmax + (size_t)kFusedRbChunk * kFusedWaves * 16 + 64, attn) * sizeof(float);
+}
+
+FinArgs make_fin(ead_handle *h, int m, bool score) {
+    FinArgs fa{};
+    fa.s = h->s; fa.p = h->plan; fa.cfg = h->cfg; fa.partials = h->lm_part;
+    fa.n_part = std::min(h->mdl[m].V / 16, h->lm_grid); fa.unit = h->prm.unit;
+    fa.score_mode = score ? 1 : 0; fa.sc_H = h->sc_H; fa.sc_arg = h->sc_arg;
+    fa.model_id = m; fa.max_new = h->max_new; fa.eos_id = h->prm.eos_id; fa.replay = h->replay; fa.n_new = h->n_new;
+    fa.force_model = h->force_model; fa.step = h->step;
+    return fa;
+}
+
+template <typename WT>
+ead_status fused_step(ead_handle *h, int mi, double keys) {
+    Model &m = h->mdl[mi];
+    FusedArgs<WT> a{};
+    a.L = m.L; a.d = m.d; a.H = m.H; a.KV = m.KV; a.hd = m.hd; a.F = m.F; a.V = m.V; a.eps = m.eps;
+    a.mats = (const FusedMat<WT> *)m.fused_mats; a.layers = (const FusedLayer<WT> *)m.fused_layers; a.n_mats = m.n_mats;
+    a.embed = (const WT *)m.embed; a.g_final = m.g_final; a.rope = m.rope;
+    a.x = h->x; a.q = h->q; a.hbuf = h->hbuf; a.att_o = h->att_o; a.att_ml = h->att_ml; a.lm_part = h->lm_part;
+    a.bar = GridBar{h->bar_mem, h->bar_mem + kBarGroups * 32, h->abort_flag, h->bar_epoch};
+    a.fin = make_fin(h, mi, false);
+    a.batch = h->batch;
+#ifdef EAD_FUSED_TRACE
+    a.trace = h->trace;
+#endif
+    void *args[] = {&a};
+    ProfScope ps(h, PK_FUSED, mi, m.weight_bytes_nolm + m.lm_bytes + keys * m.kv_bytes_per_pos);
+    HIP_TRY(h, hipLaunchCooperativeKernel(fused_kernel_for(m), dim3(h->fused_grid), dim3(kFusedThreads), args,
+                                          (unsigned)fused_lds_bytes(m), h->stream));
+    h->bar_epoch += 5u * m.L + 1u;
+    return EAD_OK;
 }
 
 // Host copy of k_plan: which rows the pass will hold.  Returns T; fills n_lm, ctx_max and,
@@ -496,30 +583,20 @@ int host_plan(ead_handle *h, int m, int budget, int limit_off, int lm_mode, bool
 
 void launch_plan(ead_handle *h, int m, int budget, int limit_off, int lm_mode, bool ignore_model, int step) {
     PlanArgs pa{h->s, h->plan, h->batch, m, budget, limit_off, lm_mode, ignore_model ? 1 : 0, step};
+    ProfScope ps(h, PK_PLAN, m, 0.0);
     hipLaunchKernelGGL(k_plan, dim3(1), dim3(256), 3 * h->batch * sizeof(int), h->stream, pa);
 }
 
 void launch_finalize(ead_handle *h, int m, int n_lm, bool score) {
-    FinArgs fa{};
-    fa.s = h->s; fa.p = h->plan; fa.cfg = h->cfg; fa.partials = h->lm_part;
-    fa.n_part = std::min(h->mdl[m].V / 16, h->lm_grid); fa.unit = h->prm.unit;
-    fa.score_mode = score ? 1 : 0; fa.sc_H = h->sc_H; fa.sc_arg = h->sc_arg;
-    fa.model_id = m; fa.max_new = h->max_new; fa.eos_id = h->prm.eos_id; fa.replay = h->replay; fa.n_new = h->n_new;
-    fa.force_model = h->force_model; fa.step = h->step;
+    FinArgs fa = make_fin(h, m, score);
+    ProfScope ps(h, PK_FINALIZE, m, 0.0);
     hipLaunchKernelGGL(k_lm_finalize, dim3(n_lm), dim3(64), 0, h->stream, fa);
 }
 
 void account_pass(ead_handle *h, int m, const std::vector<int> &rows, bool with_lm) {
     Model &md = h->mdl[m];
-    double bytes = md.weight_bytes_nolm + (with_lm ? md.lm_bytes : 0.0);
-    for (int b = 0; b < h->batch; ++b) {
-        const int n = rows[b];
-        if (!n) continue;
-        const int have = h->hs[b].kvlen[m];
-        // row j reads have + j + 1 keys
-        bytes += md.kv_bytes_per_pos * ((double)n * have + (double)n * (n + 1) / 2.0);
-    }
-    h->stats.algorithmic_bytes += bytes;
+    h->stats.algorithmic_bytes += md.weight_bytes_nolm + (with_lm ? md.lm_bytes : 0.0) +
+                                  md.kv_bytes_per_pos * keys_in_pass(h, m, rows);
 }
 
 ead_status validate_prompts(ead_handle *h, const int32_t *toks, const int32_t *lens, int batch, int max_new) {
@@ -575,7 +652,7 @@ ead_status begin_impl(ead_handle *h, const int32_t *toks, const int32_t *lens, i
             const int T = host_plan(h, m, h->Tmax, 1, 0, true, -1, &n_lm, &ctx_max, &rows, &complete);
             if (T == 0) break;
             launch_plan(h, m, h->Tmax, 1, 0, true, -1);
-            TRY(run_pass(h, m, T, 0, ctx_max, false));
+            TRY(run_pass(h, m, T, 0, ctx_max, false, rows));
             for (int b = 0; b < batch; ++b) h->hs[b].kvlen[m] += rows[b];
         }
     }
@@ -599,9 +676,14 @@ ead_status decode_impl(ead_handle *h, int n_steps) {
                 const int T = host_plan(h, m, h->Tmax, 0, 1, false, step, &n_lm, &ctx_max, &rows, &complete);
                 if (T == 0) break;
                 any = true;
-                launch_plan(h, m, h->Tmax, 0, 1, false, step);
-                TRY(run_pass(h, m, T, n_lm, ctx_max, false));
-                if (n_lm > 0) launch_finalize(h, m, n_lm, false);
+                if (T == 1 && n_lm == 1 && h->fused_on && h->mdl[m].fused_ok) {
+                    const double keys = keys_in_pass(h, m, rows);
+                    TRY(h->mdl[m].dtype == EAD_BF16 ? fused_step<bf16_t>(h, m, keys) : fused_step<float>(h, m, keys));
+                } else {
+                    launch_plan(h, m, h->Tmax, 0, 1, false, step);
+                    TRY(run_pass(h, m, T, n_lm, ctx_max, false, rows));
+                    if (n_lm > 0) launch_finalize(h, m, n_lm, false);
+                }
                 account_pass(h, m, rows, n_lm > 0);
                 if (n_lm > 0) (m ? h->stats.steps_large : h->stats.steps_small)++;
                 for (int b = 0; b < h->batch; ++b) {
@@ -655,7 +737,15 @@ ead_status decode_impl(ead_handle *h, int n_steps) {
         h->step++;
     }
     HIP_TRY(h, hipStreamSynchronize(st));
-    int err = 0;
+    int err = 0, aborted = 0;
+    HIP_TRY(h, hipMemcpy(&aborted, h->abort_flag, sizeof(int), hipMemcpyDeviceToHost));
+    if (aborted) {
+        // a grid barrier gave up: drop the fused path for this handle and start its counters afresh
+        h->fused_on = 0; h->bar_epoch = 0; h->began = 0;
+        HIP_TRY(h, hipMemset(h->bar_mem, 0, (kBarGroups * 32 + 32) * sizeof(unsigned)));
+        HIP_TRY(h, hipMemset(h->abort_flag, 0, sizeof(int)));
+        return fail(h, EAD_ERR_DEVICE, "fused decode kernel abandoned a grid barrier; fused path disabled, run again");
+    }
     HIP_TRY(h, hipMemcpy(&err, h->s.err, sizeof(int), hipMemcpyDeviceToHost));
     if (err) return fail(h, EAD_ERR_NONFINITE, "a non-finite entropy was produced (non-finite logits)");
     return EAD_OK;
@@ -753,6 +843,8 @@ void ead_destroy(ead_handle *h) {
     for (void *p : h->allocs) (void)hipFree(p);
     if (h->h_model) (void)hipHostFree(h->h_model);
     if (h->h_done) (void)hipHostFree(h->h_done);
+    prof_collect(h);
+    for (hipEvent_t e : h->ev_pool) (void)hipEventDestroy(e);
     delete h;
 }
 
@@ -812,9 +904,31 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
         HIP_TRY(h, hipMemsetAsync(h->xp_o, 0, T * qmax * 2, h->stream));
         HIP_TRY(h, hipMemsetAsync(h->xp_h, 0, T * fmax_ * 2, h->stream));
         TRY(dmalloc(h, &h->part_o, (size_t)h->items_max * qmax)); TRY(dmalloc(h, &h->part_ml, (size_t)h->items_max * std::max(a.H, b.H)));
-        TRY(dmalloc(h, &h->lm_part, (size_t)std::max<size_t>(MB, h->score_rows) * h->lm_grid));
+        TRY(dmalloc(h, &h->lm_part, std::max((size_t)std::max<size_t>(MB, h->score_rows) * h->lm_grid, (size_t)256 * kFusedRbChunk)));
         TRY(dmalloc(h, &h->logits_dump, (size_t)h->score_rows * a.V));
         TRY(dmalloc(h, &h->sc_H, (size_t)MS)); TRY(dmalloc(h, &h->sc_arg, (size_t)MS));
+        {
+            const size_t hmax = std::max(a.H, b.H), qm = qmax;
+            TRY(dmalloc(h, &h->att_o, qm * kFusedMaxSplits)); TRY(dmalloc(h, &h->att_ml, hmax * kFusedMaxSplits));
+#ifdef EAD_FUSED_TRACE
+            TRY(dmalloc(h, &h->trace, (size_t)8192));
+#endif
+            TRY(dmalloc(h, &h->bar_mem, (size_t)kBarGroups * 32 + 32)); TRY(dmalloc(h, &h->abort_flag, (size_t)1));
+            HIP_TRY(h, hipMemsetAsync(h->bar_mem, 0, (kBarGroups * 32 + 32) * sizeof(unsigned), h->stream));
+            HIP_TRY(h, hipMemsetAsync(h->abort_flag, 0, sizeof(int), h->stream));
+            int dev = 0; hipDeviceProp_t prop;
+            HIP_TRY(h, hipGetDevice(&dev)); HIP_TRY(h, hipGetDeviceProperties(&prop, dev));
+            h->fused_grid = std::min(256, prop.multiProcessorCount);
+            for (int mi = 0; mi < 2; ++mi) {
+                Model &md = h->mdl[mi];
+                void *fn = fused_kernel_for(md);
+                int per_cu = 0;
+                md.fused_ok = fn && prop.cooperativeLaunch && md.n_mats <= kFusedMaxMats &&
+                              hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fused_lds_bytes(md)) == hipSuccess &&
+                              hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kFusedThreads, fused_lds_bytes(md)) == hipSuccess &&
+                              per_cu >= 1 && md.KV * kFusedMaxSplits <= h->fused_grid;
+            }
+        }
         HIP_TRY(h, hipHostMalloc((void **)&h->h_model, std::max<size_t>((size_t)MB * MS, 64) * sizeof(int), hipHostMallocDefault));
         HIP_TRY(h, hipHostMalloc((void **)&h->h_done, std::max<size_t>(MB, 64) * sizeof(int), hipHostMallocDefault));
         HIP_TRY(h, hipStreamSynchronize(h->stream));
@@ -940,7 +1054,7 @@ ead_status ead_score(ead_handle *h, int32_t which, const int32_t *tokens, int32_
         const int T = host_plan(h, which, h->score_rows, 0, 2, false, -1, &n_lm, &ctx_max, &rows, &complete);
         if (T == 0) break;
         launch_plan(h, which, h->score_rows, 0, 2, false, -1);
-        TRY(run_pass(h, which, T, n_lm, ctx_max, out_logits != nullptr));
+        TRY(run_pass(h, which, T, n_lm, ctx_max, out_logits != nullptr, rows));
         launch_finalize(h, which, n_lm, true);
         s.kvlen[which] += T;
         if (out_logits) {
@@ -967,6 +1081,45 @@ ead_status ead_get_stats(ead_handle *h, ead_stats *out) {
 ead_status ead_reset_stats(ead_handle *h) {
     if (!h) return EAD_ERR_INVALID_ARG;
     memset(&h->stats, 0, sizeof h->stats);
+    return EAD_OK;
+}
+
+#ifdef EAD_FUSED_TRACE
+ead_status ead_trace_read(ead_handle *h, long long *out) {
+    if (!h || !out) return EAD_ERR_INVALID_ARG;
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    HIP_TRY(h, hipMemcpy(out, h->trace, 8192 * sizeof(long long), hipMemcpyDeviceToHost));
+    return EAD_OK;
+}
+#endif
+
+ead_status ead_set_fused(ead_handle *h, int32_t on) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    h->fused_on = on ? 1 : 0;
+    return EAD_OK;
+}
+
+ead_status ead_profile_enable(ead_handle *h, int32_t on) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    prof_collect(h);
+    memset(h->prof_ms, 0, sizeof h->prof_ms); memset(h->prof_bytes, 0, sizeof h->prof_bytes); memset(h->prof_n, 0, sizeof h->prof_n);
+    h->prof_on = on ? 1 : 0;
+    return EAD_OK;
+}
+
+ead_status ead_profile_read(ead_handle *h, ead_kernel_profile *out, int32_t capacity, int32_t *n_out) {
+    if (!h || !out || !n_out || capacity < 0) return EAD_ERR_INVALID_ARG;
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    prof_collect(h);
+    int n = 0;
+    for (int c = 0; c < PK_COUNT * 2 && n < capacity; ++c) {
+        if (!h->prof_n[c]) continue;
+        snprintf(out[n].name, sizeof out[n].name, "%s/%s", kProfNames[c / 2], (c & 1) ? "large" : "small");
+        out[n].launches = h->prof_n[c]; out[n].total_ms = h->prof_ms[c]; out[n].bytes = h->prof_bytes[c];
+        ++n;
+    }
+    *n_out = n;
     return EAD_OK;
 }
 

@@ -32,6 +32,7 @@ struct LinArgs {
     // outputs
     float *out;             // RES: residual stream [T, ldo] (+=); SWIGLU: h [T, ldo]; QKV: q [T, ldo]
     int ldo;
+    const WT *res_embed;    // RES, optional: the residual is this embedding row instead of out (first layer)
     bf16_t *out_tiles;      // SWIGLU, optional: h as bf16 tiles for the next MFMA layer
     int out_KC;             //   K/32 of that consumer
     // QKV
@@ -49,17 +50,26 @@ struct LinArgs {
 // groups whose lanes hold consecutive packed rows, so the rotary / SwiGLU partner is
 // the neighbouring lane.
 // ------------------------------------------------------------------------------------
-template <typename WT, int EPI>
+template <typename T> __device__ __forceinline__ void put(T *p, T v, bool coherent) {
+    if (coherent) st_coherent(p, v); else *p = v;
+}
+
+// COH: outputs are handed to other workgroups inside the same kernel (fused decode).
+template <typename WT, int EPI, bool COH = false>
 __device__ __forceinline__ void epilogue(const LinArgs<WT> &a, int p, int t, float v, bool valid,
                                          EntStat &st) {
     if constexpr (EPI == EPI_RES) {
-        if (valid) a.out[(size_t)t * a.ldo + p] += v;
+        if (valid) {
+            float *dst = a.out + (size_t)t * a.ldo + p;
+            const float r = a.res_embed ? to_f32(a.res_embed[p]) : (COH ? ld_coherent(dst) : *dst);
+            put(dst, r + v, COH);
+        }
     } else if constexpr (EPI == EPI_SWIGLU) {
         float other = __shfl_xor(v, 1, kWave);       // even lane: gate, odd lane: up
         if (valid && !(p & 1)) {
             float h = v / (1.f + __expf(-v)) * other;
             int i = p >> 1;
-            if (a.out) a.out[(size_t)t * a.ldo + i] = h;
+            if (a.out) put(a.out + (size_t)t * a.ldo + i, h, COH);
             if (a.out_tiles) {
                 size_t off = tile_offset(t >> 4, i >> 5, a.out_KC) + (size_t)(((t & 15) + 16 * ((i & 31) >> 3)) * 8 + (i & 7));
                 a.out_tiles[off].u = f32_to_bf16(h);
@@ -76,15 +86,15 @@ __device__ __forceinline__ void epilogue(const LinArgs<WT> &a, int p, int t, flo
             float2 cs = a.rope[(size_t)pos * (hd >> 1) + i];
             float res = s ? (other * cs.y + v * cs.x) : (v * cs.x - other * cs.y);
             int dim = i + s * (hd >> 1);
-            if (p < NQ) a.out[(size_t)t * a.ldo + head * hd + dim] = res;
+            if (p < NQ) put(a.out + (size_t)t * a.ldo + head * hd + dim, res, COH);
             else {
                 size_t o = (((size_t)a.row_seq[t] * a.n_kv_heads + head) * a.max_seq + pos) * hd + dim;
-                a.kcache[o] = from_f32<WT>(res);
+                put(a.kcache + o, from_f32<WT>(res), COH);
             }
         } else {
             int pp = p - NQ - NK, head = pp / hd, dim = pp % hd;
             size_t o = (((size_t)a.row_seq[t] * a.n_kv_heads + head) * a.max_seq + pos) * hd + dim;
-            a.vcache[o] = from_f32<WT>(v);
+            put(a.vcache + o, from_f32<WT>(v), COH);
         }
     } else {                                          // EPI_LOGITS: fold the logit into (m, Z, S, argmax)
         if (!valid) return;
@@ -102,7 +112,7 @@ __device__ __forceinline__ void epilogue(const LinArgs<WT> &a, int p, int t, flo
 
 // After a workgroup has seen all its row blocks: merge the 16 lanes of each token row
 // and store one partial per (row, workgroup).
-template <typename WT>
+template <typename WT, bool COH = false>
 __device__ __forceinline__ void logits_flush(const LinArgs<WT> &a, int t, bool valid, EntStat st) {
 #pragma unroll
     for (int o = 8; o > 0; o >>= 1) {
@@ -112,17 +122,30 @@ __device__ __forceinline__ void logits_flush(const LinArgs<WT> &a, int t, bool v
         st.merge(q);
     }
     if (valid && (threadIdx.x & 15) == 0) {
-        EntPartial e; e.m = st.m; e.Z = st.Z; e.S = st.S; e.idx = st.idx;
-        a.partials[(size_t)t * gridDim.x + blockIdx.x] = e;
+        EntPartial *d = a.partials + (size_t)t * gridDim.x + blockIdx.x;
+        put(&d->m, st.m, COH); put(&d->Z, st.Z, COH); put(&d->S, st.S, COH); put(&d->idx, st.idx, COH);
     }
 }
 
 // ------------------------------------------------------------------------------------
 // FMA path.  TC token rows per pass over the weights; NW waves split K.
 // dynamic LDS: xs[TC][K] floats, then red[NW][TC][16] floats.
+// A wave's tiles are fetched U at a time, one group ahead of the arithmetic, and the
+// first group of the next row block (or of the kernel, before the activations are even
+// staged) is already in flight while partial sums are being reduced.
 // ------------------------------------------------------------------------------------
+template <typename WT, int U>
+__device__ __forceinline__ void load_group(Vec8<WT> (&w)[U], const WT *wp, int kc, int kc1) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (kc + u < kc1) w[u].load_stream(wp + (size_t)u * 512);
+        else w[u].zero();
+    }
+}
+
 template <typename WT, int TC, int NW, int EPI>
 __global__ __launch_bounds__(NW * 64) void k_linear_valu(LinArgs<WT> a) {
+    constexpr int U = sizeof(WT) == 2 ? 8 : 4;
     extern __shared__ float smem[];
     const int K = a.K, KC = K >> 5, NB = a.Np >> 4;
     float *xs = smem;
@@ -132,6 +155,9 @@ __global__ __launch_bounds__(NW * 64) void k_linear_valu(LinArgs<WT> a) {
     const int g = lane >> 4;
     const int T = *a.count;
     const int kc0 = (wave * KC) / NW, kc1 = ((wave + 1) * KC) / NW;
+
+    Vec8<WT> cur[U];
+    if ((int)blockIdx.x < NB) load_group<WT, U>(cur, a.W + tile_offset(blockIdx.x, kc0, KC) + lane * 8, kc0, kc1);
 
     for (int t0 = 0; t0 < T; t0 += TC) {
         // ---- stage (and normalise) TC activation rows ----
@@ -175,37 +201,37 @@ __global__ __launch_bounds__(NW * 64) void k_linear_valu(LinArgs<WT> a) {
 #pragma unroll
             for (int tc = 0; tc < TC; ++tc) acc[tc] = 0.f;
             const WT *wp = a.W + tile_offset(rb, kc0, KC) + lane * 8;
-            const float *xq = xs + kc0 * 32 + g * 8;
-            int kc = kc0;
-            for (; kc + 4 <= kc1; kc += 4) {
-                Vec8<WT> w[4];
+            const float *xq = xs + g * 8;
+            for (int kc = kc0; kc < kc1; kc += U) {
+                // fetch one group ahead: the rest of this row block, else the head of the next
+                // one (the next pass over the same block when more token rows follow)
+                Vec8<WT> nxt[U];
+                if (kc + U < kc1) load_group<WT, U>(nxt, wp + (size_t)U * 512, kc + U, kc1);
+                else {
+                    int nrb = rb + gridDim.x;
+                    if (nrb >= NB && t0 + TC < T) nrb = blockIdx.x;
+                    if (nrb < NB) load_group<WT, U>(nxt, a.W + tile_offset(nrb, kc0, KC) + lane * 8, kc0, kc1);
+                    else {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) w[u].load_stream(wp + (size_t)u * 512);
+                        for (int u = 0; u < U; ++u) nxt[u].zero();
+                    }
+                }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < U; ++u) {
                     float wf[8];
-                    w[u].unpack(wf);
+                    cur[u].unpack(wf);
+                    const int kk = min(kc + u, kc1 - 1);          // tiles past the end are zero
 #pragma unroll
                     for (int tc = 0; tc < TC; ++tc) {
-                        const float4 x0 = *reinterpret_cast<const float4 *>(xq + (size_t)tc * K + u * 32);
-                        const float4 x1 = *reinterpret_cast<const float4 *>(xq + (size_t)tc * K + u * 32 + 4);
+                        const float4 x0 = *reinterpret_cast<const float4 *>(xq + (size_t)tc * K + kk * 32);
+                        const float4 x1 = *reinterpret_cast<const float4 *>(xq + (size_t)tc * K + kk * 32 + 4);
                         acc[tc] += wf[0] * x0.x + wf[1] * x0.y + wf[2] * x0.z + wf[3] * x0.w
                                  + wf[4] * x1.x + wf[5] * x1.y + wf[6] * x1.z + wf[7] * x1.w;
                     }
                 }
-                wp += 4 * 512; xq += 4 * 32;
-            }
-            for (; kc < kc1; ++kc) {
-                Vec8<WT> w; w.load_stream(wp);
-                float wf[8]; w.unpack(wf);
 #pragma unroll
-                for (int tc = 0; tc < TC; ++tc) {
-                    const float4 x0 = *reinterpret_cast<const float4 *>(xq + (size_t)tc * K);
-                    const float4 x1 = *reinterpret_cast<const float4 *>(xq + (size_t)tc * K + 4);
-                    acc[tc] += wf[0] * x0.x + wf[1] * x0.y + wf[2] * x0.z + wf[3] * x0.w
-                             + wf[4] * x1.x + wf[5] * x1.y + wf[6] * x1.z + wf[7] * x1.w;
-                }
-                wp += 512; xq += 32;
+                for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+                wp += (size_t)U * 512;
             }
 #pragma unroll
             for (int tc = 0; tc < TC; ++tc) {

@@ -191,3 +191,45 @@ def test_bf16_truncated_pair_score_and_replay(pair, layers, T):
     assert (rp["next_model"][0][safe] == want_next[safe]).all()
     print(f"  decisions checked outside the band: {int(safe.sum())}/24", flush=True)
     e.close()
+
+
+def test_fused_single_row_kernel_matches_per_layer_kernels(tiny):
+    """The persistent one-kernel-per-step decode path against the per-layer kernels and the oracle."""
+    e, os_, ol = tiny
+    prompt = si.prompt_np(5, "cfg1", 16, 512)
+    tau = _calibrate_tau(os_, ol, prompt, 48, 5, 55)
+    e.set_gate(5, tau, 5)
+    ref = oracle.generate(os_, ol, prompt, 48, 5, tau, d_min=5)
+    outs = []
+    for fused in (False, True):
+        e.set_fused(fused)
+        outs.append(e.generate([prompt], 48))
+        rp = e.replay([prompt], ref["tokens"], ref["model_id"])
+        assert np.abs(rp["H"][0] - ref["H"]).max() < 1e-4
+        assert (rp["argmax"][0] == ref["tokens"]).all()
+    e.set_fused(False)
+    assert np.abs(outs[0]["H"] - outs[1]["H"]).max() < 1e-4
+    if (np.abs(ref["Hbar"] - tau) > 1e-4).all():
+        assert (outs[0]["tokens"] == outs[1]["tokens"]).all() and (outs[1]["tokens"][0] == ref["tokens"]).all()
+
+
+@pytest.mark.parametrize("pair", ["llama", "qwen"])
+def test_fused_kernel_bf16_truncated(pair):
+    ead = _ead()
+    ss, sl = (s.truncated(2) for s in si.PAIRS[pair])
+    Ws, Wl, os_, ol = _pair(ss, sl)
+    e = ead.EAD(ss, Ws, sl, Wl, window=5, tau=0.0, d_min=4, max_batch=1, max_seq=64)
+    prompt = si.prompt_np(1, pair, 8, ss.vocab)
+    probe = oracle.generate(os_, ol, prompt, 20, 5, 1e30, d_min=4)
+    tau = float(np.percentile(probe["Hbar"], 50))
+    ref = oracle.generate(os_, ol, prompt, 20, 5, tau, d_min=4)
+    e.set_gate(5, tau, 4)
+    e.set_fused(True)
+    rp = e.replay([prompt], ref["tokens"], ref["model_id"])
+    print(f"{pair} fused replay H err {np.abs(rp['H'][0] - ref['H']).max():.2e}", flush=True)
+    assert np.abs(rp["H"][0] - ref["H"]).max() < TOL_H
+    assert np.abs(rp["Hbar"][0] - ref["Hbar"]).max() < TOL_H
+    safe = np.abs(ref["Hbar"] - tau) > BAND
+    want_next = np.concatenate([ref["model_id"][1:], rp["next_model"][0][-1:]])
+    assert (rp["next_model"][0][safe] == want_next[safe]).all()
+    e.close()
