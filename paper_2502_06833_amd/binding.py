@@ -99,6 +99,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2502_06833_amd.build` "
                               "(there is no fallback path)")
+        # PyTorch ships its own HIP runtime; load it first so that the library binds to the
+        # same runtime (and the same device context) as the tensors it is handed
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         for name, (res, args) in _SIGNATURES.items():
             fn = getattr(L, name)
