@@ -23,19 +23,20 @@ struct AttnArgs {
     float *part_o;             // [T*H*max_splits][hd]   un-normalised
     float2 *part_ml;           // [T*H*max_splits]       (max, sum)
     float *out;                // [T, H*hd] fp32 (optional)
-    bf16_t *out_tiles;         // bf16 tiles of [T, H*hd] for an MFMA consumer (optional)
+    bf16_t *out_tiles;         // bf16 tiles (high parts) of [T, H*hd] for an MFMA consumer (optional)
+    bf16_t *out_tiles_lo;      //   and low parts
 };
 
 constexpr float kNegBig = -1e30f;
 
 template <int HD>
-__device__ __forceinline__ void attn_store(float *out, bf16_t *out_tiles, int t, int H,
+__device__ __forceinline__ void attn_store(float *out, bf16_t *out_tiles, bf16_t *out_tiles_lo, int t, int H,
                                            int col, float r) {
     if (out) out[(size_t)t * H * HD + col] = r;
     if (out_tiles) {
         const int KC = (H * HD) >> 5;
         const size_t off = tile_offset(t >> 4, col >> 5, KC) + (size_t)(((t & 15) + 16 * ((col & 31) >> 3)) * 8 + (col & 7));
-        out_tiles[off].u = f32_to_bf16(r);
+        split_bf16(r, out_tiles[off].u, out_tiles_lo[off].u);
     }
 }
 
@@ -152,7 +153,7 @@ __global__ __launch_bounds__(64) void k_attn(AttnArgs<KT> a) {
             for (int g = 0; g < G; ++g) {
                 const float r = 1.f / l[g];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) attn_store<HD>(a.out, a.out_tiles, t, H, (kvh * G + g) * HD + dl * 8 + e, o[g][e] * r);
+                for (int e = 0; e < 8; ++e) attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, (kvh * G + g) * HD + dl * 8 + e, o[g][e] * r);
             }
         }
         return;
@@ -188,7 +189,7 @@ __global__ __launch_bounds__(HD) void k_attn_combine(AttnArgs<KT> a) {
         L += ml.y * c;
         acc += a.part_o[(item0 + s) * HD + d] * c;
     }
-    attn_store<HD>(a.out, a.out_tiles, t, H, h * HD + d, acc / L);
+    attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, h * HD + d, acc / L);
 }
 
 }  // namespace ead

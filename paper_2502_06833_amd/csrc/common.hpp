@@ -31,6 +31,13 @@ template <typename T> __device__ __forceinline__ T from_f32(float f);
 template <> __device__ __forceinline__ float from_f32<float>(float f) { return f; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) { bf16_t r; r.u = f32_to_bf16(f); return r; }
 
+// x = hi + lo with both parts bf16: an activation tile kept as two bf16 tiles carries
+// about 16 significant bits through the bf16 matrix cores.
+__device__ __forceinline__ void split_bf16(float f, uint16_t &hi, uint16_t &lo) {
+    hi = f32_to_bf16(f);
+    lo = f32_to_bf16(f - bf16_to_f32(hi));
+}
+
 template <typename V> using gptr = const V __attribute__((address_space(1))) *;
 
 // Eight consecutive elements of type T held by one lane.

@@ -156,7 +156,7 @@ struct ead_handle {
     int Tmax, items_max, lm_grid, score_rows;
     SeqState s; Plan plan; GateCfg cfg;
     // scratch
-    float *x, *q, *o, *hbuf; bf16_t *xp_a, *xp_o, *xp_h;
+    float *x, *q, *o, *hbuf; bf16_t *xp_a, *xp_o, *xp_h, *xl_a, *xl_o, *xl_h;
     float *part_o; float2 *part_ml; EntPartial *lm_part; float *logits_dump; float *sc_H; int *sc_arg;
     int *h_model, *h_done;   // pinned
     // fused single-row decode
@@ -418,9 +418,9 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         a.rope = m.rope; a.n_heads = m.H; a.n_kv_heads = m.KV; a.hd = hd; a.max_seq = h->s.max_seq;
         if (mfma) {
             if constexpr (is_bf16) {
-                PackArgs pa{h->x, d, cnt, nullptr, ly.g_attn, m.eps, h->xp_a, d};
+                PackArgs pa{h->x, d, cnt, nullptr, ly.g_attn, m.eps, h->xp_a, h->xl_a, d};
                 { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa); }
-                a.xp = h->xp_a;
+                a.xp = h->xp_a; a.xp_lo = h->xl_a;
                 launch_mfma<EPI_QKV>(h, mi, a, a.Np / 16);
             }
         } else {
@@ -433,23 +433,23 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         at.row_seq = h->plan.row_seq; at.row_pos = h->plan.row_pos; at.n_heads = m.H; at.n_kv_heads = m.KV;
         at.max_seq = h->s.max_seq; at.chunk = chunk; at.max_splits = max_splits; at.scale = 1.0f / sqrtf((float)hd);
         at.part_o = h->part_o; at.part_ml = h->part_ml;
-        if (mfma) at.out_tiles = h->xp_o; else at.out = h->o;
+        if (mfma) { at.out_tiles = h->xp_o; at.out_tiles_lo = h->xl_o; } else at.out = h->o;
         if (hd == 32) launch_attn<WT, 32>(h, mi, at, m.H / m.KV, T, attn_bytes);
         else if (hd == 64) launch_attn<WT, 64>(h, mi, at, m.H / m.KV, T, attn_bytes);
         else launch_attn<WT, 128>(h, mi, at, m.H / m.KV, T, attn_bytes);
         // ---- output projection + residual ----
         LinArgs<WT> b{};
         b.W = (const WT *)ly.wo; b.Np = d; b.K = NQ; b.count = cnt; b.out = h->x; b.ldo = d;
-        if (mfma) { if constexpr (is_bf16) { b.xp = h->xp_o; launch_mfma<EPI_RES>(h, mi, b, d / 16); } }
+        if (mfma) { if constexpr (is_bf16) { b.xp = h->xp_o; b.xp_lo = h->xl_o; launch_mfma<EPI_RES>(h, mi, b, d / 16); } }
         else { b.x = h->o; b.ldx = NQ; launch_valu<WT, EPI_RES>(h, mi, b, T, d / 16); }
         // ---- RMSNorm + gate/up + SwiGLU ----
         LinArgs<WT> c{};
         c.W = (const WT *)ly.wgu; c.Np = 2 * F; c.K = d; c.count = cnt; c.ldo = F;
         if (mfma) {
             if constexpr (is_bf16) {
-                PackArgs pa{h->x, d, cnt, nullptr, ly.g_ffn, m.eps, h->xp_a, d};
+                PackArgs pa{h->x, d, cnt, nullptr, ly.g_ffn, m.eps, h->xp_a, h->xl_a, d};
                 { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa); }
-                c.xp = h->xp_a; c.out_tiles = h->xp_h; c.out_KC = F / 32;
+                c.xp = h->xp_a; c.xp_lo = h->xl_a; c.out_tiles = h->xp_h; c.out_tiles_lo = h->xl_h; c.out_KC = F / 32;
                 launch_mfma<EPI_SWIGLU>(h, mi, c, c.Np / 16);
             }
         } else {
@@ -459,7 +459,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         // ---- down projection + residual ----
         LinArgs<WT> e{};
         e.W = (const WT *)ly.wdown; e.Np = d; e.K = F; e.count = cnt; e.out = h->x; e.ldo = d;
-        if (mfma) { if constexpr (is_bf16) { e.xp = h->xp_h; launch_mfma<EPI_RES>(h, mi, e, d / 16); } }
+        if (mfma) { if constexpr (is_bf16) { e.xp = h->xp_h; e.xp_lo = h->xl_h; launch_mfma<EPI_RES>(h, mi, e, d / 16); } }
         else { e.x = h->hbuf; e.ldx = F; launch_valu<WT, EPI_RES>(h, mi, e, T, d / 16); }
     }
     if (n_lm > 0) {
@@ -470,9 +470,9 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         const int grid = std::min(m.V / 16, h->lm_grid);
         if (is_bf16 && n_lm > 4) {
             if constexpr (is_bf16) {
-                PackArgs pa{h->x, d, cnt + 1, h->plan.lm_row, m.g_final, m.eps, h->xp_a, d};
+                PackArgs pa{h->x, d, cnt + 1, h->plan.lm_row, m.g_final, m.eps, h->xp_a, h->xl_a, d};
                 { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3((n_lm + 15) & ~15), dim3(256), 0, st, pa); }
-                g.xp = h->xp_a;
+                g.xp = h->xp_a; g.xp_lo = h->xl_a;
                 launch_mfma<EPI_LOGITS>(h, mi, g, grid);
             }
         } else {
@@ -900,6 +900,10 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
         TRY(dmalloc(h, &h->x, T * dmax)); TRY(dmalloc(h, &h->q, T * qmax)); TRY(dmalloc(h, &h->o, T * qmax));
         TRY(dmalloc(h, &h->hbuf, T * fmax_));
         TRY(dmalloc(h, &h->xp_a, T * dmax)); TRY(dmalloc(h, &h->xp_o, T * qmax)); TRY(dmalloc(h, &h->xp_h, T * fmax_));
+        TRY(dmalloc(h, &h->xl_a, T * dmax)); TRY(dmalloc(h, &h->xl_o, T * qmax)); TRY(dmalloc(h, &h->xl_h, T * fmax_));
+        HIP_TRY(h, hipMemsetAsync(h->xl_a, 0, T * dmax * 2, h->stream));
+        HIP_TRY(h, hipMemsetAsync(h->xl_o, 0, T * qmax * 2, h->stream));
+        HIP_TRY(h, hipMemsetAsync(h->xl_h, 0, T * fmax_ * 2, h->stream));
         HIP_TRY(h, hipMemsetAsync(h->xp_a, 0, T * dmax * 2, h->stream));
         HIP_TRY(h, hipMemsetAsync(h->xp_o, 0, T * qmax * 2, h->stream));
         HIP_TRY(h, hipMemsetAsync(h->xp_h, 0, T * fmax_ * 2, h->stream));

@@ -26,14 +26,16 @@ struct LinArgs {
     const int *rowmap;      // optional: activation row r reads x[rowmap[r]] (LM head), else x[r]
     const float *x;         // fp32 activations [*, ldx]        (VALU path)
     int ldx;
-    const bf16_t *xp;       // bf16 activation tiles [ceil(rows/16)][K/32][64][8] (MFMA path)
+    const bf16_t *xp;       // bf16 activation tiles [ceil(rows/16)][K/32][64][8] (MFMA path): high parts
+    const bf16_t *xp_lo;    //   and low parts (activation = hi + lo)
     const float *gain;      // RMSNorm gain (VALU path prologue), null = no norm
     float eps;
     // outputs
     float *out;             // RES: residual stream [T, ldo] (+=); SWIGLU: h [T, ldo]; QKV: q [T, ldo]
     int ldo;
     const WT *res_embed;    // RES, optional: the residual is this embedding row instead of out (first layer)
-    bf16_t *out_tiles;      // SWIGLU, optional: h as bf16 tiles for the next MFMA layer
+    bf16_t *out_tiles;      // SWIGLU, optional: h as bf16 tiles (high parts) for the next MFMA layer
+    bf16_t *out_tiles_lo;   //   and low parts
     int out_KC;             //   K/32 of that consumer
     // QKV
     WT *kcache, *vcache;    // this layer's cache, [seq][kv_head][max_seq][hd]
@@ -72,7 +74,7 @@ __device__ __forceinline__ void epilogue(const LinArgs<WT> &a, int p, int t, flo
             if (a.out) put(a.out + (size_t)t * a.ldo + i, h, COH);
             if (a.out_tiles) {
                 size_t off = tile_offset(t >> 4, i >> 5, a.out_KC) + (size_t)(((t & 15) + 16 * ((i & 31) >> 3)) * 8 + (i & 7));
-                a.out_tiles[off].u = f32_to_bf16(h);
+                split_bf16(h, a.out_tiles[off].u, a.out_tiles_lo[off].u);
             }
         }
     } else if constexpr (EPI == EPI_QKV) {
@@ -258,7 +260,10 @@ __global__ __launch_bounds__(NW * 64) void k_linear_valu(LinArgs<WT> a) {
 
 // ------------------------------------------------------------------------------------
 // MFMA path (bf16).  Token rows are processed 64 at a time (four 16-column blocks of
-// the B operand, which is read as ready-made tiles); NW waves split K.
+// the B operand, which is read as ready-made tiles); NW waves split K.  Activations are
+// kept as hi + lo bf16 tile pairs (two MFMAs per weight tile): with bf16-rounded
+// activations alone the logits of a 32-layer model drift past 2 % of their range, and
+// the matrix cores have an order of magnitude of headroom at these widths.
 // ------------------------------------------------------------------------------------
 constexpr int kMfmaTokBlocks = 4;
 
@@ -282,6 +287,7 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma(LinArgs<bf16_t> a) {
             for (int b = 0; b < kMfmaTokBlocks; ++b) acc[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
             const bf16_t *wp = a.W + tile_offset(rb, kc0, KC) + lane * 8;
             const bf16_t *xp = a.xp + tile_offset(tb0, kc0, KC) + lane * 8;
+            const bf16_t *xl = a.xp_lo + tile_offset(tb0, kc0, KC) + lane * 8;
             const size_t xstride = (size_t)KC * 512;
             int kc = kc0;
             for (; kc + 2 <= kc1; kc += 2) {
@@ -290,27 +296,34 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma(LinArgs<bf16_t> a) {
 #pragma unroll
                 for (int b = 0; b < kMfmaTokBlocks; ++b) {
                     if (b < nb) {
-                        Vec8<bf16_t> x0, x1;
+                        Vec8<bf16_t> x0, x1, l0, l1;
                         x0.load(xp + b * xstride); x1.load(xp + b * xstride + 512);
+                        l0.load(xl + b * xstride); l1.load(xl + b * xstride + 512);
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf16x8_t, w0.raw), __builtin_bit_cast(bf16x8_t, l0.raw), acc[b], 0, 0, 0);
                         acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                             __builtin_bit_cast(bf16x8_t, w0.raw), __builtin_bit_cast(bf16x8_t, x0.raw), acc[b], 0, 0, 0);
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf16x8_t, w1.raw), __builtin_bit_cast(bf16x8_t, l1.raw), acc[b], 0, 0, 0);
                         acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                             __builtin_bit_cast(bf16x8_t, w1.raw), __builtin_bit_cast(bf16x8_t, x1.raw), acc[b], 0, 0, 0);
                     }
                 }
-                wp += 1024; xp += 1024;
+                wp += 1024; xp += 1024; xl += 1024;
             }
             for (; kc < kc1; ++kc) {
                 Vec8<bf16_t> w0; w0.load_stream(wp);
 #pragma unroll
                 for (int b = 0; b < kMfmaTokBlocks; ++b) {
                     if (b < nb) {
-                        Vec8<bf16_t> x0; x0.load(xp + b * xstride);
+                        Vec8<bf16_t> x0, l0; x0.load(xp + b * xstride); l0.load(xl + b * xstride);
+                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf16x8_t, w0.raw), __builtin_bit_cast(bf16x8_t, l0.raw), acc[b], 0, 0, 0);
                         acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
                             __builtin_bit_cast(bf16x8_t, w0.raw), __builtin_bit_cast(bf16x8_t, x0.raw), acc[b], 0, 0, 0);
                     }
                 }
-                wp += 512; xp += 512;
+                wp += 512; xp += 512; xl += 512;
             }
 #pragma unroll
             for (int b = 0; b < kMfmaTokBlocks; ++b)
@@ -348,7 +361,7 @@ struct PackArgs {
     const float *x; int ldx;
     const int *count; const int *rowmap;
     const float *gain; float eps;
-    bf16_t *out; int K;
+    bf16_t *out, *out_lo; int K;
 };
 
 __global__ __launch_bounds__(256) void k_pack_act(PackArgs a) {
@@ -382,7 +395,11 @@ __global__ __launch_bounds__(256) void k_pack_act(PackArgs a) {
             }
         }
         const size_t off = tile_offset(t >> 4, k >> 5, KC) + (size_t)(((t & 15) + 16 * ((k & 31) >> 3)) * 8);
-        store8<bf16_t>(a.out + off, f);
+        float hi[8], lo[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { hi[e] = bf16_to_f32(f32_to_bf16(f[e])); lo[e] = f[e] - hi[e]; }
+        store8<bf16_t>(a.out + off, hi);
+        store8<bf16_t>(a.out_lo + off, lo);
     }
 }
 

@@ -1,0 +1,139 @@
+"""Parity at the benchmark's full sizes and in its launch configuration.
+
+The oracle can afford a few positions of the full-depth Llama-shaped pair (its fp32 weights
+take 35 GB of host memory), so logits / entropy / arg max are compared there position by
+position; everything longer is checked through properties that hold at any size (catch-up
+invariance, batch independence) or on depth-truncated pairs (same widths, heads and vocab).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+TOL_LOGIT, TOL_H, BAND = 2e-2, 1e-2, 1e-2
+
+
+def _ead():
+    import paper_2502_06833_amd as ead
+    return ead
+
+
+@pytest.fixture(scope="module")
+def llama_full():
+    ead = _ead()
+    ss, sl = si.PAIRS["llama"]
+    Ws = si.model_weights_torch(ss, 0, "cuda")
+    Wl = si.model_weights_torch(sl, 0, "cuda")
+    e = ead.EAD(ss, Ws, sl, Wl, window=5, tau=0.0, d_min=10, max_batch=2, max_seq=640)
+    yield e, Ws, Wl
+    e.close()
+
+
+def test_llama_full_depth_sampled_positions_against_oracle(llama_full):
+    e, Ws, Wl = llama_full
+    ss, sl = si.PAIRS["llama"]
+    toks = si.prompt_np(0, "full", 5, ss.vocab)
+    for which, shape, W in ((0, ss, Ws), (1, sl, Wl)):
+        print(f"full-depth {shape.name}: oracle on {len(toks)} positions", flush=True)
+        om = oracle.Model(shape, {k: v.float().cpu().numpy() for k, v in W.items()})
+        ref = om.forward_dense(toks)
+        del om
+        for n in (len(toks), 3):                 # 5 rows: MFMA kernels; 3 rows: FMA kernels
+            out = e.score(which, toks[:n])
+            err = np.abs(out["logits"] - ref[:n]).max(axis=1) / np.abs(ref[:n]).max(axis=1)
+            Hr, ar = oracle.entropy_rows(ref[:n])
+            print(f"  rows={n}: logits rel err {err.max():.2e}, H err {np.abs(out['H'] - Hr).max():.2e}", flush=True)
+            assert err.max() < TOL_LOGIT
+            assert np.abs(out["H"] - Hr).max() < TOL_H
+            top2 = np.sort(ref[:n], axis=1)
+            clear = (top2[:, -1] - top2[:, -2]) > 2 * TOL_LOGIT * np.abs(ref[:n]).max(axis=1)
+            assert (out["argmax"][clear] == ar[clear]).all()
+        sigma = 0.02 * math.sqrt(shape.d_model)          # logits ~ N(0, sigma^2): H ~ ln V - sigma^2/2
+        assert abs(Hr.mean() - (math.log(shape.vocab) - sigma * sigma / 2)) < 0.1
+
+
+def test_llama_full_size_catchup_and_paths_agree(llama_full):
+    """512-token prompt, the benchmark's launch configuration: after 10 small-model tokens the
+    large model catches up (11 rows through the MFMA kernels); its entropy there equals the
+    one it gives when scoring the same tokens from scratch; the fused single-row kernel and
+    the per-layer kernels agree."""
+    e, _, _ = llama_full
+    ss, _ = si.PAIRS["llama"]
+    prompt = si.prompt_np(0, "row0", 512, ss.vocab)
+    e.set_gate(5, 0.0, 10)
+    outs = []
+    for fused in (False, True):
+        e.set_fused(fused)
+        outs.append(e.generate([prompt], 14))
+    e.set_fused(False)
+    a, b = outs
+    assert list(a["model_id"][0]) == [0] * 10 + [1] * 4
+    assert np.abs(a["H"] - b["H"]).max() < TOL_H
+    seq = np.concatenate([prompt, a["tokens"][0]])
+    sc = e.score(1, seq[:-1], want_logits=False)
+    for i in range(10, 14):
+        assert abs(sc["H"][512 + i - 1] - a["H"][0, i]) < TOL_H
+    st = e.stats()
+    assert st["tokens_small"] == 10 and st["tokens_large"] == 4
+
+
+def test_llama_full_size_batch_rows_independent(llama_full):
+    e, _, _ = llama_full
+    ss, _ = si.PAIRS["llama"]
+    prompts = [si.prompt_np(0, "row0", 300, ss.vocab), si.prompt_np(1, "row1", 77, ss.vocab)]
+    e.set_gate(5, 11.3526, 3)
+    both = e.generate(prompts, 12)
+    for b, p in enumerate(prompts):
+        one = e.generate([p], 12)
+        assert np.abs(one["H"][0] - both["H"][b]).max() < TOL_H
+
+
+def test_qwen_truncated_batch_with_ragged_prompts_and_catchups():
+    """Qwen-shaped widths (2 layers each), 8 rows with prompts of 5-40 tokens decoded together:
+    rows switch at different times, so small- and large-model rows mix within a step and each
+    row gets its own catch-up.  Four rows are checked against the oracle token by token."""
+    ead = _ead()
+    ss, sl = (s.truncated(2) for s in si.PAIRS["qwen"])
+    Ws = si.model_weights_torch(ss, 0, "cuda")
+    Wl = si.model_weights_torch(sl, 0, "cuda")
+    os_ = oracle.Model(ss, {k: v.float().cpu().numpy() for k, v in Ws.items()})
+    ol = oracle.Model(sl, {k: v.float().cpu().numpy() for k, v in Wl.items()})
+    B, n_new, d_min = 8, 20, 3
+    lens = si.prompt_lengths(3, B, 5, 40)
+    prompts = [si.prompt_np(3, f"q{b}", int(lens[b]), ss.vocab) for b in range(B)]
+    probe = oracle.generate(os_, ol, prompts[0], n_new, 5, 1e30, d_min=d_min)
+    tau = float(np.percentile(probe["Hbar"], 40))
+    checked = [0, 2, 5, 7]
+    refs = {b: oracle.generate(os_, ol, prompts[b], n_new, 5, tau, d_min=d_min) for b in checked}
+    print("large share per checked row:", [float(refs[b]["model_id"].mean()) for b in checked], flush=True)
+    e = ead.EAD(ss, Ws, sl, Wl, window=5, tau=tau, d_min=d_min, max_batch=B, max_seq=64)
+    free = e.generate(prompts, n_new)                    # mixed small/large rows, device-side decisions
+    st = e.stats()
+    assert st["tokens_small"] + st["tokens_large"] == B * n_new
+    assert st["catchup_rows_large"] > 0
+    # teacher-forced along the oracle trajectories (unchecked rows replay the GPU's own run)
+    ft = free["tokens"].copy(); fm = free["model_id"].copy()
+    for b in checked:
+        ft[b], fm[b] = refs[b]["tokens"], refs[b]["model_id"]
+    rp = e.replay(prompts, ft, fm)
+    n_dec = 0
+    for b in checked:
+        r = refs[b]
+        assert np.abs(rp["H"][b] - r["H"]).max() < TOL_H, b
+        assert np.abs(rp["Hbar"][b] - r["Hbar"]).max() < TOL_H, b
+        safe = np.abs(r["Hbar"] - tau) > BAND
+        want_next = np.concatenate([r["model_id"][1:], rp["next_model"][b][-1:]])
+        assert (rp["next_model"][b][safe] == want_next[safe]).all(), b
+        n_dec += int(safe.sum())
+    print(f"decisions checked outside the band: {n_dec}/{len(checked) * n_new}", flush=True)
+    # unchecked rows: replaying the GPU's own trajectory reproduces its entropies
+    for b in range(B):
+        if b not in checked:
+            assert np.abs(rp["H"][b] - free["H"][b]).max() < 2e-3
+    e.close()
