@@ -116,6 +116,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-single-model", action="store_true", help="skip the small-only / large-only runs")
     ap.add_argument("--profile-steps", type=int, default=64)
+    ap.add_argument("--fused", type=int, default=None, help="1/0: force the fused single-row decode kernel on/off")
     ap.add_argument("--tau", type=float, default=None, help="skip the calibration runs and use this threshold (nats)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for hardware byte counters)")
@@ -145,6 +146,8 @@ def main():
         del Ws, Wl
         torch.cuda.empty_cache()
     log(f"[bench] handle created at {time.time() - t0:.1f}s")
+    if args.fused is not None:
+        e.set_fused(bool(args.fused))
 
     if args.copy_probe:
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").fill_(1.0)

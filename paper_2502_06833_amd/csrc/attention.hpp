@@ -5,7 +5,8 @@
 // hd/8 lanes cover one key (8 elements = one 16-byte load each for bf16), so a wave
 // works on 64/(hd/8) keys per iteration, each lane group keeping its own online
 // soft-max state; groups are merged at the end, and key ranges (splits) are merged by
-// k_attn_combine.  Causality comes from the cache itself: row t reads keys 0..pos_t.
+// whichever split finishes last.  Causality comes from the cache itself: row t reads keys
+// 0..pos_t.
 #pragma once
 #include "common.hpp"
 
@@ -22,6 +23,7 @@ struct AttnArgs {
     float scale;               // 1/sqrt(hd)
     float *part_o;             // [T*H*max_splits][hd]   un-normalised
     float2 *part_ml;           // [T*H*max_splits]       (max, sum)
+    int *tickets;              // [T*n_kv_heads] arrival counters, zero between launches
     float *out;                // [T, H*hd] fp32 (optional)
     bf16_t *out_tiles;         // bf16 tiles (high parts) of [T, H*hd] for an MFMA consumer (optional)
     bf16_t *out_tiles_lo;      //   and low parts
@@ -40,15 +42,28 @@ __device__ __forceinline__ void attn_store(float *out, bf16_t *out_tiles, bf16_t
     }
 }
 
-// Keys are taken in chunks of NI * (64 / LPK): all K and V loads of a chunk are issued
-// before any arithmetic, scores of the chunk are formed, one rescale is applied per chunk
-// and then the values are accumulated.  A row whose whole context fits one split is
-// finished here; otherwise k_attn_combine merges the splits.
+// A workgroup of kAttnWaves waves handles one (token row, KV head, key split).  Its waves take
+// the split's keys in chunks of NI * (64 / LPK): all K and V loads of a chunk are issued before
+// any arithmetic, scores of the chunk are formed, one rescale is applied per chunk and then
+// the values are accumulated.  The waves meet in LDS.  With a single split (the usual case:
+// the host makes a split cover at least 512 keys) the workgroup normalises and writes the
+// output.  Otherwise it leaves an un-normalised partial, written through to memory
+// (st_coherent), and the workgroup that arrives last (ticket counter per (row, KV head))
+// merges the partials with coherent loads, so neither a second launch nor a cache
+// write-back / invalidate is needed -- only completion of the stores before the ticket is
+// taken.  The counter is left at zero for the next launch.
+constexpr int kAttnWaves = 8;
+constexpr int kAttnMaxSplits = 16;
+
 template <typename KT, int HD, int G>
-__global__ __launch_bounds__(64) void k_attn(AttnArgs<KT> a) {
+__global__ __launch_bounds__(kAttnWaves * 64) void k_attn(AttnArgs<KT> a) {
     constexpr int LPK = HD / 8;        // lanes per key
     constexpr int KPI = 64 / LPK;      // keys per load instruction
     constexpr int NI = 8;              // load instructions per chunk
+    constexpr int CH = NI * KPI;
+    __shared__ float s_o[kAttnWaves][G][HD];
+    __shared__ float s_m[kAttnWaves][G], s_l[kAttnWaves][G];
+    __shared__ int s_ticket;
     const int t = blockIdx.z;
     if (t >= *a.count) return;
     const int kvh = blockIdx.y, split = blockIdx.x;
@@ -57,7 +72,7 @@ __global__ __launch_bounds__(64) void k_attn(AttnArgs<KT> a) {
     if (k0 >= nkeys) return;
     const int k1 = min(k0 + a.chunk, nkeys);
     const int nsplit = (nkeys + a.chunk - 1) / a.chunk;
-    const int lane = threadIdx.x, slot = lane / LPK, dl = lane % LPK;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, slot = lane / LPK, dl = lane % LPK;
     const int H = a.n_heads;
 
     float qv[G][8];
@@ -78,7 +93,7 @@ __global__ __launch_bounds__(64) void k_attn(AttnArgs<KT> a) {
     const size_t base = ((size_t)a.row_seq[t] * a.n_kv_heads + kvh) * (size_t)a.max_seq * HD;
     const KT *kb = a.kcache + base + dl * 8, *vb = a.vcache + base + dl * 8;
 
-    for (int c0 = k0; c0 < k1; c0 += NI * KPI) {
+    for (int c0 = k0 + wave * CH; c0 < k1; c0 += kAttnWaves * CH) {
         Vec8<KT> kx[NI], vx[NI];
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
@@ -147,49 +162,75 @@ __global__ __launch_bounds__(64) void k_attn(AttnArgs<KT> a) {
             m[g] = M;
         }
     }
-    if (nsplit == 1) {                     // whole context in one split: finish here
-        if (slot == 0) {
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float r = 1.f / l[g];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, (kvh * G + g) * HD + dl * 8 + e, o[g][e] * r);
-            }
-        }
-        return;
-    }
+    // the waves meet in LDS
     if (slot == 0) {
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const size_t item = ((size_t)t * H + (kvh * G + g)) * a.max_splits + split;
-            float *po = a.part_o + item * HD + dl * 8;
-            *reinterpret_cast<float4 *>(po) = make_float4(o[g][0], o[g][1], o[g][2], o[g][3]);
-            *reinterpret_cast<float4 *>(po + 4) = make_float4(o[g][4], o[g][5], o[g][6], o[g][7]);
-            if (dl == 0) a.part_ml[item] = make_float2(m[g], l[g]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s_o[wave][g][dl * 8 + e] = o[g][e];
+            if (dl == 0) { s_m[wave][g] = m[g]; s_l[wave][g] = l[g]; }
         }
     }
-}
-
-// One workgroup of HD threads per (head, token row): merge the splits (rows whose context
-// fits one split were finished by k_attn itself).
-template <typename KT, int HD>
-__global__ __launch_bounds__(HD) void k_attn_combine(AttnArgs<KT> a) {
-    const int t = blockIdx.y;
-    if (t >= *a.count) return;
-    const int h = blockIdx.x, d = threadIdx.x, H = a.n_heads;
-    const int nsplit = (a.row_pos[t] + a.chunk) / a.chunk;       // ceil((pos+1)/chunk)
-    if (nsplit == 1) return;
-    const size_t item0 = ((size_t)t * H + h) * a.max_splits;
-    float M = kNegBig;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, a.part_ml[item0 + s].x);
-    float L = 0.f, acc = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-        const float2 ml = a.part_ml[item0 + s];
-        const float c = __expf(ml.x - M);
-        L += ml.y * c;
-        acc += a.part_o[(item0 + s) * HD + d] * c;
+    __syncthreads();
+    float M_[(G * HD + kAttnWaves * 64 - 1) / (kAttnWaves * 64)], L_[(G * HD + kAttnWaves * 64 - 1) / (kAttnWaves * 64)],
+          O_[(G * HD + kAttnWaves * 64 - 1) / (kAttnWaves * 64)];
+    int n_e = 0;
+    for (int e = tid; e < G * HD; e += kAttnWaves * 64, ++n_e) {
+        const int g = e / HD, dd = e % HD;
+        float M = kNegBig;
+#pragma unroll
+        for (int w = 0; w < kAttnWaves; ++w) M = fmaxf(M, s_m[w][g]);
+        float L = 0.f, acc = 0.f;
+#pragma unroll
+        for (int w = 0; w < kAttnWaves; ++w) {
+            const float c = __expf(s_m[w][g] - M);
+            L += s_l[w][g] * c;
+            acc += s_o[w][g][dd] * c;
+        }
+        M_[n_e] = M; L_[n_e] = L; O_[n_e] = acc;
+        const int h = kvh * G + g;
+        if (nsplit == 1) attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, h * HD + dd, acc / L);
+        else {
+            const size_t item = ((size_t)t * H + h) * a.max_splits + split;
+            st_coherent(a.part_o + item * HD + dd, acc);
+            if (dd == 0) {
+                float *ml = reinterpret_cast<float *>(a.part_ml + item);
+                st_coherent(ml, M); st_coherent(ml + 1, L);
+            }
+        }
     }
-    attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, h * HD + d, acc / L);
+    if (nsplit == 1) return;
+    wait_stores();
+    __syncthreads();
+    int *tk = a.tickets + t * a.n_kv_heads + kvh;
+    if (tid == 0) s_ticket = __hip_atomic_fetch_add(tk, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_ticket != nsplit - 1) return;
+    if (tid == 0) st_coherent(tk, 0);
+    for (int e = tid; e < G * HD; e += kAttnWaves * 64) {
+        const int g = e / HD, dd = e % HD, h = kvh * G + g;
+        const size_t item0 = ((size_t)t * H + h) * a.max_splits;
+        float mm[kAttnMaxSplits], ll[kAttnMaxSplits], oo[kAttnMaxSplits];
+#pragma unroll
+        for (int sp = 0; sp < kAttnMaxSplits; ++sp) {
+            if (sp < nsplit) {
+                const float *ml = reinterpret_cast<const float *>(a.part_ml + item0 + sp);
+                mm[sp] = ld_coherent(ml); ll[sp] = ld_coherent(ml + 1);
+                oo[sp] = ld_coherent(a.part_o + (item0 + sp) * HD + dd);
+            } else { mm[sp] = kNegBig; ll[sp] = 0.f; oo[sp] = 0.f; }
+        }
+        float M = kNegBig;
+#pragma unroll
+        for (int sp = 0; sp < kAttnMaxSplits; ++sp) M = fmaxf(M, mm[sp]);
+        float L = 0.f, acc = 0.f;
+#pragma unroll
+        for (int sp = 0; sp < kAttnMaxSplits; ++sp) {
+            const float c = __expf(mm[sp] - M);
+            L += ll[sp] * c;
+            acc += oo[sp] * c;
+        }
+        attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, h * HD + dd, acc / L);
+    }
 }
 
 }  // namespace ead

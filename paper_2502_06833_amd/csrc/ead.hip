@@ -153,11 +153,11 @@ struct ead_handle {
     Model mdl[2];
     ead_params prm;
     hipStream_t stream;
-    int Tmax, items_max, lm_grid, score_rows;
+    int Tmax, items_max, lm_grid, score_rows, n_cu = 256;
     SeqState s; Plan plan; GateCfg cfg;
     // scratch
     float *x, *q, *o, *hbuf; bf16_t *xp_a, *xp_o, *xp_h, *xl_a, *xl_o, *xl_h;
-    float *part_o; float2 *part_ml; EntPartial *lm_part; float *logits_dump; float *sc_H; int *sc_arg;
+    float *part_o; float2 *part_ml; int *tickets; EntPartial *lm_part; float *logits_dump; float *sc_H; int *sc_arg;
     int *h_model, *h_done;   // pinned
     // fused single-row decode
     long long *trace = nullptr;
@@ -375,14 +375,10 @@ void launch_attn(ead_handle *h, int mi, AttnArgs<KT> &a, int G, int T, double kv
     dim3 grid(a.max_splits, a.n_kv_heads, T);
     {
         ProfScope ps(h, PK_ATTN_PARTIAL, mi, kv_bytes);
-#define EAD_LA(G_) hipLaunchKernelGGL((k_attn<KT, HD, G_>), grid, dim3(64), 0, h->stream, a)
+#define EAD_LA(G_) hipLaunchKernelGGL((k_attn<KT, HD, G_>), grid, dim3(kAttnWaves * 64), 0, h->stream, a)
         switch (G) { case 1: EAD_LA(1); break; case 2: EAD_LA(2); break; case 4: EAD_LA(4); break;
                      case 5: EAD_LA(5); break; case 7: EAD_LA(7); break; default: EAD_LA(8); break; }
 #undef EAD_LA
-    }
-    if (a.max_splits > 1) {
-        ProfScope ps(h, PK_ATTN_COMBINE, mi, 0.0);
-        hipLaunchKernelGGL((k_attn_combine<KT, HD>), dim3(a.n_heads, T), dim3(HD), 0, h->stream, a);
     }
 }
 
@@ -404,8 +400,11 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
     }
     const double attn_bytes = keys_read * 2.0 * NK * sizeof(WT);
     // attention split: enough waves to fill the chip, bounded scratch
-    int chunk = 8 * (64 / (hd / 8));          // one register-resident chunk of keys per wave at least
-    while ((long)ctx_max * T * m.KV / chunk > 4096 && chunk < 4096) chunk <<= 1;
+    // attention split: a workgroup (8 waves) takes at least 512 keys; more splits only while
+    // that helps to fill the chip, never more than 16 (the last one merges them all)
+    int chunk = 512;
+    while ((long)T * m.KV * ((ctx_max + chunk - 1) / chunk) > 1024 && chunk < 65536) chunk <<= 1;
+    while ((ctx_max + chunk - 1) / chunk > kAttnMaxSplits) chunk <<= 1;
     while ((long)T * ((ctx_max + chunk - 1) / chunk) > h->items_max) chunk <<= 1;
     const int max_splits = (ctx_max + chunk - 1) / chunk;
 
@@ -432,7 +431,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         at.q = h->q; at.kcache = (const WT *)ly.kcache; at.vcache = (const WT *)ly.vcache; at.count = cnt;
         at.row_seq = h->plan.row_seq; at.row_pos = h->plan.row_pos; at.n_heads = m.H; at.n_kv_heads = m.KV;
         at.max_seq = h->s.max_seq; at.chunk = chunk; at.max_splits = max_splits; at.scale = 1.0f / sqrtf((float)hd);
-        at.part_o = h->part_o; at.part_ml = h->part_ml;
+        at.part_o = h->part_o; at.part_ml = h->part_ml; at.tickets = h->tickets;
         if (mfma) { at.out_tiles = h->xp_o; at.out_tiles_lo = h->xl_o; } else at.out = h->o;
         if (hd == 32) launch_attn<WT, 32>(h, mi, at, m.H / m.KV, T, attn_bytes);
         else if (hd == 64) launch_attn<WT, 64>(h, mi, at, m.H / m.KV, T, attn_bytes);
@@ -454,7 +453,8 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
             }
         } else {
             c.x = h->x; c.ldx = d; c.gain = ly.g_ffn; c.eps = m.eps; c.out = h->hbuf;
-            launch_valu<WT, EPI_SWIGLU>(h, mi, c, T, c.Np / 16);
+            // two resident workgroups per CU stride over the row blocks: activations are staged once
+            launch_valu<WT, EPI_SWIGLU>(h, mi, c, T, std::min(c.Np / 16, 2 * h->n_cu));
         }
         // ---- down projection + residual ----
         LinArgs<WT> e{};
@@ -908,6 +908,8 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
         HIP_TRY(h, hipMemsetAsync(h->xp_o, 0, T * qmax * 2, h->stream));
         HIP_TRY(h, hipMemsetAsync(h->xp_h, 0, T * fmax_ * 2, h->stream));
         TRY(dmalloc(h, &h->part_o, (size_t)h->items_max * qmax)); TRY(dmalloc(h, &h->part_ml, (size_t)h->items_max * std::max(a.H, b.H)));
+        TRY(dmalloc(h, &h->tickets, (size_t)h->Tmax * std::max(a.KV, b.KV)));
+        HIP_TRY(h, hipMemsetAsync(h->tickets, 0, (size_t)h->Tmax * std::max(a.KV, b.KV) * sizeof(int), h->stream));
         TRY(dmalloc(h, &h->lm_part, std::max((size_t)std::max<size_t>(MB, h->score_rows) * h->lm_grid, (size_t)256 * kFusedRbChunk)));
         TRY(dmalloc(h, &h->logits_dump, (size_t)h->score_rows * a.V));
         TRY(dmalloc(h, &h->sc_H, (size_t)MS)); TRY(dmalloc(h, &h->sc_arg, (size_t)MS));
@@ -923,6 +925,7 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
             int dev = 0; hipDeviceProp_t prop;
             HIP_TRY(h, hipGetDevice(&dev)); HIP_TRY(h, hipGetDeviceProperties(&prop, dev));
             h->fused_grid = std::min(256, prop.multiProcessorCount);
+            h->n_cu = prop.multiProcessorCount;
             for (int mi = 0; mi < 2; ++mi) {
                 Model &md = h->mdl[mi];
                 void *fn = fused_kernel_for(md);

@@ -3,11 +3,11 @@
 // At batch 1 a decoder layer is five dependent, bandwidth-bound phases of a few
 // microseconds each (QKV, attention, output projection, gate/up, down).  Launching them
 // as separate kernels leaves HBM idle at every boundary.  Here 256 workgroups (one per
-// CU, 16 waves each) stay resident for the whole step and meet at grid barriers instead;
-// every wave reads its weight tiles through a cursor that issues the next 8-tile group as
-// soon as the previous one has been multiplied and that does not stop at a barrier, so the
-// next phase's weights are already in flight (16 waves x 8 KB per CU) while the grid
-// synchronises and the activations are re-staged.
+// CU, 8 waves each) stay resident for the whole step and meet at grid barriers instead;
+// every wave keeps two 8-tile groups of its weight stream in flight (two register buffers
+// that take turns) and the stream does not stop at a barrier, so the next phase's weights
+// are already on their way (8 waves x 16 KB per CU) while the grid synchronises and the
+// activations are re-staged.
 // The cursor pauses only in front of the attention phase (whose inputs are the K/V
 // cache, not weights).
 //
@@ -27,7 +27,7 @@ namespace ead {
 #define EAD_TS(slot) do {} while (0)
 #endif
 
-constexpr int kFusedWaves = 16;
+constexpr int kFusedWaves = 8;
 constexpr int kFusedThreads = kFusedWaves * 64;
 constexpr long kFusedSpinLimit = 1L << 21;
 constexpr int kFusedMaxSplits = 8;
@@ -109,9 +109,9 @@ struct FusedArgs {
 
 // ---- staging the activation vector of a phase into LDS ----------------------------------------
 // Right after a grid barrier every one of these loads misses the caches, so all loads of a
-// thread are issued before the first use (K <= 16384: at most 16 per thread).  Vectors
+// thread are issued before the first use (K <= 16384: at most 32 per thread).  Vectors
 // written by other workgroups during this kernel are read with ld_coherent.
-constexpr int kStageElems = 16;      // elements per thread: K <= 16 * 1024
+constexpr int kStageElems = 32;      // elements per thread: K <= 32 * 512
 
 __device__ __forceinline__ void stage_norm(float *xs, float *s_red, const float *src, int K, const float *gain, float eps) {
     const int tid = threadIdx.x;
@@ -201,19 +201,25 @@ __device__ __forceinline__ void stage_attn(float *xs, const float *att_o, const 
 }
 
 // ---- one linear phase --------------------------------------------------------------------------
-// The weight stream of a wave is the concatenation, over the matrices of the step, of its
-// K-slice of the row blocks wg, wg+G, ...  It is read in groups of U tiles.  `cur` always
-// holds the wave's next group, requested from memory as soon as the previous one had been
-// multiplied -- also across the end of a matrix, so that the first group of the next
-// phase is in flight while the grid synchronises.  All control here is wave-uniform and
-// the loads are unconditional (tiles past the end of a slice re-read its last tile and
-// are multiplied with zeros), which keeps the loop free of branches.
+// The weight stream of a wave is the concatenation, over the matrices of the step in which
+// its workgroup owns row blocks, of its K-slice of the row blocks wg, wg+G, ...  It is read
+// in groups of U tiles.  Two register buffers take turns: while one group is multiplied the
+// other is in flight, and as soon as a group has been multiplied the group after next is
+// requested into the same registers -- also across the end of a matrix, so that the first
+// two groups of the next phase are on their way while the grid synchronises.  Control is
+// wave-uniform and the loads are unconditional (tiles past the end of a slice re-read its
+// last tile and meet zeros), which keeps a group step free of branches around the loads.
 template <typename WT>
 struct WaveSlice {                   // this wave's share of one matrix
     const WT *W; int NB, KC, kc0, kc1, ng;
     __device__ __forceinline__ void set(const FusedMat<WT> &m, int wave) {
         constexpr int U = sizeof(WT) == 2 ? 8 : 4;
-        W = m.W; NB = m.NB; KC = m.KC;
+        // descriptors come from LDS: tell the compiler they are the same in every lane
+        const uint64_t w = (uint64_t)m.W;
+        const uint32_t w_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(w >> 32));
+        const uint32_t w_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)w);   // no sign extension
+        W = (const WT *)(((uint64_t)w_hi << 32) | (uint64_t)w_lo);
+        NB = __builtin_amdgcn_readfirstlane(m.NB); KC = __builtin_amdgcn_readfirstlane(m.KC);
         kc0 = (wave * KC) / kFusedWaves; kc1 = ((wave + 1) * KC) / kFusedWaves;
         ng = ((KC + kFusedWaves - 1) / kFusedWaves + U - 1) / U;
     }
@@ -229,11 +235,99 @@ __device__ __forceinline__ void issue_group(Vec8<WT> (&buf)[U], const WT *W, int
     }
 }
 
+// Walks the wave's stream two groups ahead of the arithmetic.
+template <typename WT>
+struct IssueCursor {
+    static constexpr int U = sizeof(WT) == 2 ? 8 : 4;
+    const FusedMat<WT> *mats; int n_mats, im, wave, lane;
+    WaveSlice<WT> s; int rb, gi;
+    bool none, done;                 // none: no matrix has a row block for this workgroup
+    __device__ __forceinline__ int next_owned(int j) const {
+        while (j < n_mats && (int)blockIdx.x >= __builtin_amdgcn_readfirstlane(mats[j].NB)) ++j;
+        return j;
+    }
+    __device__ __forceinline__ void init(const FusedMat<WT> *m, int n, int wave_, int lane_) {
+        mats = m; n_mats = n; wave = wave_; lane = lane_; done = false;
+        im = next_owned(0); none = im >= n_mats;
+        if (!none) { s.set(mats[im], wave); rb = blockIdx.x; gi = 0; }
+    }
+    __device__ __forceinline__ void issue(Vec8<WT> (&buf)[U]) {
+        if (none) return;
+        issue_group<WT, U>(buf, s.W, s.KC, rb, s.kc0 + gi * U, s.kc1, lane);
+        if (done) return;                                   // past the end: keep re-reading the last group
+        if (++gi == s.ng) {
+            gi = 0; rb += gridDim.x;
+            if (rb >= s.NB) {
+                const int j = next_owned(im + 1);
+                if (j < n_mats) { im = j; s.set(mats[j], wave); rb = blockIdx.x; }
+                else { done = true; rb -= gridDim.x; gi = s.ng - 1; }
+            }
+        }
+    }
+};
+
+// One group step: multiply the group in `buf`, then request the group after next into it.
+template <typename WT, int U>
+__device__ __forceinline__ float group_step(Vec8<WT> (&buf)[U], IssueCursor<WT> &ic, const float *xq, const float *xzero,
+                                            int kc, int kc1) {
+    float part = 0.f;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        float wf[8];
+        buf[u].unpack(wf);
+        const float *xp = (kc + u < kc1) ? xq + (kc + u) * 32 : xzero;
+        const float4 x0 = *reinterpret_cast<const float4 *>(xp);
+        const float4 x1 = *reinterpret_cast<const float4 *>(xp + 4);
+        part += wf[0] * x0.x + wf[1] * x0.y + wf[2] * x0.z + wf[3] * x0.w
+              + wf[4] * x1.x + wf[5] * x1.y + wf[6] * x1.z + wf[7] * x1.w;
+    }
+    // neither the scheduler nor code sinking may move the refill above the arithmetic (it
+    // would need a third buffer): pin the sum here
+    asm volatile("" : "+v"(part));
+    __builtin_amdgcn_sched_barrier(0);
+    ic.issue(buf);
+    __builtin_amdgcn_sched_barrier(0);
+    return part;
+}
+
+// The groups of up to kFusedRbChunk row blocks; X holds the first group, Y the second.
+// Returns true when an odd number of groups was taken (the buffers have swapped roles).
+template <typename WT>
+__device__ __forceinline__ bool chunk_groups(Vec8<WT> (&X)[sizeof(WT) == 2 ? 8 : 4], Vec8<WT> (&Y)[sizeof(WT) == 2 ? 8 : 4],
+                                             IssueCursor<WT> &ic, const WaveSlice<WT> &cs, int nin, const float *xq,
+                                             const float *xzero, float *red, int wave, int lane) {
+    constexpr int U = sizeof(WT) == 2 ? 8 : 4;
+    const int n = nin * cs.ng;
+    int gi = 0, slot = 0, i = 0;
+    float acc = 0.f;
+    auto end_of_group = [&]() {
+        if (++gi == cs.ng) {                 // last group of a row block: leave the partial sums in LDS
+            gi = 0;
+            acc += __shfl_xor(acc, 16, kWave);
+            acc += __shfl_xor(acc, 32, kWave);
+            if (lane < 16) red[(slot * kFusedWaves + wave) * 16 + lane] = acc;
+            acc = 0.f; ++slot;
+        }
+    };
+    for (; i + 2 <= n; i += 2) {
+        acc += group_step<WT, U>(X, ic, xq, xzero, cs.kc0 + gi * U, cs.kc1);
+        end_of_group();
+        acc += group_step<WT, U>(Y, ic, xq, xzero, cs.kc0 + gi * U, cs.kc1);
+        end_of_group();
+    }
+    if (i < n) {
+        acc += group_step<WT, U>(X, ic, xq, xzero, cs.kc0 + gi * U, cs.kc1);
+        end_of_group();
+        return true;
+    }
+    return false;
+}
+
 template <typename WT>
 __device__ __forceinline__ void fused_linear(const LinArgs<WT> &a, int epi, const float *xs, const float *xzero,
-                                             float *red, const WaveSlice<WT> &cs, const WaveSlice<WT> &ns,
-                                             Vec8<WT> (&cur)[sizeof(WT) == 2 ? 8 : 4], EntStat &st) {
-    constexpr int U = sizeof(WT) == 2 ? 8 : 4;
+                                             float *red, const WaveSlice<WT> &cs, IssueCursor<WT> &ic,
+                                             Vec8<WT> (&A)[sizeof(WT) == 2 ? 8 : 4], Vec8<WT> (&B)[sizeof(WT) == 2 ? 8 : 4],
+                                             int &par, EntStat &st) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 4;
     const int G = gridDim.x;
     const float *xq = xs + g * 8;
@@ -241,46 +335,10 @@ __device__ __forceinline__ void fused_linear(const LinArgs<WT> &a, int epi, cons
     // and moves on, and the workgroup synchronises once per chunk, so the waves of a CU
     // drift apart and keep their loads evenly in flight.
     for (int rb0 = blockIdx.x; rb0 < cs.NB; rb0 += G * kFusedRbChunk) {
-        int nin = 0;
-        for (int i = 0; i < kFusedRbChunk; ++i) {
-            const int rb = rb0 + i * G;
-            if (rb >= cs.NB) break;
-            ++nin;
-            float acc = 0.f;
-            for (int gi = 0; gi < cs.ng; ++gi) {
-                const int kc = cs.kc0 + gi * U;
-                float part = 0.f;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    float wf[8];
-                    cur[u].unpack(wf);
-                    const float *xp = (kc + u < cs.kc1) ? xq + (kc + u) * 32 : xzero;
-                    const float4 x0 = *reinterpret_cast<const float4 *>(xp);
-                    const float4 x1 = *reinterpret_cast<const float4 *>(xp + 4);
-                    part += wf[0] * x0.x + wf[1] * x0.y + wf[2] * x0.z + wf[3] * x0.w
-                          + wf[4] * x1.x + wf[5] * x1.y + wf[6] * x1.z + wf[7] * x1.w;
-                    // keep the scheduler from hoisting every LDS read above the arithmetic
-                    if (u & 1) __builtin_amdgcn_sched_barrier(0);
-                }
-                acc += part;
-                // request the wave's next group: same row block, next row block, or the first
-                // group of the next matrix (ns == cs when there is none: a harmless re-read).
-                // Selects, not branches: one basic block per group keeps loads behind the FMAs.
-                const bool same_rb = gi + 1 < cs.ng;
-                const bool in_mat = same_rb || rb + G < cs.NB;
-                const WT *nW = in_mat ? cs.W : ns.W;
-                const int nKC = in_mat ? cs.KC : ns.KC;
-                const int nrb = in_mat ? (same_rb ? rb : rb + G) : (int)blockIdx.x;
-                const int nkc = in_mat ? (same_rb ? kc + U : cs.kc0) : ns.kc0;
-                const int nk1 = in_mat ? cs.kc1 : ns.kc1;
-                __builtin_amdgcn_sched_barrier(0);
-                issue_group<WT, U>(cur, nW, nKC, nrb, nkc, nk1, lane);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            acc += __shfl_xor(acc, 16, kWave);
-            acc += __shfl_xor(acc, 32, kWave);
-            if (lane < 16) red[(i * kFusedWaves + wave) * 16 + lane] = acc;
-        }
+        const int nin = min(kFusedRbChunk, (cs.NB - rb0 + G - 1) / G);
+        const bool flipped = par ? chunk_groups<WT>(B, A, ic, cs, nin, xq, xzero, red, wave, lane)
+                                 : chunk_groups<WT>(A, B, ic, cs, nin, xq, xzero, red, wave, lane);
+        par ^= flipped ? 1 : 0;
         __syncthreads();
         if (tid < 16 * nin) {
             const int i = tid >> 4, j = tid & 15;
@@ -426,15 +484,13 @@ __global__ __launch_bounds__(kFusedThreads) void k_decode_fused(FusedArgs<WT> a)
     for (int i = tid; i < a.n_mats; i += kFusedThreads) s_mats[i] = a.mats[i];
     if (tid < 64) xzero[tid] = 0.f;
     __syncthreads();
-    // index of the first matrix at or after i in which this workgroup owns a row block
-    auto next_mat = [&](int i) { while (i < a.n_mats && (int)blockIdx.x >= s_mats[i].NB) ++i; return i; };
-    Vec8<WT> cur[U];
-    WaveSlice<WT> cs, ns;
-    int cm = next_mat(0);                       // matrix whose first group `cur` holds
-    if (cm < a.n_mats) {
-        cs.set(s_mats[cm], wave);
-        issue_group<WT, U>(cur, cs.W, cs.KC, blockIdx.x, cs.kc0, cs.kc1, lane);
-    }
+    IssueCursor<WT> ic;
+    ic.init(s_mats, a.n_mats, wave, lane);
+    Vec8<WT> A[U], B[U];
+    int par = 0;                                // 0: the next group to multiply is in A
+    ic.issue(A);
+    ic.issue(B);
+    WaveSlice<WT> cs;
 
     // the one sequence this model serves in this step, and its newest position
     if (tid == 0) {
@@ -499,11 +555,9 @@ __global__ __launch_bounds__(kFusedThreads) void k_decode_fused(FusedArgs<WT> a)
         }
         EAD_TS(1);
         const int mat = ph < 5 * a.L ? 4 * l + (kind == 0 ? 0 : kind - 1) : 4 * a.L;
-        if (mat == cm) {                        // this workgroup has row blocks in this matrix
-            const int nm = next_mat(mat + 1);
-            if (nm < a.n_mats) ns.set(s_mats[nm], wave); else ns = cs;
-            fused_linear<WT>(p, epi, xs, xzero, red, cs, ns, cur, st);
-            cs = ns; cm = nm;
+        if ((int)blockIdx.x < __builtin_amdgcn_readfirstlane(s_mats[mat].NB)) {     // this workgroup has row blocks here
+            cs.set(s_mats[mat], wave);
+            fused_linear<WT>(p, epi, xs, xzero, red, cs, ic, A, B, par, st);
         }
         EAD_TS(1);
         if (kind == 5 && tid < 16 * kFusedRbChunk) {      // one partial per (workgroup, chunk slot)
