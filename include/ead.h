@@ -196,6 +196,16 @@ ead_status ead_gate_step_logits(ead_gate *g, const void *logits_dev, int32_t dty
                                 int32_t unit, float *H_dev, int32_t *argmax_dev,
                                 uint8_t *model_id_dev, float *window_mean_dev,
                                 uint8_t *next_model_dev);
+/* The same for n_steps consecutive steps without returning to the host: step s reads the
+ * tensor logits_dev_list[s % n_tensors] (a HOST array of device pointers, each
+ * [rows, vocab] of `dtype`).  Entropies of several steps are computed per launch; the
+ * window and the switch rule then take the steps in order.  Outputs (nullable device
+ * pointers) are [n_steps, rows]: H_dev, argmax_dev, model_id_dev (model current for that
+ * step's token), window_mean_dev.  Asynchronous on the gate's stream. */
+ead_status ead_gate_run_logits(ead_gate *g, const void *const *logits_dev_list, int32_t n_tensors,
+                               int32_t n_steps, int32_t dtype, int32_t vocab, int32_t unit,
+                               float *H_dev, int32_t *argmax_dev, uint8_t *model_id_dev,
+                               float *window_mean_dev);
 ead_status ead_gate_reset(ead_gate *g);
 void ead_gate_destroy(ead_gate *g);
 

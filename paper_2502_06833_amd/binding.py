@@ -74,6 +74,8 @@ _SIGNATURES = {
     "ead_gate_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "ead_gate_step_logits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "ead_gate_run_logits": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                      C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "ead_gate_reset": (C.c_int, [C.c_void_p]),
     "ead_gate_destroy": (None, [C.c_void_p]),
     "ead_get_stats": (C.c_int, [C.c_void_p, C.POINTER(Stats)]),
@@ -313,6 +315,24 @@ class Gate:
         if rc:
             raise EadError(rc, (lib().ead_last_error(None) or b"").decode())
         return self.H, self.argmax, self.model_id, self.window_mean, self.next_model
+
+    def run_logits(self, tensors, n_steps, unit=NATS, want_outputs=True):
+        """n_steps steps; step s reads tensors[s % len(tensors)].  Returns (H, argmax, model_id, window_mean),
+        each [n_steps, rows] on the GPU (None when want_outputs is False)."""
+        import torch
+        arr = (C.c_void_p * len(tensors))(*[t.data_ptr() for t in tensors])
+        outs = (None, None, None, None)
+        if want_outputs:
+            outs = (torch.empty((n_steps, self.rows), dtype=torch.float32, device="cuda"),
+                    torch.empty((n_steps, self.rows), dtype=torch.int32, device="cuda"),
+                    torch.empty((n_steps, self.rows), dtype=torch.uint8, device="cuda"),
+                    torch.empty((n_steps, self.rows), dtype=torch.float32, device="cuda"))
+        ptr = [o.data_ptr() if o is not None else None for o in outs]
+        rc = lib().ead_gate_run_logits(self._g, arr, len(tensors), n_steps, _dtype_code(tensors[0]), tensors[0].shape[1],
+                                       unit, *ptr)
+        if rc:
+            raise EadError(rc, (lib().ead_last_error(None) or b"").decode())
+        return outs
 
     def reset(self):
         lib().ead_gate_reset(self._g)

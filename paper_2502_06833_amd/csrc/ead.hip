@@ -777,15 +777,19 @@ constexpr int kEntMaxRows = 4096, kEntMaxChunks = 64;
 EntPartial *g_ent_scratch[16] = {nullptr};
 
 template <typename T>
-void launch_entropy_partial(const void *logits, int rows, int V, EntPartial *part, int *n_chunks, hipStream_t st) {
+void launch_entropy_partial(const void *logits, int rows, int V, EntPartial *part, int *n_chunks, hipStream_t st,
+                            const void *const *list = nullptr, int list_n = 0, int list_first = 0, int steps = 1) {
     const int nvec = V / 8;
-    int chunks = std::max(1, std::min(kEntMaxChunks, 2048 / std::max(rows, 1)));
-    chunks = std::min(chunks, std::max(1, nvec / 256));
+    // long chunks (up to 8 vectors per thread) amortise the per-workgroup merge; shorter ones
+    // only when there would otherwise be too few workgroups to fill the chip
+    int chunks = std::max(1, (nvec + 2047) / 2048);
+    while ((long)chunks * rows * steps < 1024 && chunks < kEntMaxChunks && nvec / (chunks * 2) >= 256) chunks *= 2;
+    chunks = std::min(chunks, kEntMaxChunks * 4);
     int per = (std::max(nvec, 1) + chunks - 1) / chunks;
-    while (per > 8 * 256) { ++chunks; per = (nvec + chunks - 1) / chunks; }    // rows this long get more chunks
+    while (per > 8 * 256) { ++chunks; per = (nvec + chunks - 1) / chunks; }
     *n_chunks = chunks;
-    EntArgs<T> a{(const T *)logits, V, per, part};
-    dim3 grid(chunks, rows);
+    EntArgs<T> a{(const T *)logits, V, per, part, (const T *const *)list, list_n, list_first};
+    dim3 grid(chunks, rows, steps);
     if (per <= 256) hipLaunchKernelGGL((k_entropy_partial<T, 1>), grid, dim3(256), 0, st, a);
     else if (per <= 512) hipLaunchKernelGGL((k_entropy_partial<T, 2>), grid, dim3(256), 0, st, a);
     else if (per <= 1024) hipLaunchKernelGGL((k_entropy_partial<T, 4>), grid, dim3(256), 0, st, a);
@@ -808,16 +812,17 @@ ead_status entropy_scratch(EntPartial **out) {
 }
 
 ead_status entropy_partials(const void *logits, int dtype, int rows, int vocab, hipStream_t st, EntPartial **part,
-                            int *chunks) {
-    if (!logits) return fail(nullptr, EAD_ERR_INVALID_ARG, "null logits pointer");
+                            int *chunks, const void *const *list = nullptr, int list_n = 0, int list_first = 0,
+                            int steps = 1) {
+    if (!logits && !list) return fail(nullptr, EAD_ERR_INVALID_ARG, "null logits pointer");
     if (rows < 1 || rows > kEntMaxRows) return fail(nullptr, EAD_ERR_INVALID_ARG, "rows must be in 1..%d", kEntMaxRows);
     if (vocab < 1) return fail(nullptr, EAD_ERR_INVALID_ARG, "vocab must be >= 1");
     if (dtype != EAD_F32 && dtype != EAD_BF16) return fail(nullptr, EAD_ERR_INVALID_ARG, "unknown dtype");
     if (vocab % 8) return fail(nullptr, EAD_ERR_SHAPE, "vocab must be a multiple of 8");
     if ((long)vocab > 64L * 2048 * 8 * 4) return fail(nullptr, EAD_ERR_SHAPE, "vocab too large");
     TRY(entropy_scratch(part));
-    if (dtype == EAD_BF16) launch_entropy_partial<bf16_t>(logits, rows, vocab, *part, chunks, st);
-    else launch_entropy_partial<float>(logits, rows, vocab, *part, chunks, st);
+    if (dtype == EAD_BF16) launch_entropy_partial<bf16_t>(logits, rows, vocab, *part, chunks, st, list, list_n, list_first, steps);
+    else launch_entropy_partial<float>(logits, rows, vocab, *part, chunks, st, list, list_n, list_first, steps);
     return EAD_OK;
 }
 
@@ -826,6 +831,7 @@ ead_status entropy_partials(const void *logits, int dtype, int rows, int vocab, 
 struct ead_gate {
     GateState st; GateCfg cfg; int rows; hipStream_t stream;
     std::vector<void *> allocs;
+    const void **list_dev = nullptr; int list_cap = 0;
 };
 
 // ======================================================================================
@@ -1182,7 +1188,7 @@ ead_status ead_gate_step(ead_gate *g, const float *H_dev, uint8_t *model_id_dev,
                          uint8_t *next_model_dev) {
     if (!g || !H_dev) return EAD_ERR_INVALID_ARG;
     GateStepArgs a{};
-    a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.H = H_dev;
+    a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.steps = 1; a.H = H_dev;
     a.model_id_out = model_id_dev; a.Hbar_out = window_mean_dev; a.next_out = next_model_dev;
     hipLaunchKernelGGL(k_gate_step, dim3(g->rows), dim3(64), 0, g->stream, a);
     return hipGetLastError() == hipSuccess ? EAD_OK : EAD_ERR_DEVICE;
@@ -1196,10 +1202,40 @@ ead_status ead_gate_step_logits(ead_gate *g, const void *logits_dev, int32_t dty
     EntPartial *part = nullptr; int chunks = 0;
     TRY(entropy_partials(logits_dev, dtype, g->rows, vocab, g->stream, &part, &chunks));
     GateStepArgs a{};
-    a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.partials = part; a.n_part = chunks; a.unit = unit;
+    a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.steps = 1; a.partials = part; a.n_part = chunks; a.unit = unit;
     a.H_out = H_dev; a.argmax_out = argmax_dev;
     a.model_id_out = model_id_dev; a.Hbar_out = window_mean_dev; a.next_out = next_model_dev;
     hipLaunchKernelGGL(k_gate_step, dim3(g->rows), dim3(64), 0, g->stream, a);
+    return hipGetLastError() == hipSuccess ? EAD_OK : EAD_ERR_DEVICE;
+}
+
+ead_status ead_gate_run_logits(ead_gate *g, const void *const *logits_dev_list, int32_t n_tensors, int32_t n_steps,
+                               int32_t dtype, int32_t vocab, int32_t unit, float *H_dev, int32_t *argmax_dev,
+                               uint8_t *model_id_dev, float *window_mean_dev) {
+    if (!g || !logits_dev_list) return EAD_ERR_INVALID_ARG;
+    if (n_tensors < 1 || n_tensors > 4096 || n_steps < 0) return fail(nullptr, EAD_ERR_INVALID_ARG, "need 1 <= n_tensors <= 4096, n_steps >= 0");
+    if (unit != EAD_NATS && unit != EAD_BITS) return fail(nullptr, EAD_ERR_INVALID_ARG, "unit must be 0 or 1");
+    for (int i = 0; i < n_tensors; ++i) if (!logits_dev_list[i]) return fail(nullptr, EAD_ERR_INVALID_ARG, "null logits pointer");
+    if (g->list_cap < n_tensors) {
+        void *p = nullptr;
+        if (hipMalloc(&p, sizeof(void *) * n_tensors) != hipSuccess) return fail(nullptr, EAD_ERR_OOM, "hipMalloc failed");
+        g->allocs.push_back(p); g->list_dev = (const void **)p; g->list_cap = n_tensors;
+    }
+    if (hipMemcpyAsync(g->list_dev, logits_dev_list, sizeof(void *) * n_tensors, hipMemcpyHostToDevice, g->stream) != hipSuccess)
+        return fail(nullptr, EAD_ERR_DEVICE, "hipMemcpyAsync failed");
+    // steps per launch pair, bounded by the scratch for the partials
+    const int S = std::max(1, std::min(kGateMaxSteps, kEntMaxRows / g->rows));
+    for (int s0 = 0; s0 < n_steps; s0 += S) {
+        const int ns = std::min(S, n_steps - s0);
+        EntPartial *part = nullptr; int chunks = 0;
+        TRY(entropy_partials(nullptr, dtype, g->rows, vocab, g->stream, &part, &chunks, g->list_dev, n_tensors, s0 % n_tensors, ns));
+        GateStepArgs a{};
+        a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.steps = ns; a.partials = part; a.n_part = chunks; a.unit = unit;
+        const size_t o = (size_t)s0 * g->rows;
+        a.H_out = H_dev ? H_dev + o : nullptr; a.argmax_out = argmax_dev ? argmax_dev + o : nullptr;
+        a.model_id_out = model_id_dev ? model_id_dev + o : nullptr; a.Hbar_out = window_mean_dev ? window_mean_dev + o : nullptr;
+        hipLaunchKernelGGL(k_gate_step, dim3(g->rows), dim3(ns * 64), 0, g->stream, a);
+    }
     return hipGetLastError() == hipSuccess ? EAD_OK : EAD_ERR_DEVICE;
 }
 

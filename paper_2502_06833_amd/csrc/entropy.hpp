@@ -15,21 +15,31 @@ __device__ __forceinline__ float entropy_from(const EntStat &s, int unit) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Stand-alone pass over a logits matrix [rows, V]: grid (chunks, rows), 256 threads.
-// Each thread takes up to NV vectors of 8 logits, finds their maximum first and only then
-// exponentiates (one rescale per thread instead of one per element).
+// Stand-alone pass over a logits matrix [rows, V]: grid (chunks, rows, steps), 256 threads.
+// Two bytes per logit leave only a handful of ALU operations per element before the
+// kernel stops being bandwidth-bound, so the work per logit is pared down:
+//  * each thread takes up to NV vectors of 8 logits, finds their maximum first and only
+//    then exponentiates: one rescale per thread, not one per element;
+//  * the exponentials are taken in base 2 (the hardware instruction): d = (l - m) log2 e is
+//    one FMA, Z = sum 2^d, S2 = sum 2^d d, and S = S2 ln 2 once per thread;
+//  * d is clamped at -160, where 2^d is 0 in fp32, so -inf logits need no test;
+//  * the arg max index is looked up afterwards, only by the threads that hold the
+//    workgroup's maximum.
 // ---------------------------------------------------------------------------------------
 template <typename T>
 struct EntArgs {
     const T *logits; int V; int vec_per_wg;   // 8-element vectors per workgroup
-    EntPartial *partials;                     // [rows][gridDim.x]
+    EntPartial *partials;                     // [steps][rows][gridDim.x]
+    const T *const *list; int list_n, list_first;   // optional: step z reads list[(list_first + z) % list_n]
 };
+
+constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 
 template <typename T, int NV>
 __global__ __launch_bounds__(256) void k_entropy_partial(EntArgs<T> a) {
     __shared__ EntPartial s_part[4];
     const int row = blockIdx.y, tid = threadIdx.x;
-    const T *base = a.logits + (size_t)row * a.V;
+    const T *base = (a.list ? a.list[(a.list_first + blockIdx.z) % a.list_n] : a.logits) + (size_t)row * a.V;
     const int nvec = a.V >> 3;
     const int v0 = blockIdx.x * a.vec_per_wg, v1 = min(v0 + a.vec_per_wg, nvec);
     float f[NV][8];
@@ -48,20 +58,37 @@ __global__ __launch_bounds__(256) void k_entropy_partial(EntArgs<T> a) {
     }
     EntStat st; st.init();
     if (mx > -INFINITY) {
-        float Z = 0.f, S = 0.f; int idx = 0x7FFFFFFF;
+        const float off = -mx * kLog2e;
+        float Z = 0.f, S2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float d = fmaxf(fmaf(f[i][e], kLog2e, off), -160.f);
+                const float ex = __builtin_amdgcn_exp2f(d);
+                Z += ex;
+                S2 = fmaf(ex, d, S2);
+            }
+        }
+        st.m = mx; st.Z = Z; st.S = S2 * kLn2; st.idx = tid;      // idx: provisional, the owner thread
+    }
+    // the workgroup's maximum; then only its holders look their index up
+    const float wmx = wave_max(mx);
+    if ((tid & 63) == 0) s_part[tid >> 6].m = wmx;
+    __syncthreads();
+    const float gmx = fmaxf(fmaxf(s_part[0].m, s_part[1].m), fmaxf(s_part[2].m, s_part[3].m));
+    __syncthreads();
+    if (mx == gmx && mx > -INFINITY) {
+        int idx = 0x7FFFFFFF;
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             const int v = v0 + tid + i * 256;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float d = f[i][e] - mx;
-                const float ex = __expf(d);
-                Z += ex;
-                S += ex > 0.f ? ex * d : 0.f;
-                if (f[i][e] == mx) idx = min(idx, v * 8 + e);
-            }
+            for (int e = 0; e < 8; ++e) if (f[i][e] == mx) idx = min(idx, v * 8 + e);
         }
-        st.m = mx; st.Z = Z; st.S = S; st.idx = idx;
+        st.idx = idx;
+    } else {
+        st.idx = 0x7FFFFFFF;
     }
     st = wave_merge(st);
     if ((tid & 63) == 0) { EntPartial e; e.m = st.m; e.Z = st.Z; e.S = st.S; e.idx = st.idx; s_part[tid >> 6] = e; }
@@ -77,7 +104,7 @@ __global__ __launch_bounds__(256) void k_entropy_partial(EntArgs<T> a) {
             }
         }
         EntPartial e; e.m = r.m; e.Z = r.Z; e.S = r.S; e.idx = r.idx;
-        a.partials[(size_t)row * gridDim.x + blockIdx.x] = e;
+        a.partials[((size_t)blockIdx.z * gridDim.y + row) * gridDim.x + blockIdx.x] = e;
     }
 }
 
@@ -122,34 +149,49 @@ struct GateState {           // device arrays, one entry per sequence
 
 struct GateStepArgs {
     GateState st; GateCfg cfg; int rows;
+    int steps;                      // consecutive steps handled by one launch (partials / outputs strided by rows)
     const float *H;                 // [rows] or null (then from partials)
     const EntPartial *partials; int n_part; int unit;
     float *H_out; int *argmax_out;
     uint8_t *model_id_out; float *Hbar_out; uint8_t *next_out;
 };
 
-// One wave per row: (optionally) finish the entropy from partials, then step the gate.
-__global__ __launch_bounds__(64) void k_gate_step(GateStepArgs a) {
-    const int r = blockIdx.x;
+// One workgroup per row, one wave per step of the launch: the waves finish the entropies
+// of their steps from the partials side by side, then one thread takes the steps in order
+// through the window and the switch rule (which make them sequential per row).
+constexpr int kGateMaxSteps = 16;
+
+__global__ __launch_bounds__(kGateMaxSteps * 64) void k_gate_step(GateStepArgs a) {
+    __shared__ float s_H[kGateMaxSteps];
+    const int r = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     if (r >= a.rows) return;
-    float H;
-    if (a.partials) {
-        EntStat s = merge_partials(a.partials + (size_t)r * a.n_part, a.n_part);
-        H = entropy_from(s, a.unit);
-        if (threadIdx.x == 0) {
-            if (a.H_out) a.H_out[r] = H;
-            if (a.argmax_out) a.argmax_out[r] = s.idx;
+    if (wave < a.steps) {
+        const size_t o = (size_t)wave * a.rows + r;
+        float H;
+        if (a.partials) {
+            EntStat st = merge_partials(a.partials + o * a.n_part, a.n_part);
+            H = entropy_from(st, a.unit);
+            if (lane == 0) {
+                if (a.H_out) a.H_out[o] = H;
+                if (a.argmax_out) a.argmax_out[o] = st.idx;
+            }
+        } else {
+            H = a.H[o];
         }
-    } else {
-        H = a.H[r];
+        if (lane == 0) s_H[wave] = H;
     }
+    __syncthreads();
     if (threadIdx.x == 0 && a.st.ring) {
         int model = a.st.model[r], c = a.st.c[r], n = a.st.n[r];
-        if (a.model_id_out) a.model_id_out[r] = (uint8_t)model;
-        const float hb = gate_update(a.st.ring + (size_t)r * a.cfg.w, n, H, a.cfg, &model, &c);
-        a.st.model[r] = model; a.st.c[r] = c; a.st.n[r] = n + 1;
-        if (a.Hbar_out) a.Hbar_out[r] = hb;
-        if (a.next_out) a.next_out[r] = (uint8_t)model;
+        for (int s = 0; s < a.steps; ++s) {
+            const size_t o = (size_t)s * a.rows + r;
+            if (a.model_id_out) a.model_id_out[o] = (uint8_t)model;
+            const float hb = gate_update(a.st.ring + (size_t)r * a.cfg.w, n, s_H[s], a.cfg, &model, &c);
+            ++n;
+            if (a.Hbar_out) a.Hbar_out[o] = hb;
+            if (a.next_out) a.next_out[o] = (uint8_t)model;
+        }
+        a.st.model[r] = model; a.st.c[r] = c; a.st.n[r] = n;
     }
 }
 

@@ -117,3 +117,25 @@ def test_entropy_gate_stream_config2():
             assert (hbs[:, r] == hbr).all() and (ids[:, r] == idr).all()
         assert 0 < ids.mean() < 1
         g.close()
+
+
+def test_multi_step_run_matches_single_steps():
+    """ead_gate_run_logits (several steps per launch) against step-by-step calls and the oracle."""
+    ead = _ead()
+    rows, V, steps, w, tau, d_min = 64, 151936, 37, 5, 2.0, 3
+    pool = [si.logits_torch(100 + i, "cfg2", rows, V, torch.bfloat16, "cuda") for i in range(5)]
+    g1 = ead.Gate(rows, w, tau, d_min)
+    H, am, mid, hb = g1.run_logits(pool, steps)
+    g2 = ead.Gate(rows, w, tau, d_min)
+    for t in range(steps):
+        H2, am2, mid2, hb2, _ = g2.step_logits(pool[t % 5])
+        assert (H[t] == H2).all() and (am[t] == am2).all() and (mid[t] == mid2).all() and (hb[t] == hb2).all()
+    Hn, midn, hbn = H.cpu().numpy(), mid.cpu().numpy(), hb.cpu().numpy()
+    for r in range(0, rows, 7):
+        hbr, idr = oracle.gate_trace(Hn[:, r], w, d_min, tau)
+        assert (hbn[:, r] == hbr).all() and (midn[:, r] == idr).all()
+    ref = si.logits_np(102, "cfg2", rows, V)
+    Hr, ar = oracle.entropy_rows(ref)
+    assert np.abs(Hn[2] - Hr).max() < TOL_H and (am[2].cpu().numpy() == ar).all()
+    assert 0 < midn.mean() < 1
+    g1.close(); g2.close()
