@@ -777,23 +777,33 @@ constexpr int kEntMaxRows = 4096, kEntMaxChunks = 64;
 EntPartial *g_ent_scratch[16] = {nullptr};
 
 template <typename T>
-void launch_entropy_partial(const void *logits, int rows, int V, EntPartial *part, int *n_chunks, hipStream_t st,
-                            const void *const *list = nullptr, int list_n = 0, int list_first = 0, int steps = 1) {
+void launch_entropy_partial(const void *const *step_logits, int steps, int rows, int V, EntPartial *part, int *n_chunks,
+                            hipStream_t st) {
     const int nvec = V / 8;
     // long chunks (up to 8 vectors per thread) amortise the per-workgroup merge; shorter ones
-    // only when there would otherwise be too few workgroups to fill the chip
+    // only when the rows of one step would otherwise give too few workgroups to fill the chip.
+    // The split depends on (rows, V) alone, so a step's result does not depend on how many
+    // steps share a launch.
     int chunks = std::max(1, (nvec + 2047) / 2048);
-    while ((long)chunks * rows * steps < 1024 && chunks < kEntMaxChunks && nvec / (chunks * 2) >= 256) chunks *= 2;
-    chunks = std::min(chunks, kEntMaxChunks * 4);
+    while ((long)chunks * rows < 512 && chunks < kEntMaxChunks && nvec / (chunks * 2) >= 256) chunks *= 2;
     int per = (std::max(nvec, 1) + chunks - 1) / chunks;
     while (per > 8 * 256) { ++chunks; per = (nvec + chunks - 1) / chunks; }
     *n_chunks = chunks;
-    EntArgs<T> a{(const T *)logits, V, per, part, (const T *const *)list, list_n, list_first};
-    dim3 grid(chunks, rows, steps);
-    if (per <= 256) hipLaunchKernelGGL((k_entropy_partial<T, 1>), grid, dim3(256), 0, st, a);
-    else if (per <= 512) hipLaunchKernelGGL((k_entropy_partial<T, 2>), grid, dim3(256), 0, st, a);
-    else if (per <= 1024) hipLaunchKernelGGL((k_entropy_partial<T, 4>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((k_entropy_partial<T, 8>), grid, dim3(256), 0, st, a);
+    EntArgs<T> a{};
+    for (int z = 0; z < steps; ++z) a.step_logits[z] = (const T *)step_logits[z];
+    a.V = V; a.rows = rows; a.chunks = chunks; a.vec_per_item = per; a.items = steps * rows * chunks; a.partials = part;
+    // persistent grid: as many workgroups as the chip holds at once
+    static int resident = 0;
+    if (!resident) {
+        int per_cu = 0, dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_entropy_partial<T>, 256, 0) == hipSuccess && per_cu > 0)
+            resident = per_cu * prop.multiProcessorCount;
+        else
+            resident = 1024;
+    }
+    hipLaunchKernelGGL((k_entropy_partial<T>), dim3(std::min(a.items, resident)), dim3(256), 0, st, a);
 }
 
 ead_status entropy_scratch(EntPartial **out) {
@@ -811,18 +821,21 @@ ead_status entropy_scratch(EntPartial **out) {
     return EAD_OK;
 }
 
-ead_status entropy_partials(const void *logits, int dtype, int rows, int vocab, hipStream_t st, EntPartial **part,
-                            int *chunks, const void *const *list = nullptr, int list_n = 0, int list_first = 0,
-                            int steps = 1) {
-    if (!logits && !list) return fail(nullptr, EAD_ERR_INVALID_ARG, "null logits pointer");
+// step_logits: host array of `steps` device pointers (<= kGateMaxSteps), one [rows, vocab] matrix each
+ead_status entropy_partials(const void *const *step_logits, int steps, int dtype, int rows, int vocab, hipStream_t st,
+                            EntPartial **part, int *chunks) {
+    if (steps < 1 || steps > kGateMaxSteps || (long)steps * rows > kEntMaxRows)
+        return fail(nullptr, EAD_ERR_INVALID_ARG, "too many steps for one launch");
+    for (int z = 0; z < steps; ++z)
+        if (!step_logits[z]) return fail(nullptr, EAD_ERR_INVALID_ARG, "null logits pointer");
     if (rows < 1 || rows > kEntMaxRows) return fail(nullptr, EAD_ERR_INVALID_ARG, "rows must be in 1..%d", kEntMaxRows);
     if (vocab < 1) return fail(nullptr, EAD_ERR_INVALID_ARG, "vocab must be >= 1");
     if (dtype != EAD_F32 && dtype != EAD_BF16) return fail(nullptr, EAD_ERR_INVALID_ARG, "unknown dtype");
     if (vocab % 8) return fail(nullptr, EAD_ERR_SHAPE, "vocab must be a multiple of 8");
     if ((long)vocab > 64L * 2048 * 8 * 4) return fail(nullptr, EAD_ERR_SHAPE, "vocab too large");
     TRY(entropy_scratch(part));
-    if (dtype == EAD_BF16) launch_entropy_partial<bf16_t>(logits, rows, vocab, *part, chunks, st, list, list_n, list_first, steps);
-    else launch_entropy_partial<float>(logits, rows, vocab, *part, chunks, st, list, list_n, list_first, steps);
+    if (dtype == EAD_BF16) launch_entropy_partial<bf16_t>(step_logits, steps, rows, vocab, *part, chunks, st);
+    else launch_entropy_partial<float>(step_logits, steps, rows, vocab, *part, chunks, st);
     return EAD_OK;
 }
 
@@ -831,7 +844,6 @@ ead_status entropy_partials(const void *logits, int dtype, int rows, int vocab, 
 struct ead_gate {
     GateState st; GateCfg cfg; int rows; hipStream_t stream;
     std::vector<void *> allocs;
-    const void **list_dev = nullptr; int list_cap = 0;
 };
 
 // ======================================================================================
@@ -1142,7 +1154,7 @@ ead_status ead_entropy_argmax(const void *logits_dev, int32_t dtype, int32_t row
     if (!H_dev) return fail(nullptr, EAD_ERR_INVALID_ARG, "H_dev is null");
     if (unit != EAD_NATS && unit != EAD_BITS) return fail(nullptr, EAD_ERR_INVALID_ARG, "unit must be 0 or 1");
     EntPartial *part = nullptr; int chunks = 0;
-    TRY(entropy_partials(logits_dev, dtype, rows, vocab, (hipStream_t)hip_stream, &part, &chunks));
+    TRY(entropy_partials(&logits_dev, 1, dtype, rows, vocab, (hipStream_t)hip_stream, &part, &chunks));
     hipLaunchKernelGGL(k_entropy_finalize, dim3(rows), dim3(64), 0, (hipStream_t)hip_stream, part, chunks, rows, unit,
                        H_dev, argmax_dev);
     if (hipGetLastError() != hipSuccess) return fail(nullptr, EAD_ERR_DEVICE, "kernel launch failed");
@@ -1200,7 +1212,7 @@ ead_status ead_gate_step_logits(ead_gate *g, const void *logits_dev, int32_t dty
     if (!g) return EAD_ERR_INVALID_ARG;
     if (unit != EAD_NATS && unit != EAD_BITS) return fail(nullptr, EAD_ERR_INVALID_ARG, "unit must be 0 or 1");
     EntPartial *part = nullptr; int chunks = 0;
-    TRY(entropy_partials(logits_dev, dtype, g->rows, vocab, g->stream, &part, &chunks));
+    TRY(entropy_partials(&logits_dev, 1, dtype, g->rows, vocab, g->stream, &part, &chunks));
     GateStepArgs a{};
     a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.steps = 1; a.partials = part; a.n_part = chunks; a.unit = unit;
     a.H_out = H_dev; a.argmax_out = argmax_dev;
@@ -1216,19 +1228,14 @@ ead_status ead_gate_run_logits(ead_gate *g, const void *const *logits_dev_list, 
     if (n_tensors < 1 || n_tensors > 4096 || n_steps < 0) return fail(nullptr, EAD_ERR_INVALID_ARG, "need 1 <= n_tensors <= 4096, n_steps >= 0");
     if (unit != EAD_NATS && unit != EAD_BITS) return fail(nullptr, EAD_ERR_INVALID_ARG, "unit must be 0 or 1");
     for (int i = 0; i < n_tensors; ++i) if (!logits_dev_list[i]) return fail(nullptr, EAD_ERR_INVALID_ARG, "null logits pointer");
-    if (g->list_cap < n_tensors) {
-        void *p = nullptr;
-        if (hipMalloc(&p, sizeof(void *) * n_tensors) != hipSuccess) return fail(nullptr, EAD_ERR_OOM, "hipMalloc failed");
-        g->allocs.push_back(p); g->list_dev = (const void **)p; g->list_cap = n_tensors;
-    }
-    if (hipMemcpyAsync(g->list_dev, logits_dev_list, sizeof(void *) * n_tensors, hipMemcpyHostToDevice, g->stream) != hipSuccess)
-        return fail(nullptr, EAD_ERR_DEVICE, "hipMemcpyAsync failed");
     // steps per launch pair, bounded by the scratch for the partials
     const int S = std::max(1, std::min(kGateMaxSteps, kEntMaxRows / g->rows));
     for (int s0 = 0; s0 < n_steps; s0 += S) {
         const int ns = std::min(S, n_steps - s0);
         EntPartial *part = nullptr; int chunks = 0;
-        TRY(entropy_partials(nullptr, dtype, g->rows, vocab, g->stream, &part, &chunks, g->list_dev, n_tensors, s0 % n_tensors, ns));
+        const void *ptrs[kGateMaxSteps];
+        for (int z = 0; z < ns; ++z) ptrs[z] = logits_dev_list[(s0 + z) % n_tensors];
+        TRY(entropy_partials(ptrs, ns, dtype, g->rows, vocab, g->stream, &part, &chunks));
         GateStepArgs a{};
         a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.steps = ns; a.partials = part; a.n_part = chunks; a.unit = unit;
         const size_t o = (size_t)s0 * g->rows;

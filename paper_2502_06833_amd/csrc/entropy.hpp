@@ -7,6 +7,7 @@
 namespace ead {
 
 constexpr float kLn2Inv = 1.4426950408889634f;
+constexpr int kGateMaxSteps = 16;       // steps of the gate one launch can take
 
 // H = ln Z - S/Z in nats, or divided by ln 2 for bits
 __device__ __forceinline__ float entropy_from(const EntStat &s, int unit) {
@@ -15,96 +16,166 @@ __device__ __forceinline__ float entropy_from(const EntStat &s, int unit) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Stand-alone pass over a logits matrix [rows, V]: grid (chunks, rows, steps), 256 threads.
-// Two bytes per logit leave only a handful of ALU operations per element before the
-// kernel stops being bandwidth-bound, so the work per logit is pared down:
-//  * each thread takes up to NV vectors of 8 logits, finds their maximum first and only
-//    then exponentiates: one rescale per thread, not one per element;
-//  * the exponentials are taken in base 2 (the hardware instruction): d = (l - m) log2 e is
-//    one FMA, Z = sum 2^d, S2 = sum 2^d d, and S = S2 ln 2 once per thread;
-//  * d is clamped at -160, where 2^d is 0 in fp32, so -inf logits need no test;
-//  * the arg max index is looked up afterwards, only by the threads that hold the
-//    workgroup's maximum.
+// Stand-alone pass over logits matrices [rows, V].  A work item is one chunk of one row of
+// one step (up to 2048 vectors of 8 logits); item i leaves partial i.  The grid is
+// persistent: a workgroup of 256 threads takes items i, i + grid, ... and keeps loads in
+// flight across them -- each thread holds two sets of four vectors, and while it works on
+// one set the other (the second half of this item, or the first half of the next) is on
+// its way, so memory and arithmetic overlap inside every wave instead of by luck between
+// waves.
+//
+// Two bytes per logit leave only a handful of ALU operations per element before the kernel
+// stops being bandwidth-bound, so the work per logit is pared down:
+//  * the maximum of a set of 32 logits is found first, then they are exponentiated: one
+//    rescale of the running sums per set, not per element;
+//  * exponentials are taken in base 2 (the hardware instruction): d = (l - m) log2 e is
+//    one FMA, Z = sum 2^d, S2 = sum 2^d d, and S = S2 ln 2 once per item;
+//  * d is clamped at -160, where 2^d is 0 in fp32, so -inf logits need no test, and a
+//    vector past the end of the chunk is switched off through its FMA offset (-inf);
+//  * for the arg max a thread keeps the packed vector that holds its running maximum; the
+//    element is looked up at the end, only by the threads that hold the item's maximum.
 // ---------------------------------------------------------------------------------------
 template <typename T>
 struct EntArgs {
-    const T *logits; int V; int vec_per_wg;   // 8-element vectors per workgroup
-    EntPartial *partials;                     // [steps][rows][gridDim.x]
-    const T *const *list; int list_n, list_first;   // optional: step z reads list[(list_first + z) % list_n]
+    const T *step_logits[kGateMaxSteps];      // one [rows, V] matrix per step of the launch
+    int V, rows, chunks, vec_per_item, items; // items = steps * rows * chunks
+    EntPartial *partials;                     // [items]
 };
 
 constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+constexpr float kEntNone = -1e30f;            // running maximum before any logit was seen
 
-template <typename T, int NV>
+template <typename T>
+struct EntItem { const T *base; int v0, v1; };
+
+template <typename T>
+__device__ __forceinline__ EntItem<T> ent_item(const EntArgs<T> &a, int item) {
+    const int chunk = item % a.chunks, rz = item / a.chunks, row = rz % a.rows, z = rz / a.rows;
+    const T *p = a.step_logits[z];
+    EntItem<T> it;
+    it.base = p + (size_t)row * a.V;
+    it.v0 = chunk * a.vec_per_item;
+    it.v1 = min(it.v0 + a.vec_per_item, a.V >> 3);
+    return it;
+}
+
+// vectors j0 .. j0+3 of a thread (vector v0 + tid + 256 j); past the end: a valid address
+// whose contents are ignored, so no branch surrounds the loads
+template <typename T>
+__device__ __forceinline__ void ent_load4(Vec8<T> (&s)[4], const EntItem<T> &it, int j0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int v = max(min(it.v0 + (int)threadIdx.x + (j0 + i) * 256, it.v1 - 1), 0);
+        s[i].load_stream(it.base + (size_t)v * 8);
+    }
+}
+
+template <typename T>
+struct EntRun {              // a thread's running statistics within one item
+    float m, Z, S2; int bestj; Vec8<T> best;
+};
+
+template <typename T>
+__device__ __forceinline__ void ent_take4(const Vec8<T> (&s)[4], EntRun<T> &r, const EntItem<T> &it, int j0) {
+    float f[4][8];
+    bool valid[4];
+    const float m_old = r.m;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s[i].unpack(f[i]);
+        valid[i] = it.v0 + (int)threadIdx.x + (j0 + i) * 256 < it.v1;
+        float vm = fmaxf(fmaxf(fmaxf(f[i][0], f[i][1]), fmaxf(f[i][2], f[i][3])),
+                         fmaxf(fmaxf(f[i][4], f[i][5]), fmaxf(f[i][6], f[i][7])));
+        vm = valid[i] ? vm : kEntNone;
+        if (vm > r.m) { r.m = vm; r.bestj = j0 + i; r.best = s[i]; }
+    }
+    // move the sums to the new maximum: d' = d - delta
+    const float delta = (r.m - m_old) * kLog2e;
+    const float sc = __builtin_amdgcn_exp2f(-fminf(delta, 160.f));
+    r.S2 = sc * (r.S2 - delta * r.Z);
+    r.Z *= sc;
+    const float off = -r.m * kLog2e;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float o = valid[i] ? off : -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float d = fmaxf(fmaf(f[i][e], kLog2e, o), -160.f);
+            const float ex = __builtin_amdgcn_exp2f(d);
+            r.Z += ex;
+            r.S2 = fmaf(ex, d, r.S2);
+        }
+    }
+}
+
+template <typename T>
 __global__ __launch_bounds__(256) void k_entropy_partial(EntArgs<T> a) {
-    __shared__ EntPartial s_part[4];
-    const int row = blockIdx.y, tid = threadIdx.x;
-    const T *base = (a.list ? a.list[(a.list_first + blockIdx.z) % a.list_n] : a.logits) + (size_t)row * a.V;
-    const int nvec = a.V >> 3;
-    const int v0 = blockIdx.x * a.vec_per_wg, v1 = min(v0 + a.vec_per_wg, nvec);
-    float f[NV][8];
-    float mx = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int v = v0 + tid + i * 256;
-        if (v < v1) {
-            Vec8<T> x; x.load_stream(base + (size_t)v * 8); x.unpack(f[i]);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) f[i][e] = -INFINITY;
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) mx = fmaxf(mx, f[i][e]);
-    }
-    EntStat st; st.init();
-    if (mx > -INFINITY) {
-        const float off = -mx * kLog2e;
-        float Z = 0.f, S2 = 0.f;
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float d = fmaxf(fmaf(f[i][e], kLog2e, off), -160.f);
-                const float ex = __builtin_amdgcn_exp2f(d);
-                Z += ex;
-                S2 = fmaf(ex, d, S2);
-            }
-        }
-        st.m = mx; st.Z = Z; st.S = S2 * kLn2; st.idx = tid;      // idx: provisional, the owner thread
-    }
-    // the workgroup's maximum; then only its holders look their index up
-    const float wmx = wave_max(mx);
-    if ((tid & 63) == 0) s_part[tid >> 6].m = wmx;
-    __syncthreads();
-    const float gmx = fmaxf(fmaxf(s_part[0].m, s_part[1].m), fmaxf(s_part[2].m, s_part[3].m));
-    __syncthreads();
-    if (mx == gmx && mx > -INFINITY) {
+    __shared__ float s_max[4];
+    __shared__ EntPartial s_fin[4];
+    const int tid = threadIdx.x;
+    int item = blockIdx.x;                  // uniform: kept in scalar registers
+    if (item >= a.items) return;
+    EntItem<T> it = ent_item(a, item);
+    Vec8<T> A[4], B[4], C[4];
+    ent_load4(A, it, 0);
+    // one item: `first` holds its first half (already requested), B takes its second half and
+    // `next` the first half of the item after it.  Returns true after the last item.
+    auto one_item = [&](Vec8<T> (&first)[4], Vec8<T> (&next)[4]) __attribute__((always_inline)) -> bool {
+        ent_load4(B, it, 4);
+        // the next item's first half is requested before this item's second half is worked
+        // on; after the last item the request repeats this one and its result is dropped
+        const int nitem = item + gridDim.x;
+        const bool more = nitem < a.items;
+        const EntItem<T> nit = ent_item(a, more ? nitem : item);
+        EntRun<T> r; r.m = kEntNone; r.Z = 0.f; r.S2 = 0.f; r.bestj = 0; r.best.zero();
+        // pin the order: without it the compiler moves the next requests behind the second
+        // half's arithmetic and nothing is in flight while a wave computes
+        __builtin_amdgcn_sched_barrier(0);
+        ent_take4(first, r, it, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        ent_load4(next, nit, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        ent_take4(B, r, it, 4);
+
+        // the item's maximum; every thread moves its sums to that reference once, so the
+        // rest of the reduction is plain sums in a fixed order
+        const float wmx = wave_max(r.m);
+        if ((tid & 63) == 0) s_max[tid >> 6] = wmx;
+        __syncthreads();
+        const float gmx = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+        const float delta = (gmx - r.m) * kLog2e;
+        const float sc = __builtin_amdgcn_exp2f(-fminf(delta, 160.f));
+        float S2 = sc * (r.S2 - delta * r.Z), Z = r.Z * sc;
         int idx = 0x7FFFFFFF;
+        if (r.m == gmx && r.m > kEntNone) {
+            float f[8];
+            r.best.unpack(f);
+            int e0 = 8;
 #pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const int v = v0 + tid + i * 256;
+            for (int e = 7; e >= 0; --e) if (f[e] == r.m) e0 = e;
+            idx = (it.v0 + tid + r.bestj * 256) * 8 + e0;
+        }
+        Z = wave_sum(Z); S2 = wave_sum(S2);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) if (f[i][e] == mx) idx = min(idx, v * 8 + e);
+        for (int o = 32; o > 0; o >>= 1) idx = min(idx, __shfl_xor(idx, o, kWave));
+        if ((tid & 63) == 0) { EntPartial e; e.m = gmx; e.Z = Z; e.S = S2; e.idx = idx; s_fin[tid >> 6] = e; }
+        __syncthreads();
+        if (tid == 0) {
+            EntPartial e;
+            e.m = gmx > kEntNone ? gmx : -INFINITY;
+            e.Z = ((s_fin[0].Z + s_fin[1].Z) + s_fin[2].Z) + s_fin[3].Z;
+            e.S = (((s_fin[0].S + s_fin[1].S) + s_fin[2].S) + s_fin[3].S) * kLn2;
+            e.idx = min(min(s_fin[0].idx, s_fin[1].idx), min(s_fin[2].idx, s_fin[3].idx));
+            a.partials[item] = e;
         }
-        st.idx = idx;
-    } else {
-        st.idx = 0x7FFFFFFF;
-    }
-    st = wave_merge(st);
-    if ((tid & 63) == 0) { EntPartial e; e.m = st.m; e.Z = st.Z; e.S = st.S; e.idx = st.idx; s_part[tid >> 6] = e; }
-    __syncthreads();
-    if (tid == 0) {
-        EntStat r; r.init();
-        for (int w = 0; w < 4; ++w) { EntStat q; q.m = s_part[w].m; q.Z = s_part[w].Z; q.S = s_part[w].S; q.idx = s_part[w].idx; r.merge(q); }
-        // scalar tail of a vocabulary that is not a multiple of 8 (last chunk only)
-        if (blockIdx.x == gridDim.x - 1) {
-            for (int i = nvec * 8; i < a.V; ++i) {
-                EntStat q; q.m = to_f32(base[i]); q.Z = q.m > -INFINITY ? 1.f : 0.f; q.S = 0.f; q.idx = i;
-                r.merge(q);
-            }
-        }
-        EntPartial e; e.m = r.m; e.Z = r.Z; e.S = r.S; e.idx = r.idx;
-        a.partials[((size_t)blockIdx.z * gridDim.y + row) * gridDim.x + blockIdx.x] = e;
+        item = __builtin_amdgcn_readfirstlane(nitem); it = nit;
+        return !more;
+    };
+    // the first-half registers alternate between A and C, so no request ever has to land
+    // before the loop can go round
+    for (;;) {
+        if (one_item(A, C)) break;
+        if (one_item(C, A)) break;
     }
 }
 
@@ -159,12 +230,17 @@ struct GateStepArgs {
 // One workgroup per row, one wave per step of the launch: the waves finish the entropies
 // of their steps from the partials side by side, then one thread takes the steps in order
 // through the window and the switch rule (which make them sequential per row).
-constexpr int kGateMaxSteps = 16;
+constexpr int kGateMaxWindow = 4096;    // largest rolling window w (entries kept in LDS)
 
 __global__ __launch_bounds__(kGateMaxSteps * 64) void k_gate_step(GateStepArgs a) {
     __shared__ float s_H[kGateMaxSteps];
+    __shared__ float s_ring[kGateMaxWindow];
     const int r = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     if (r >= a.rows) return;
+    // the window lives in LDS while the steps are taken: a store-then-load round trip through
+    // device memory per step would dominate this kernel
+    if (a.st.ring)
+        for (int i = threadIdx.x; i < a.cfg.w; i += blockDim.x) s_ring[i] = a.st.ring[(size_t)r * a.cfg.w + i];
     if (wave < a.steps) {
         const size_t o = (size_t)wave * a.rows + r;
         float H;
@@ -181,18 +257,21 @@ __global__ __launch_bounds__(kGateMaxSteps * 64) void k_gate_step(GateStepArgs a
         if (lane == 0) s_H[wave] = H;
     }
     __syncthreads();
-    if (threadIdx.x == 0 && a.st.ring) {
+    if (!a.st.ring) return;
+    if (threadIdx.x == 0) {
         int model = a.st.model[r], c = a.st.c[r], n = a.st.n[r];
         for (int s = 0; s < a.steps; ++s) {
             const size_t o = (size_t)s * a.rows + r;
             if (a.model_id_out) a.model_id_out[o] = (uint8_t)model;
-            const float hb = gate_update(a.st.ring + (size_t)r * a.cfg.w, n, s_H[s], a.cfg, &model, &c);
+            const float hb = gate_update(s_ring, n, s_H[s], a.cfg, &model, &c);
             ++n;
             if (a.Hbar_out) a.Hbar_out[o] = hb;
             if (a.next_out) a.next_out[o] = (uint8_t)model;
         }
         a.st.model[r] = model; a.st.c[r] = c; a.st.n[r] = n;
     }
+    __syncthreads();
+    for (int i = threadIdx.x; i < a.cfg.w; i += blockDim.x) a.st.ring[(size_t)r * a.cfg.w + i] = s_ring[i];
 }
 
 }  // namespace ead
