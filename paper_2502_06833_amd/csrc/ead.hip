@@ -372,10 +372,14 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int grid) {
 
 template <typename KT, int HD>
 void launch_attn(ead_handle *h, int mi, AttnArgs<KT> &a, int G, int T, double kv_bytes) {
-    dim3 grid(a.max_splits, a.n_kv_heads, T);
+    // few rows: one workgroup per query head (latency-bound, wants the lanes); many rows:
+    // one per KV head, so K and V are streamed once for the heads that share them
+    const bool per_head = (long)T * a.n_kv_heads * a.max_splits <= 64;
+    dim3 grid(a.max_splits, per_head ? a.n_heads : a.n_kv_heads, T);
     {
         ProfScope ps(h, PK_ATTN_PARTIAL, mi, kv_bytes);
-#define EAD_LA(G_) hipLaunchKernelGGL((k_attn<KT, HD, G_>), grid, dim3(kAttnWaves * 64), 0, h->stream, a)
+#define EAD_LA(G_) do { if (per_head) hipLaunchKernelGGL((k_attn<KT, HD, G_, 1>), grid, dim3(kAttnWaves * 64), 0, h->stream, a); \
+                        else hipLaunchKernelGGL((k_attn<KT, HD, G_, G_>), grid, dim3(kAttnWaves * 64), 0, h->stream, a); } while (0)
         switch (G) { case 1: EAD_LA(1); break; case 2: EAD_LA(2); break; case 4: EAD_LA(4); break;
                      case 5: EAD_LA(5); break; case 7: EAD_LA(7); break; default: EAD_LA(8); break; }
 #undef EAD_LA
@@ -926,8 +930,8 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
         HIP_TRY(h, hipMemsetAsync(h->xp_o, 0, T * qmax * 2, h->stream));
         HIP_TRY(h, hipMemsetAsync(h->xp_h, 0, T * fmax_ * 2, h->stream));
         TRY(dmalloc(h, &h->part_o, (size_t)h->items_max * qmax)); TRY(dmalloc(h, &h->part_ml, (size_t)h->items_max * std::max(a.H, b.H)));
-        TRY(dmalloc(h, &h->tickets, (size_t)h->Tmax * std::max(a.KV, b.KV)));
-        HIP_TRY(h, hipMemsetAsync(h->tickets, 0, (size_t)h->Tmax * std::max(a.KV, b.KV) * sizeof(int), h->stream));
+        TRY(dmalloc(h, &h->tickets, (size_t)h->Tmax * std::max(a.H, b.H)));
+        HIP_TRY(h, hipMemsetAsync(h->tickets, 0, (size_t)h->Tmax * std::max(a.H, b.H) * sizeof(int), h->stream));
         TRY(dmalloc(h, &h->lm_part, std::max((size_t)std::max<size_t>(MB, h->score_rows) * h->lm_grid, (size_t)256 * kFusedRbChunk)));
         TRY(dmalloc(h, &h->logits_dump, (size_t)h->score_rows * a.V));
         TRY(dmalloc(h, &h->sc_H, (size_t)MS)); TRY(dmalloc(h, &h->sc_arg, (size_t)MS));
