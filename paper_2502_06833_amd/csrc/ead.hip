@@ -157,6 +157,7 @@ struct ead_handle {
     SeqState s; Plan plan; GateCfg cfg;
     // scratch
     float *x, *q, *o, *hbuf; bf16_t *xp_a, *xp_o, *xp_h, *xl_a, *xl_o, *xl_h;
+    float *sk_part; int *sk_tickets;     // split-K partial sums of the MFMA path
     float *part_o; float2 *part_ml; int *tickets; EntPartial *lm_part; float *logits_dump; float *sc_H; int *sc_arg;
     int *h_model, *h_done;   // pinned
     // fused single-row decode
@@ -363,11 +364,46 @@ void launch_valu(ead_handle *h, int mi, LinArgs<WT> &a, int T, int grid) {
 #undef EAD_LV
 }
 
+// T: the host's count of token rows.  The shape of the matrix alone picks the workgroup:
+//  * many row blocks: four waves, four row blocks each (an activation tile is fetched once
+//    for four weight tiles);
+//  * few row blocks but a large matrix (long K): the same, with K split over KS workgroups
+//    per group so that the chip still gets about two workgroups per compute unit; passes of
+//    more than 64 rows (prefill) are bound by the matrix cores instead and take eight waves
+//    that split K inside one workgroup of two row blocks;
+//  * small matrices are latency-bound: one row block per four-wave workgroup, as many
+//    workgroups as possible.
+// NT token blocks per pass follow T; the ring depth D follows the register budget.
+constexpr int kSplitKGroups = 4096;                     // arrival counters
+constexpr size_t kSplitKFloats = (size_t)4 << 20;      // partial sums: KS * Np * 64 floats at most
+
 template <int EPI>
-void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int grid) {
+void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap = 0) {
     ProfScope ps(h, PK_MFMA_QKV + EPI, mi, (double)a.Np * a.K * 2.0);
-    if (a.K / 32 >= 64) hipLaunchKernelGGL((k_linear_mfma<8, EPI>), dim3(grid), dim3(512), 0, h->stream, a);
-    else hipLaunchKernelGGL((k_linear_mfma<4, EPI>), dim3(grid), dim3(256), 0, h->stream, a);
+    const int NB = a.Np / 16, TB = (T + 15) / 16;
+    const bool big = (double)a.Np * a.K * 2.0 >= 24e6;
+    const int NT = TB <= 1 ? 1 : (TB == 2 ? 2 : 4);
+    int cfg = !big ? 1 : (NB >= 4 * 256 ? 4 : 2);       // 1: (4 waves, R=1)  4: (4, R=4)  2: (8 waves, R=2)  5: (4, R=4, split K)
+    int grid = (NB + cfg - 1) / cfg;
+    if (cfg == 2 && TB <= 4 && EPI != EPI_LOGITS) {
+        const int NG = (NB + 3) / 4;
+        int KS = std::min(kSplitKMax, std::max(1, (2 * h->n_cu + NG / 2) / NG));
+        while (KS > 1 && (a.K / 32) / KS < 16) --KS;                   // a slab keeps at least 16 k tiles
+        if (KS > 1 && (size_t)KS * NG * 4 * NT * 256 <= kSplitKFloats && NG <= kSplitKGroups) {
+            cfg = 5; a.KS = KS; a.sk_part = h->sk_part; a.sk_tickets = h->sk_tickets; grid = NG * KS;
+        }
+    }
+    if (grid_cap > 0) grid = grid_cap;      // LM head: the number of partials per row is fixed
+#define EAD_LM(NW_, R_, NT_, D_, SK_) hipLaunchKernelGGL((k_linear_mfma<NW_, R_, NT_, D_, EPI, SK_>), dim3(grid), dim3(NW_ * 64), 0, h->stream, a)
+    switch (cfg * 10 + NT) {
+        case 11: EAD_LM(4, 1, 1, 8, false); break; case 12: EAD_LM(4, 1, 2, 6, false); break; case 14: EAD_LM(4, 1, 4, 4, false); break;
+        case 21: EAD_LM(8, 2, 1, 8, false); break; case 22: EAD_LM(8, 2, 2, 6, false); break; case 24: EAD_LM(8, 2, 4, 3, false); break;
+        case 41: EAD_LM(4, 4, 1, 6, false); break; case 42: EAD_LM(4, 4, 2, 4, false); break; case 44: EAD_LM(4, 4, 4, 3, false); break;
+        case 51: if constexpr (EPI != EPI_LOGITS) EAD_LM(4, 4, 1, 6, true); break;
+        case 52: if constexpr (EPI != EPI_LOGITS) EAD_LM(4, 4, 2, 4, true); break;
+        default: if constexpr (EPI != EPI_LOGITS) EAD_LM(4, 4, 4, 3, true); break;
+    }
+#undef EAD_LM
 }
 
 template <typename KT, int HD>
@@ -424,7 +460,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
                 PackArgs pa{h->x, d, cnt, nullptr, ly.g_attn, m.eps, h->xp_a, h->xl_a, d};
                 { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa); }
                 a.xp = h->xp_a; a.xp_lo = h->xl_a;
-                launch_mfma<EPI_QKV>(h, mi, a, a.Np / 16);
+                launch_mfma<EPI_QKV>(h, mi, a, T);
             }
         } else {
             a.x = h->x; a.ldx = d; a.gain = ly.g_attn; a.eps = m.eps;
@@ -443,7 +479,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         // ---- output projection + residual ----
         LinArgs<WT> b{};
         b.W = (const WT *)ly.wo; b.Np = d; b.K = NQ; b.count = cnt; b.out = h->x; b.ldo = d;
-        if (mfma) { if constexpr (is_bf16) { b.xp = h->xp_o; b.xp_lo = h->xl_o; launch_mfma<EPI_RES>(h, mi, b, d / 16); } }
+        if (mfma) { if constexpr (is_bf16) { b.xp = h->xp_o; b.xp_lo = h->xl_o; launch_mfma<EPI_RES>(h, mi, b, T); } }
         else { b.x = h->o; b.ldx = NQ; launch_valu<WT, EPI_RES>(h, mi, b, T, d / 16); }
         // ---- RMSNorm + gate/up + SwiGLU ----
         LinArgs<WT> c{};
@@ -453,7 +489,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
                 PackArgs pa{h->x, d, cnt, nullptr, ly.g_ffn, m.eps, h->xp_a, h->xl_a, d};
                 { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa); }
                 c.xp = h->xp_a; c.xp_lo = h->xl_a; c.out_tiles = h->xp_h; c.out_tiles_lo = h->xl_h; c.out_KC = F / 32;
-                launch_mfma<EPI_SWIGLU>(h, mi, c, c.Np / 16);
+                launch_mfma<EPI_SWIGLU>(h, mi, c, T);
             }
         } else {
             c.x = h->x; c.ldx = d; c.gain = ly.g_ffn; c.eps = m.eps; c.out = h->hbuf;
@@ -463,7 +499,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         // ---- down projection + residual ----
         LinArgs<WT> e{};
         e.W = (const WT *)ly.wdown; e.Np = d; e.K = F; e.count = cnt; e.out = h->x; e.ldo = d;
-        if (mfma) { if constexpr (is_bf16) { e.xp = h->xp_h; e.xp_lo = h->xl_h; launch_mfma<EPI_RES>(h, mi, e, d / 16); } }
+        if (mfma) { if constexpr (is_bf16) { e.xp = h->xp_h; e.xp_lo = h->xl_h; launch_mfma<EPI_RES>(h, mi, e, T); } }
         else { e.x = h->hbuf; e.ldx = F; launch_valu<WT, EPI_RES>(h, mi, e, T, d / 16); }
     }
     if (n_lm > 0) {
@@ -477,7 +513,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
                 PackArgs pa{h->x, d, cnt + 1, h->plan.lm_row, m.g_final, m.eps, h->xp_a, h->xl_a, d};
                 { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3((n_lm + 15) & ~15), dim3(256), 0, st, pa); }
                 g.xp = h->xp_a; g.xp_lo = h->xl_a;
-                launch_mfma<EPI_LOGITS>(h, mi, g, grid);
+                launch_mfma<EPI_LOGITS>(h, mi, g, n_lm, grid);
             }
         } else {
             g.x = h->x; g.ldx = d; g.gain = m.g_final; g.eps = m.eps;
@@ -931,6 +967,8 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
         HIP_TRY(h, hipMemsetAsync(h->xp_h, 0, T * fmax_ * 2, h->stream));
         TRY(dmalloc(h, &h->part_o, (size_t)h->items_max * qmax)); TRY(dmalloc(h, &h->part_ml, (size_t)h->items_max * std::max(a.H, b.H)));
         TRY(dmalloc(h, &h->tickets, (size_t)h->Tmax * std::max(a.H, b.H)));
+        TRY(dmalloc(h, &h->sk_part, kSplitKFloats)); TRY(dmalloc(h, &h->sk_tickets, (size_t)kSplitKGroups));
+        HIP_TRY(h, hipMemsetAsync(h->sk_tickets, 0, kSplitKGroups * sizeof(int), h->stream));
         HIP_TRY(h, hipMemsetAsync(h->tickets, 0, (size_t)h->Tmax * std::max(a.H, b.H) * sizeof(int), h->stream));
         TRY(dmalloc(h, &h->lm_part, std::max((size_t)std::max<size_t>(MB, h->score_rows) * h->lm_grid, (size_t)256 * kFusedRbChunk)));
         TRY(dmalloc(h, &h->logits_dump, (size_t)h->score_rows * a.V));

@@ -347,10 +347,10 @@ __device__ __forceinline__ void fused_linear(const LinArgs<WT> &a, int epi, cons
             for (int w = 0; w < kFusedWaves; ++w) v += red[(i * kFusedWaves + w) * 16 + j];
             const int p = (rb0 + i * G) * 16 + j;
             switch (epi) {
-                case EPI_QKV: epilogue<WT, EPI_QKV, true>(a, p, 0, v, true, st); break;
-                case EPI_RES: epilogue<WT, EPI_RES, true>(a, p, 0, v, true, st); break;
-                case EPI_SWIGLU: epilogue<WT, EPI_SWIGLU, true>(a, p, 0, v, true, st); break;
-                default: epilogue<WT, EPI_LOGITS, true>(a, p, 0, v, true, st); break;
+                case EPI_QKV: epilogue<WT, EPI_QKV, true>(a, p, 0, v, true, st, epi_prefetch<WT, EPI_QKV, true>(a, p, 0, true)); break;
+                case EPI_RES: epilogue<WT, EPI_RES, true>(a, p, 0, v, true, st, epi_prefetch<WT, EPI_RES, true>(a, p, 0, true)); break;
+                case EPI_SWIGLU: epilogue<WT, EPI_SWIGLU, true>(a, p, 0, v, true, st, epi_prefetch<WT, EPI_SWIGLU, true>(a, p, 0, true)); break;
+                default: epilogue<WT, EPI_LOGITS, true>(a, p, 0, v, true, st, epi_prefetch<WT, EPI_LOGITS, true>(a, p, 0, true)); break;
             }
         }
         __syncthreads();

@@ -4,11 +4,11 @@
 // Two kernels share the tiled weight layout and the epilogues:
 //   k_linear_valu  plain FMA path for a handful of token rows (and for fp32 weights);
 //                  activations stay fp32, staged once per workgroup in LDS.
-//   k_linear_mfma  16x16x32 bf16 MFMA path for wider batches of token rows (decode at
-//                  batch > 4, catch-up chunks, prompt prefill); activations are bf16 tiles.
-// In both, one workgroup owns a 16-row block of W at a time and its waves split K, so a
-// wave reads one contiguous stream of 1 KB (bf16) tiles; partial sums meet in LDS and are
-// added in wave order, so a row's result does not depend on how many rows are in flight.
+//   k_linear_mfma  16x16x32 bf16 MFMA path for two or more token rows (batched decode,
+//                  catch-up chunks, prompt prefill); activations are bf16 tiles.
+// In both, a workgroup owns 16-row blocks of W and its waves split K, so a wave reads
+// contiguous streams of 1 KB (bf16) tiles; partial sums meet in LDS and are added in wave
+// order, so a row's result does not depend on how many rows are in flight.
 #pragma once
 #include "common.hpp"
 
@@ -45,6 +45,10 @@ struct LinArgs {
     // LOGITS
     EntPartial *partials;   // [rows][gridDim.x]
     float *logits;          // optional dump [rows][Np]
+    // MFMA path with K split over KS workgroups per row-block group
+    int KS;
+    float *sk_part;         // [KS][groups][R][NT][256] partial sums
+    int *sk_tickets;        // [groups] arrival counters, zero between launches
 };
 
 // ------------------------------------------------------------------------------------
@@ -56,16 +60,35 @@ template <typename T> __device__ __forceinline__ void put(T *p, T v, bool cohere
     if (coherent) st_coherent(p, v); else *p = v;
 }
 
+// What an epilogue reads from memory for one output element.  It is fetched ahead (before
+// the k loop of the FMA path, before the reduction of the MFMA path) so that the chain
+// position -> rotary table, or the residual, is not waited for between two barriers.
+struct EpiPre { float res; float2 cs; int pos, seq; };
+
 // COH: outputs are handed to other workgroups inside the same kernel (fused decode).
 template <typename WT, int EPI, bool COH = false>
-__device__ __forceinline__ void epilogue(const LinArgs<WT> &a, int p, int t, float v, bool valid,
-                                         EntStat &st) {
+__device__ __forceinline__ EpiPre epi_prefetch(const LinArgs<WT> &a, int p, int t, bool valid) {
+    EpiPre e; e.res = 0.f; e.cs = make_float2(1.f, 0.f); e.pos = 0; e.seq = 0;
+    if (!valid) return e;
     if constexpr (EPI == EPI_RES) {
-        if (valid) {
-            float *dst = a.out + (size_t)t * a.ldo + p;
-            const float r = a.res_embed ? to_f32(a.res_embed[p]) : (COH ? ld_coherent(dst) : *dst);
-            put(dst, r + v, COH);
+        const float *dst = a.out + (size_t)t * a.ldo + p;
+        e.res = a.res_embed ? to_f32(a.res_embed[p]) : (COH ? ld_coherent(dst) : *dst);
+    } else if constexpr (EPI == EPI_QKV) {
+        e.pos = a.row_pos[t]; e.seq = a.row_seq[t];
+        const int hd = a.hd, NQ = a.n_heads * hd, NK = a.n_kv_heads * hd;
+        if (p < NQ + NK) {
+            const int pp = p < NQ ? p : p - NQ;
+            e.cs = a.rope[(size_t)e.pos * (hd >> 1) + ((pp % hd) >> 1)];
         }
+    }
+    return e;
+}
+
+template <typename WT, int EPI, bool COH = false>
+__device__ __forceinline__ void epilogue(const LinArgs<WT> &a, int p, int t, float v, bool valid,
+                                         EntStat &st, const EpiPre &pre) {
+    if constexpr (EPI == EPI_RES) {
+        if (valid) put(a.out + (size_t)t * a.ldo + p, pre.res + v, COH);
     } else if constexpr (EPI == EPI_SWIGLU) {
         float other = __shfl_xor(v, 1, kWave);       // even lane: gate, odd lane: up
         if (valid && !(p & 1)) {
@@ -81,21 +104,21 @@ __device__ __forceinline__ void epilogue(const LinArgs<WT> &a, int p, int t, flo
         float other = __shfl_xor(v, 1, kWave);
         if (!valid) return;
         const int hd = a.hd, NQ = a.n_heads * hd, NK = a.n_kv_heads * hd;
-        const int pos = a.row_pos[t];
+        const int pos = pre.pos;
         if (p < NQ + NK) {                            // rotary: lanes (2i, 2i+1) hold dims (i, i+hd/2)
             int pp = p < NQ ? p : p - NQ;
             int head = pp / hd, r = pp % hd, i = r >> 1, s = r & 1;
-            float2 cs = a.rope[(size_t)pos * (hd >> 1) + i];
+            const float2 cs = pre.cs;
             float res = s ? (other * cs.y + v * cs.x) : (v * cs.x - other * cs.y);
             int dim = i + s * (hd >> 1);
             if (p < NQ) put(a.out + (size_t)t * a.ldo + head * hd + dim, res, COH);
             else {
-                size_t o = (((size_t)a.row_seq[t] * a.n_kv_heads + head) * a.max_seq + pos) * hd + dim;
+                size_t o = (((size_t)pre.seq * a.n_kv_heads + head) * a.max_seq + pos) * hd + dim;
                 put(a.kcache + o, from_f32<WT>(res), COH);
             }
         } else {
             int pp = p - NQ - NK, head = pp / hd, dim = pp % hd;
-            size_t o = (((size_t)a.row_seq[t] * a.n_kv_heads + head) * a.max_seq + pos) * hd + dim;
+            size_t o = (((size_t)pre.seq * a.n_kv_heads + head) * a.max_seq + pos) * hd + dim;
             put(a.vcache + o, from_f32<WT>(v), COH);
         }
     } else {                                          // EPI_LOGITS: fold the logit into (m, Z, S, argmax)
@@ -107,7 +130,7 @@ __device__ __forceinline__ void epilogue(const LinArgs<WT> &a, int p, int t, flo
             st.S = e * (st.S + d * st.Z); st.Z = st.Z * e + 1.f; st.m = v; st.idx = p;
         } else {
             float d = v - st.m, e = __expf(d);
-            st.Z += e; st.S += e * d;
+            st.S += e * d; st.Z += e;
         }
     }
 }
@@ -204,6 +227,8 @@ __global__ __launch_bounds__(NW * 64) void k_linear_valu(LinArgs<WT> a) {
             for (int tc = 0; tc < TC; ++tc) acc[tc] = 0.f;
             const WT *wp = a.W + tile_offset(rb, kc0, KC) + lane * 8;
             const float *xq = xs + g * 8;
+            // what the epilogue reads is requested now and arrives during the k loop
+            const EpiPre pre = epi_prefetch<WT, EPI>(a, rb * 16 + (tid & 15), t0 + (tid >> 4), tid < 16 * TC && t0 + (tid >> 4) < T);
             for (int kc = kc0; kc < kc1; kc += U) {
                 // fetch one group ahead: the rest of this row block, else the head of the next
                 // one (the next pass over the same block when more token rows follow)
@@ -248,7 +273,7 @@ __global__ __launch_bounds__(NW * 64) void k_linear_valu(LinArgs<WT> a) {
                 float v = 0.f;
 #pragma unroll
                 for (int w = 0; w < NW; ++w) v += red[(w * TC + tc) * 16 + j];
-                epilogue<WT, EPI>(a, rb * 16 + j, t0 + tc, v, t0 + tc < T, st);
+                epilogue<WT, EPI>(a, rb * 16 + j, t0 + tc, v, t0 + tc < T, st, pre);
             }
             __syncthreads();
         }
@@ -259,95 +284,191 @@ __global__ __launch_bounds__(NW * 64) void k_linear_valu(LinArgs<WT> a) {
 }
 
 // ------------------------------------------------------------------------------------
-// MFMA path (bf16).  Token rows are processed 64 at a time (four 16-column blocks of
-// the B operand, which is read as ready-made tiles); NW waves split K.  Activations are
-// kept as hi + lo bf16 tile pairs (two MFMAs per weight tile): with bf16-rounded
-// activations alone the logits of a 32-layer model drift past 2 % of their range, and
-// the matrix cores have an order of magnitude of headroom at these widths.
+// MFMA path (bf16).  A workgroup of NW waves owns R row blocks of W at a time and NT
+// blocks of 16 token rows; its waves split K.  For every k tile a wave fetches R weight
+// tiles (the stream from memory) and the NT activation tiles (from cache), so an activation
+// tile is fetched once for R weight tiles: with R = 1 the activation fetches alone would
+// take most of a compute unit's load-issue cycles at a batch of 32.  Fetches run a ring of
+// D k tiles ahead of the matrix cores; the ring slots are register arrays indexed by the
+// unrolled loop, so nothing is copied and a wave keeps D * R KB of weights in flight.
+// Activations are hi + lo bf16 tile pairs (two MFMAs per weight tile): with bf16-rounded
+// activations alone the logits of a 32-layer model drift past 2 % of their range, and the
+// matrix cores have an order of magnitude of headroom at these widths.  Every output
+// element accumulates its k tiles in ascending order (lo, then hi) and the waves' sums
+// are added in wave order, whatever R, NT and D are: a row's result does not depend
+// on how many rows share the pass (NW is fixed per matrix shape).  Matrices with few row
+// blocks and a long K are also split along K over KS workgroups per group (SK), whose sums
+// meet in memory; KS follows the matrix shape alone and the slabs are added in order.
 // ------------------------------------------------------------------------------------
-constexpr int kMfmaTokBlocks = 4;
+constexpr int kSplitKMax = 8;       // most K slabs per row-block group
 
-template <int NW, int EPI>
+template <int NW, int R, int NT, int D, int EPI, bool SK = false>
 __global__ __launch_bounds__(NW * 64) void k_linear_mfma(LinArgs<bf16_t> a) {
-    __shared__ float red[NW][kMfmaTokBlocks][64][4];
-    const int K = a.K, KC = K >> 5, NB = a.Np >> 4;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int NE = (NT * 256 + NW * 64 - 1) / (NW * 64);     // epilogue elements per thread and row block
+    __shared__ float red[NW][NT][64][4];
+    __shared__ int s_ticket;
+    const int K = a.K, KC = K >> 5, NB = a.Np >> 4, NG = (NB + R - 1) / R;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // uniform: keeps the k range in scalar registers
     const int T = *a.count;
     const int TB = (T + 15) >> 4;
-    const int kc0 = (wave * KC) / NW, kc1 = ((wave + 1) * KC) / NW;
+    if (TB == 0) return;
+    // SK: workgroup (g, ks) takes slab ks of K for row-block group g, and TB <= NT
+    const int KS = SK ? a.KS : 1;
+    const int ks = SK ? (int)blockIdx.x % KS : 0;
+    const int slab0 = (ks * KC) / KS, slab1 = ((ks + 1) * KC) / KS;
+    const int kc0 = slab0 + (wave * (slab1 - slab0)) / NW, kc1 = slab0 + ((wave + 1) * (slab1 - slab0)) / NW;
+    const int nsteps = kc1 - kc0;
+    const int c = (tid >> 4) & 15, j = tid & 15;        // this thread's token column and weight row in the epilogue
 
-    for (int tb0 = 0; tb0 < TB; tb0 += kMfmaTokBlocks) {
-        const int nb = min(kMfmaTokBlocks, TB - tb0);
-        EntStat st[(kMfmaTokBlocks * 256) / (NW * 64) > 0 ? (kMfmaTokBlocks * 256) / (NW * 64) : 1];
+    for (int tb0 = 0; tb0 < TB; tb0 += NT) {
+        EntStat st[NE];
 #pragma unroll
-        for (auto &s : st) s.init();
-        for (int rb = blockIdx.x; rb < NB; rb += gridDim.x) {
-            f32x4_t acc[kMfmaTokBlocks];
+        for (int i = 0; i < NE; ++i) st[i].init();
+        const bf16_t *xh[NT], *xl[NT];
 #pragma unroll
-            for (int b = 0; b < kMfmaTokBlocks; ++b) acc[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            const bf16_t *wp = a.W + tile_offset(rb, kc0, KC) + lane * 8;
-            const bf16_t *xp = a.xp + tile_offset(tb0, kc0, KC) + lane * 8;
-            const bf16_t *xl = a.xp_lo + tile_offset(tb0, kc0, KC) + lane * 8;
-            const size_t xstride = (size_t)KC * 512;
-            int kc = kc0;
-            for (; kc + 2 <= kc1; kc += 2) {
-                Vec8<bf16_t> w0, w1;
-                w0.load_stream(wp); w1.load_stream(wp + 512);
+        for (int b = 0; b < NT; ++b) {       // token blocks past the end repeat the last one; their results are dropped
+            const size_t o = tile_offset(min(tb0 + b, TB - 1), kc0, KC) + lane * 8;
+            xh[b] = a.xp + o; xl[b] = a.xp_lo + o;
+        }
+        const int gstep = SK ? NG : (int)gridDim.x;
+        for (int g = SK ? (int)blockIdx.x / KS : (int)blockIdx.x; g < NG; g += gstep) {
+            f32x4_t acc[R][NT];
+            const bf16_t *wp[R];
 #pragma unroll
-                for (int b = 0; b < kMfmaTokBlocks; ++b) {
-                    if (b < nb) {
-                        Vec8<bf16_t> x0, x1, l0, l1;
-                        x0.load(xp + b * xstride); x1.load(xp + b * xstride + 512);
-                        l0.load(xl + b * xstride); l1.load(xl + b * xstride + 512);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(bf16x8_t, w0.raw), __builtin_bit_cast(bf16x8_t, l0.raw), acc[b], 0, 0, 0);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(bf16x8_t, w0.raw), __builtin_bit_cast(bf16x8_t, x0.raw), acc[b], 0, 0, 0);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(bf16x8_t, w1.raw), __builtin_bit_cast(bf16x8_t, l1.raw), acc[b], 0, 0, 0);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(bf16x8_t, w1.raw), __builtin_bit_cast(bf16x8_t, x1.raw), acc[b], 0, 0, 0);
+            for (int r = 0; r < R; ++r) {
+#pragma unroll
+                for (int b = 0; b < NT; ++b) acc[r][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                wp[r] = a.W + tile_offset(min(g * R + r, NB - 1), kc0, KC) + lane * 8;
+            }
+            Vec8<bf16_t> wa[D][R], xa[D][NT], la[D][NT];
+            // k tile i of the wave's range into ring slot s; past the end the last tile is
+            // fetched again (from cache) and not used, so no branch surrounds the loads
+            auto issue = [&](int s, int i) __attribute__((always_inline)) {
+                const size_t off = (size_t)max(min(i, nsteps - 1), 0) * 512;
+#pragma unroll
+                for (int r = 0; r < R; ++r) wa[s][r].load_stream(wp[r] + off);
+#pragma unroll
+                for (int b = 0; b < NT; ++b) { xa[s][b].load(xh[b] + off); la[s][b].load(xl[b] + off); }
+            };
+#pragma unroll
+            for (int s = 0; s < D; ++s) {    // in slot order: the waits below count on it
+                issue(s, s);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            for (int i0 = 0; i0 < nsteps; i0 += D) {
+#pragma unroll
+                for (int s = 0; s < D; ++s) {
+                    if (i0 + s < nsteps) {
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+#pragma unroll
+                            for (int b = 0; b < NT; ++b) {
+                                acc[r][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                    __builtin_bit_cast(bf16x8_t, wa[s][r].raw), __builtin_bit_cast(bf16x8_t, la[s][b].raw), acc[r][b], 0, 0, 0);
+                                acc[r][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                    __builtin_bit_cast(bf16x8_t, wa[s][r].raw), __builtin_bit_cast(bf16x8_t, xa[s][b].raw), acc[r][b], 0, 0, 0);
+                            }
+                        }
+                    }
+                    // the slot is refilled only after its last reader has been issued: moved any
+                    // earlier, the refill needs registers of its own and a copy that waits for it
+                    __builtin_amdgcn_sched_barrier(0);
+                    issue(s, i0 + s + D);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            // what the epilogues read is requested for all row blocks at once
+            EpiPre pre[R][NE];
+            if (!SK) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < NE; ++i) {
+                        const int b = (tid + i * NW * 64) >> 8, t = (tb0 + b) * 16 + c, rb = g * R + r;
+                        pre[r][i] = epi_prefetch<bf16_t, EPI>(a, rb * 16 + j, t, b < NT && rb < NB && tb0 + b < TB && t < T);
+                    }
+            }
+            // the waves' partial sums meet in LDS, one row block at a time.  D holds weight
+            // row j of token column c in lane c + 16*(j/4), register j%4.
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+#pragma unroll
+                for (int b = 0; b < NT; ++b)
+                    *reinterpret_cast<float4 *>(&red[wave][b][lane][0]) = make_float4(acc[r][b][0], acc[r][b][1], acc[r][b][2], acc[r][b][3]);
+                __syncthreads();
+                const int rb = g * R + r;
+#pragma unroll
+                for (int i = 0; i < NE; ++i) {
+                    const int b = (tid + i * NW * 64) >> 8;          // uniform within a wave
+                    if (b < NT) {
+                        float v = 0.f;
+#pragma unroll
+                        for (int w = 0; w < NW; ++w) v += red[w][b][c + 16 * (j >> 2)][j & 3];
+                        const int t = (tb0 + b) * 16 + c;
+                        if constexpr (SK)
+                            st_coherent(a.sk_part + ((((size_t)ks * NG + g) * R + r) * NT + b) * 256 + (tid & 255), v);
+                        else
+                            epilogue<bf16_t, EPI>(a, rb * 16 + j, t, v, rb < NB && tb0 + b < TB && t < T, st[i], pre[r][i]);
                     }
                 }
-                wp += 1024; xp += 1024; xl += 1024;
+                __syncthreads();
             }
-            for (; kc < kc1; ++kc) {
-                Vec8<bf16_t> w0; w0.load_stream(wp);
+            if constexpr (SK) {
+                // the slab's sums are written through to memory; the workgroup that arrives last
+                // for this group adds the slabs in order and runs the epilogue.  The counter
+                // is left at zero for the next launch.
+                wait_stores();
+                __syncthreads();
+                if (tid == 0) s_ticket = __hip_atomic_fetch_add(a.sk_tickets + g, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __syncthreads();
+                if (s_ticket == KS - 1) {
+                    if (tid == 0) st_coherent(a.sk_tickets + g, 0);
+                    // all slabs of all the group's elements, and what the epilogues read, are
+                    // requested before the first sum
 #pragma unroll
-                for (int b = 0; b < kMfmaTokBlocks; ++b) {
-                    if (b < nb) {
-                        Vec8<bf16_t> x0, l0; x0.load(xp + b * xstride); l0.load(xl + b * xstride);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(bf16x8_t, w0.raw), __builtin_bit_cast(bf16x8_t, l0.raw), acc[b], 0, 0, 0);
-                        acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(bf16x8_t, w0.raw), __builtin_bit_cast(bf16x8_t, x0.raw), acc[b], 0, 0, 0);
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int i = 0; i < NE; ++i) {
+                            const int b = (tid + i * NW * 64) >> 8, t = (tb0 + b) * 16 + c, rb = g * R + r;
+                            pre[r][i] = epi_prefetch<bf16_t, EPI>(a, rb * 16 + j, t, b < NT && rb < NB && tb0 + b < TB && t < T);
+                        }
+                    float pv[R][NE][kSplitKMax];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int i = 0; i < NE; ++i) {
+                            const int b = min((tid + i * NW * 64) >> 8, NT - 1);
+#pragma unroll
+                            for (int q = 0; q < kSplitKMax; ++q)
+                                pv[r][i][q] = ld_coherent(a.sk_part + ((((size_t)min(q, KS - 1) * NG + g) * R + r) * NT + b) * 256 + (tid & 255));
+                        }
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const int rb = g * R + r;
+#pragma unroll
+                        for (int i = 0; i < NE; ++i) {
+                            const int b = (tid + i * NW * 64) >> 8;
+                            if (b < NT) {
+                                float v = 0.f;
+#pragma unroll
+                                for (int q = 0; q < kSplitKMax; ++q) v += q < KS ? pv[r][i][q] : 0.f;
+                                const int t = (tb0 + b) * 16 + c;
+                                epilogue<bf16_t, EPI>(a, rb * 16 + j, t, v, rb < NB && tb0 + b < TB && t < T, st[i], pre[r][i]);
+                            }
+                        }
                     }
                 }
-                wp += 512; xp += 512; xl += 512;
             }
-#pragma unroll
-            for (int b = 0; b < kMfmaTokBlocks; ++b)
-                *reinterpret_cast<float4 *>(&red[wave][b][lane][0]) = make_float4(acc[b][0], acc[b][1], acc[b][2], acc[b][3]);
-            __syncthreads();
-            // element e -> (token block b, token column c, weight row j); D holds row j of
-            // column c in lane c + 16*(j/4), register j%4
-            int si = 0;
-            for (int e = tid; e < kMfmaTokBlocks * 256; e += NW * 64, ++si) {
-                const int b = e >> 8, c = (e >> 4) & 15, j = e & 15;
-                float v = 0.f;
-#pragma unroll
-                for (int w = 0; w < NW; ++w) v += red[w][b][c + 16 * (j >> 2)][j & 3];
-                const int t = (tb0 + b) * 16 + c;
-                epilogue<bf16_t, EPI>(a, rb * 16 + j, t, v, b < nb && t < T, st[si]);
-            }
-            __syncthreads();
         }
         if constexpr (EPI == EPI_LOGITS) {
-            int si = 0;
-            for (int e = tid; e < kMfmaTokBlocks * 256; e += NW * 64, ++si) {
-                const int b = e >> 8, c = (e >> 4) & 15;
-                const int t = (tb0 + b) * 16 + c;
-                logits_flush<bf16_t>(a, t, b < nb && t < T, st[si]);
+#pragma unroll
+            for (int i = 0; i < NE; ++i) {
+                const int b = (tid + i * NW * 64) >> 8;
+                if (b < NT) {
+                    const int t = (tb0 + b) * 16 + c;
+                    logits_flush<bf16_t>(a, t, tb0 + b < TB && t < T, st[i]);
+                }
             }
         }
     }
