@@ -169,6 +169,10 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=64)
     ap.add_argument("--fused", type=int, default=None, help="1/0: force the fused single-row decode kernel on/off")
     ap.add_argument("--tau", type=float, default=None, help="skip the calibration runs and use this threshold (nats)")
+    ap.add_argument("--schedule", choices=["lockstep", "grouped"], default="lockstep",
+                    help="grouped: small-model rows run ahead, large-model rows are served together")
+    ap.add_argument("--sched-start", type=float, default=0.5, help="grouped: large model starts at this share of waiting rows")
+    ap.add_argument("--sched-stop", type=float, default=0.25, help="grouped: ... and stops below this share")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for hardware byte counters)")
     args = ap.parse_args()
@@ -217,8 +221,9 @@ def main():
         log(f"[bench] tau={tau:.6f} nats -> large share {share_cal:.3f} over {n_cal} calibration tokens "
             f"at {time.time() - t0:.1f}s")
 
-    def timed(force):
+    def timed(force, grouped=False):
         e.force_model(force)
+        e.set_schedule(grouped, args.sched_start, args.sched_stop)
         e.set_gate(w, tau, d_min)
         e.begin(prompts, warmup + steps)
         e.decode(warmup)
@@ -230,15 +235,25 @@ def main():
         dt = time.perf_counter() - a
         st = e.stats()
         e.force_model(-1)
+        e.set_schedule(False)
         return dt, st
 
-    dt, st = timed(-1)
+    grouped = args.schedule == "grouped"
+    dt, st = timed(-1, grouped)
     n_tok = st["tokens_small"] + st["tokens_large"]
     tok_s = n_tok / dt
     algo_gbs = st["algorithmic_bytes"] / dt / 1e9
     log(f"[bench] EAD: {tok_s:.1f} tok/s, {algo_gbs:.0f} GB/s algorithmic ({algo_gbs / HBM_PEAK_GBS:.1%} of peak), "
         f"large share {st['large_share']:.3f}, switches {st['switches']}, host syncs {st['host_syncs']}")
     extra = {}
+    if grouped:
+        d1, s1 = timed(-1, False)
+        n1 = s1["tokens_small"] + s1["tokens_large"]
+        extra["lockstep"] = {"tokens_per_s": n1 / d1, "large_passes": s1["steps_large"], "small_passes": s1["steps_small"]}
+        extra["grouped"] = {"start": args.sched_start, "stop": args.sched_stop, "large_passes": st["steps_large"],
+                            "small_passes": st["steps_small"]}
+        log(f"[bench] lock step: {n1 / d1:.1f} tok/s with {s1['steps_large']} large / {s1['steps_small']} small passes; "
+            f"grouped: {st['steps_large']} / {st['steps_small']}")
     if not args.no_single_model:
         for name, which in (("small_only", 0), ("large_only", 1)):
             d2, s2 = timed(which)
@@ -278,7 +293,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if ss.bf16 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "small": ss.name, "large": sl.name, "batch": batch,
                    "prompt_len": [int(plo), int(phi)], "window": w, "d_min": d_min, "tau_nats": tau,
-                   "vocab": ss.vocab},
+                   "vocab": ss.vocab, "schedule": args.schedule},
         "decode_hbm_gbs": algo_gbs, "decode_hbm_frac_of_peak": algo_gbs / HBM_PEAK_GBS,
         "large_token_share": st["large_share"], "param_ratio": st["param_ratio"], "switches": st["switches"],
         "host_syncs": st["host_syncs"], **extra, "roofline": roofline,

@@ -215,6 +215,14 @@ ead_status ead_reset_stats(ead_handle *h);
 /* Run only one model for every row (0 / 1), or follow the gate (-1, the default).
  * Used to time small-only and large-only decoding on the same prompts. */
 ead_status ead_force_model(ead_handle *h, int32_t which_model_or_minus1);
+/* How rows of a batch are stepped.  grouped = 0 (default): lock step, every unfinished row
+ * produces one token per step.  grouped = 1: rows are independent instances of Algorithm 1,
+ * so rows served by the small model run ahead while rows that switched to the large model
+ * wait; the large model starts running when at least start_fraction of the unfinished rows
+ * wait for it and keeps running until fewer than stop_fraction do, so its weights are streamed
+ * once for many rows.  Outputs per row are the same (up to the rounding differences between
+ * passes of different width).  ead_decode(n) then lets every row produce up to n more tokens. */
+ead_status ead_set_schedule(ead_handle *h, int32_t grouped, float start_fraction, float stop_fraction);
 /* Single-row decode steps can run as ONE persistent kernel per step (grid barriers
  * instead of kernel boundaries, weight prefetch across them) instead of the per-layer
  * kernels that wider batches use.  Off by default; on = 1 selects it for the shapes it

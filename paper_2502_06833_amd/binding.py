@@ -82,6 +82,7 @@ _SIGNATURES = {
     "ead_reset_stats": (C.c_int, [C.c_void_p]),
     "ead_force_model": (C.c_int, [C.c_void_p, C.c_int32]),
     "ead_set_fused": (C.c_int, [C.c_void_p, C.c_int32]),
+    "ead_set_schedule": (C.c_int, [C.c_void_p, C.c_int32, C.c_float, C.c_float]),
     "ead_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),
     "ead_profile_read": (C.c_int, [C.c_void_p, C.POINTER(KernelProfile), C.c_int32, _I32P]),
 }
@@ -252,6 +253,9 @@ class EAD:
         s = Stats()
         self._check(lib().ead_get_stats(self._h, C.byref(s)))
         return {k: getattr(s, k) for k, _ in Stats._fields_}
+
+    def set_schedule(self, grouped: bool, start_fraction: float = 0.5, stop_fraction: float = 0.25):
+        self._check(lib().ead_set_schedule(self._h, 1 if grouped else 0, start_fraction, stop_fraction))
 
     def set_fused(self, on: bool):
         self._check(lib().ead_set_fused(self._h, 1 if on else 0))

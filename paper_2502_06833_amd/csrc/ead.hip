@@ -85,7 +85,8 @@ __global__ __launch_bounds__(256) void k_plan(PlanArgs a) {
         int off = 0, nlm = 0;
         for (int b = 0; b < a.batch; ++b) {
             const bool active = !a.s.done[b] && (a.ignore_model || a.s.model[b] == a.m) &&
-                                (a.step < 0 || a.s.last_step[b] != a.step);
+                                (a.step < 0 || a.s.last_step[b] != a.step) &&
+                                (a.ignore_model || a.s.ngen[b] < a.s.goal[b]);
             const int target = a.s.len[b] - a.limit_off, have = a.s.kvlen[a.m * a.s.max_batch + b];
             int n = active ? max(0, target - have) : 0;
             n = min(n, a.budget - off);
@@ -145,7 +146,7 @@ struct Model {
     size_t esz() const { return dtype == EAD_BF16 ? 2 : 4; }
 };
 
-struct HostSeq { int len, kvlen[2], model, c, ngen, done, last_step; };
+struct HostSeq { int len, kvlen[2], model, c, ngen, done, last_step, goal; };
 
 }  // namespace
 
@@ -166,6 +167,7 @@ struct ead_handle {
     std::vector<void *> allocs;
     std::vector<HostSeq> hs;
     int batch, max_new, began, replay, n_new, force_model, step;
+    int sched_grouped = 0, sched_phase = 0; float sched_hi = 0.5f, sched_lo = 0.25f;
     ead_stats stats;
     std::string err;
     // optional per-kernel event timing
@@ -428,7 +430,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
     Model &m = h->mdl[mi];
     const int d = m.d, hd = m.hd, NQ = m.H * hd, NK = m.KV * hd, F = m.F;
     constexpr bool is_bf16 = std::is_same<WT, bf16_t>::value;
-    const bool mfma = is_bf16 && T > 4;
+    const bool mfma = is_bf16 && T > 2;      // the FMA path takes 1, 2 or 4 rows a pass and is slow at 4
     hipStream_t st = h->stream;
     const int *cnt = h->plan.hdr;
     const int T16 = (T + 15) & ~15;
@@ -508,7 +510,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         g.W = (const WT *)m.lm_head; g.Np = m.V; g.K = d; g.count = cnt + 1; g.rowmap = h->plan.lm_row;
         g.partials = h->lm_part; g.logits = dump_logits ? h->logits_dump : nullptr;
         const int grid = std::min(m.V / 16, h->lm_grid);
-        if (is_bf16 && n_lm > 4) {
+        if (is_bf16 && n_lm > 2) {
             if constexpr (is_bf16) {
                 PackArgs pa{h->x, d, cnt + 1, h->plan.lm_row, m.g_final, m.eps, h->xp_a, h->xl_a, d};
                 { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3((n_lm + 15) & ~15), dim3(256), 0, st, pa); }
@@ -605,7 +607,8 @@ int host_plan(ead_handle *h, int m, int budget, int limit_off, int lm_mode, bool
     rows->assign(h->batch, 0); complete->assign(h->batch, 0);
     for (int b = 0; b < h->batch; ++b) {
         HostSeq &s = h->hs[b];
-        const bool active = !s.done && (ignore_model || s.model == m) && (step < 0 || s.last_step != step);
+        const bool active = !s.done && (ignore_model || s.model == m) && (step < 0 || s.last_step != step) &&
+                            (ignore_model || s.ngen < s.goal);
         const int target = s.len - limit_off, have = s.kvlen[m];
         int n = active ? std::max(0, target - have) : 0;
         n = std::min(n, budget - off);
@@ -670,7 +673,7 @@ ead_status begin_impl(ead_handle *h, const int32_t *toks, const int32_t *lens, i
         off += lens[b];
         len[b] = lens[b];
         HostSeq &s = h->hs[b];
-        s.len = lens[b]; s.kvlen[0] = s.kvlen[1] = 0; s.c = 0; s.ngen = 0; s.done = 0; s.last_step = -1;
+        s.len = lens[b]; s.kvlen[0] = s.kvlen[1] = 0; s.c = 0; s.ngen = 0; s.done = 0; s.last_step = -1; s.goal = max_new;
         s.model = h->force_model >= 0 ? h->force_model : (h->replay ? -1 : 0);
         model[b] = std::max(s.model, 0);
     }
@@ -682,6 +685,8 @@ ead_status begin_impl(ead_handle *h, const int32_t *toks, const int32_t *lens, i
     HIP_TRY(h, hipMemcpyAsync(h->s.ngen, zeros.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.done, zeros.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.last_step, neg.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
+    std::vector<int> goal(MB, max_new);
+    HIP_TRY(h, hipMemcpyAsync(h->s.goal, goal.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.err, zeros.data(), sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipStreamSynchronize(st));
     // both models consume every prompt token but the last
@@ -702,78 +707,148 @@ ead_status begin_impl(ead_handle *h, const int32_t *toks, const int32_t *lens, i
     return EAD_OK;
 }
 
+// One forward pass of model m over the rows the plan gives it, with the host's copy of
+// the per-sequence state advanced for the rows that produced a token.  Returns the number of
+// token rows through *T_out (0: nothing to do).  `step` gates rows that already produced a
+// token in this lock-step iteration; -1 takes every eligible row.
+ead_status decode_pass(ead_handle *h, int m, int step, std::vector<char> &emitted, int *T_out) {
+    std::vector<int> rows; std::vector<char> complete;
+    int n_lm, ctx_max;
+    const int T = host_plan(h, m, h->Tmax, 0, 1, false, step, &n_lm, &ctx_max, &rows, &complete);
+    *T_out = T;
+    if (T == 0) return EAD_OK;
+    if (T == 1 && n_lm == 1 && h->fused_on && h->mdl[m].fused_ok) {
+        const double keys = keys_in_pass(h, m, rows);
+        TRY(h->mdl[m].dtype == EAD_BF16 ? fused_step<bf16_t>(h, m, keys) : fused_step<float>(h, m, keys));
+    } else {
+        launch_plan(h, m, h->Tmax, 0, 1, false, step);
+        TRY(run_pass(h, m, T, n_lm, ctx_max, false, rows));
+        if (n_lm > 0) launch_finalize(h, m, n_lm, false);
+    }
+    account_pass(h, m, rows, n_lm > 0);
+    if (n_lm > 0) (m ? h->stats.steps_large : h->stats.steps_small)++;
+    for (int b = 0; b < h->batch; ++b) {
+        HostSeq &s = h->hs[b];
+        if (!rows[b]) continue;
+        const int extra = rows[b] - (complete[b] ? 1 : 0);
+        (m ? h->stats.catchup_rows_large : h->stats.catchup_rows_small) += extra;
+        s.kvlen[m] += rows[b];
+        if (complete[b]) {
+            emitted[b] = 1; s.last_step = step;
+            (m ? h->stats.tokens_large : h->stats.tokens_small)++;
+        }
+    }
+    return EAD_OK;
+}
+
+// Advance the host's copy of the state of the rows that produced a token, and learn from the
+// device which model serves them next -- only when that can have changed (a row's counter has
+// reached d_min, or an end-of-sequence id can end it).
+ead_status after_tokens(ead_handle *h, const std::vector<char> &emitted) {
+    hipStream_t st = h->stream;
+    bool need_sync = h->prm.eos_id >= 0;
+    for (int b = 0; b < h->batch; ++b) {
+        if (!emitted[b]) continue;
+        HostSeq &s = h->hs[b];
+        s.len++; s.ngen++; s.c++;
+        if (s.ngen >= h->max_new) s.done = 1;
+        if (h->replay || h->force_model >= 0) continue;
+        if (s.c >= h->cfg.d_min && !s.done) need_sync = true;
+    }
+    if (h->replay) {
+        // the next model is dictated: read it from the host copy of the forced ids
+        for (int b = 0; b < h->batch; ++b) {
+            HostSeq &s = h->hs[b];
+            if (!emitted[b] || s.done) continue;
+            const int nxt = h->h_model[(size_t)b * h->s.cap + s.ngen];   // forced ids staged by ead_replay
+            if (nxt != s.model) { s.model = nxt; s.c = 0; h->stats.switches++; }
+        }
+    } else if (need_sync && h->force_model < 0) {
+        HIP_TRY(h, hipMemcpyAsync(h->h_model, h->s.model, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
+        HIP_TRY(h, hipMemcpyAsync(h->h_done, h->s.done, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
+        HIP_TRY(h, hipStreamSynchronize(st));
+        h->stats.host_syncs++;
+        for (int b = 0; b < h->batch; ++b) {
+            HostSeq &s = h->hs[b];
+            if (!emitted[b]) continue;
+            if (h->h_done[b]) s.done = 1;
+            if (h->h_model[b] != s.model) { s.model = h->h_model[b]; s.c = 0; h->stats.switches++; }
+        }
+    } else if (need_sync) {
+        HIP_TRY(h, hipMemcpyAsync(h->h_done, h->s.done, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
+        HIP_TRY(h, hipStreamSynchronize(st));
+        for (int b = 0; b < h->batch; ++b) if (h->h_done[b]) h->hs[b].done = 1;
+    }
+    return EAD_OK;
+}
+
+// Grouped schedule.  Every sequence is its own instance of Algorithm 1, so rows need not move
+// in lock step: rows served by the small model run ahead through cheap small passes while rows
+// that switched to the large model wait, and one large pass then serves all that have
+// gathered -- the large model's weights are streamed once for many rows instead of once per
+// token position.  The large model starts running when at least `hi` of the unfinished rows
+// wait for it and keeps running until fewer than `lo` do (rows stay on it for at least d_min
+// tokens, so its passes come in bursts).  No row's arithmetic depends on the schedule.
+ead_status decode_grouped(ead_handle *h, int n_tokens) {
+    hipStream_t st = h->stream;
+    std::vector<int> goal(h->s.max_batch, 0);
+    for (int b = 0; b < h->batch; ++b) {
+        HostSeq &s = h->hs[b];
+        s.goal = (int)std::min<long>(h->max_new, (long)s.ngen + n_tokens);
+        goal[b] = s.goal;
+    }
+    HIP_TRY(h, hipMemcpyAsync(h->s.goal, goal.data(), h->s.max_batch * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipStreamSynchronize(st));      // `goal` leaves scope
+    std::vector<char> emitted(h->batch);
+    for (;;) {
+        int n[2] = {0, 0};
+        for (int b = 0; b < h->batch; ++b) {
+            const HostSeq &s = h->hs[b];
+            if (!s.done && s.ngen < s.goal) n[s.model ? 1 : 0]++;
+        }
+        const int N = n[0] + n[1];
+        if (N == 0) break;
+        if (n[1] == 0) h->sched_phase = 0;
+        else if (n[0] == 0) h->sched_phase = 1;
+        else if (h->sched_phase == 1 && (float)n[1] < h->sched_lo * (float)N) h->sched_phase = 0;
+        else if (h->sched_phase == 0 && (float)n[1] >= h->sched_hi * (float)N) h->sched_phase = 1;
+        const int m = h->sched_phase;
+        std::fill(emitted.begin(), emitted.end(), 0);
+        int T = 0;
+        TRY(decode_pass(h, m, -1, emitted, &T));
+        if (T == 0) return fail(h, EAD_ERR_STATE, "scheduler found no work for model %d", m);
+        TRY(after_tokens(h, emitted));
+        h->step++;
+    }
+    // pauses end here: rows may run to the bound of the run again
+    for (int b = 0; b < h->batch; ++b) { h->hs[b].goal = h->max_new; goal[b] = h->max_new; }
+    HIP_TRY(h, hipMemcpyAsync(h->s.goal, goal.data(), h->s.max_batch * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipStreamSynchronize(st));
+    return EAD_OK;
+}
+
 ead_status decode_impl(ead_handle *h, int n_steps) {
     if (!h->began) return fail(h, EAD_ERR_STATE, "ead_decode before ead_begin");
     hipStream_t st = h->stream;
-    std::vector<int> rows; std::vector<char> complete, emitted(h->batch);
+    std::vector<char> emitted(h->batch);
+    if (h->sched_grouped) {
+        TRY(decode_grouped(h, n_steps));
+        n_steps = 0;
+    }
     for (int it = 0; it < n_steps; ++it) {
         const int step = h->step;
         std::fill(emitted.begin(), emitted.end(), 0);
         bool any = false;
         for (int m = 0; m < 2; ++m) {
             for (;;) {
-                int n_lm, ctx_max;
-                const int T = host_plan(h, m, h->Tmax, 0, 1, false, step, &n_lm, &ctx_max, &rows, &complete);
+                int T = 0;
+                TRY(decode_pass(h, m, step, emitted, &T));
                 if (T == 0) break;
                 any = true;
-                if (T == 1 && n_lm == 1 && h->fused_on && h->mdl[m].fused_ok) {
-                    const double keys = keys_in_pass(h, m, rows);
-                    TRY(h->mdl[m].dtype == EAD_BF16 ? fused_step<bf16_t>(h, m, keys) : fused_step<float>(h, m, keys));
-                } else {
-                    launch_plan(h, m, h->Tmax, 0, 1, false, step);
-                    TRY(run_pass(h, m, T, n_lm, ctx_max, false, rows));
-                    if (n_lm > 0) launch_finalize(h, m, n_lm, false);
-                }
-                account_pass(h, m, rows, n_lm > 0);
-                if (n_lm > 0) (m ? h->stats.steps_large : h->stats.steps_small)++;
-                for (int b = 0; b < h->batch; ++b) {
-                    HostSeq &s = h->hs[b];
-                    if (!rows[b]) continue;
-                    const int extra = rows[b] - (complete[b] ? 1 : 0);
-                    (m ? h->stats.catchup_rows_large : h->stats.catchup_rows_small) += extra;
-                    s.kvlen[m] += rows[b];
-                    if (complete[b]) {
-                        emitted[b] = 1; s.last_step = step;
-                        (m ? h->stats.tokens_large : h->stats.tokens_small)++;
-                    }
-                }
             }
         }
         if (!any) break;
-        // advance the host's copy of the per-sequence state
-        bool need_sync = h->prm.eos_id >= 0;
-        for (int b = 0; b < h->batch; ++b) {
-            if (!emitted[b]) continue;
-            HostSeq &s = h->hs[b];
-            s.len++; s.ngen++; s.c++;
-            if (s.ngen >= h->max_new) s.done = 1;
-            if (h->replay || h->force_model >= 0) continue;
-            if (s.c >= h->cfg.d_min && !s.done) need_sync = true;
-        }
-        if (h->replay) {
-            // the next model is dictated: read it from the host copy of the forced ids
-            for (int b = 0; b < h->batch; ++b) {
-                HostSeq &s = h->hs[b];
-                if (!emitted[b] || s.done) continue;
-                const int nxt = h->h_model[(size_t)b * h->s.cap + s.ngen];   // forced ids staged by ead_replay
-                if (nxt != s.model) { s.model = nxt; s.c = 0; h->stats.switches++; }
-            }
-        } else if (need_sync && h->force_model < 0) {
-            HIP_TRY(h, hipMemcpyAsync(h->h_model, h->s.model, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
-            HIP_TRY(h, hipMemcpyAsync(h->h_done, h->s.done, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
-            HIP_TRY(h, hipStreamSynchronize(st));
-            h->stats.host_syncs++;
-            for (int b = 0; b < h->batch; ++b) {
-                HostSeq &s = h->hs[b];
-                if (!emitted[b]) continue;
-                if (h->h_done[b]) s.done = 1;
-                if (h->h_model[b] != s.model) { s.model = h->h_model[b]; s.c = 0; h->stats.switches++; }
-            }
-        } else if (need_sync) {
-            HIP_TRY(h, hipMemcpyAsync(h->h_done, h->s.done, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
-            HIP_TRY(h, hipStreamSynchronize(st));
-            for (int b = 0; b < h->batch; ++b) if (h->h_done[b]) h->hs[b].done = 1;
-        }
+        TRY(after_tokens(h, emitted));
         h->step++;
     }
     HIP_TRY(h, hipStreamSynchronize(st));
@@ -943,7 +1018,7 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
         s.max_batch = MB; s.max_seq = MS; s.cap = MS;
         TRY(dmalloc(h, &s.tokens, (size_t)MB * MS)); TRY(dmalloc(h, &s.len, (size_t)MB)); TRY(dmalloc(h, &s.kvlen, (size_t)2 * MB));
         TRY(dmalloc(h, &s.model, (size_t)MB)); TRY(dmalloc(h, &s.c, (size_t)MB)); TRY(dmalloc(h, &s.ngen, (size_t)MB));
-        TRY(dmalloc(h, &s.done, (size_t)MB)); TRY(dmalloc(h, &s.last_step, (size_t)MB));
+        TRY(dmalloc(h, &s.done, (size_t)MB)); TRY(dmalloc(h, &s.last_step, (size_t)MB)); TRY(dmalloc(h, &s.goal, (size_t)MB));
         TRY(dmalloc(h, &s.ring, (size_t)MB * 4096)); TRY(dmalloc(h, &s.err, (size_t)1));
         TRY(dmalloc(h, &s.out_tok, (size_t)MB * MS)); TRY(dmalloc(h, &s.out_mid, (size_t)MB * MS));
         TRY(dmalloc(h, &s.out_H, (size_t)MB * MS)); TRY(dmalloc(h, &s.out_Hbar, (size_t)MB * MS));
@@ -1105,14 +1180,16 @@ ead_status ead_score(ead_handle *h, int32_t which, const int32_t *tokens, int32_
     h->began = 0; h->batch = 1; h->replay = 0;
     h->hs.assign(1, HostSeq{});
     HostSeq &s = h->hs[0];
-    s.len = len; s.model = which; s.last_step = -1;
-    const int zero = 0, one_len = len, neg = -1;
+    s.len = len; s.model = which; s.last_step = -1; s.ngen = 0; s.goal = 1;
+    const int zero = 0, one_len = len, neg = -1, one = 1;
     HIP_TRY(h, hipMemcpyAsync(h->s.tokens, tokens, len * sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.len, &one_len, sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.kvlen + which * h->s.max_batch, &zero, sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.model, &which, sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.done, &zero, sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.last_step, &neg, sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.ngen, &zero, sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.goal, &one, sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipStreamSynchronize(st));
     std::vector<int> rows; std::vector<char> complete;
     for (;;) {
@@ -1159,6 +1236,15 @@ ead_status ead_trace_read(ead_handle *h, long long *out) {
     return EAD_OK;
 }
 #endif
+
+ead_status ead_set_schedule(ead_handle *h, int32_t grouped, float start_fraction, float stop_fraction) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    if (grouped && !(start_fraction > 0.f && start_fraction <= 1.f && stop_fraction >= 0.f && stop_fraction <= start_fraction))
+        return fail(h, EAD_ERR_INVALID_ARG, "need 0 < start_fraction <= 1 and 0 <= stop_fraction <= start_fraction");
+    h->sched_grouped = grouped ? 1 : 0; h->sched_phase = 0;
+    if (grouped) { h->sched_hi = start_fraction; h->sched_lo = stop_fraction; }
+    return EAD_OK;
+}
 
 ead_status ead_set_fused(ead_handle *h, int32_t on) {
     if (!h) return EAD_ERR_INVALID_ARG;

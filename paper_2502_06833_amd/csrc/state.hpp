@@ -11,6 +11,7 @@ struct SeqState {
     int *len;               // tokens present
     int *kvlen;             // [2][max_batch] positions each model has consumed
     int *model, *c, *ngen, *done, *last_step;
+    int *goal;              // tokens a sequence may have generated before it pauses (<= the run's bound)
     float *ring;            // [max_batch][w_cap]
     int *out_tok; uint8_t *out_mid; float *out_H; float *out_Hbar; uint8_t *out_dec;   // [max_batch][cap]
     int *forced_tok; uint8_t *forced_mid;                                              // replay, [max_batch][cap]

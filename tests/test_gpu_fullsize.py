@@ -136,4 +136,19 @@ def test_qwen_truncated_batch_with_ragged_prompts_and_catchups():
     for b in range(B):
         if b not in checked:
             assert np.abs(rp["H"][b] - free["H"][b]).max() < 2e-3
+    # the grouped schedule (small-model rows run ahead, large-model rows served together)
+    # replays the same trajectories to the same entropies and decisions
+    e.set_schedule(True, 0.5, 0.25)
+    rg = e.replay(prompts, ft, fm)
+    sg = e.stats()
+    assert sg["tokens_small"] + sg["tokens_large"] == B * n_new
+    for b in checked:
+        r = refs[b]
+        assert np.abs(rg["H"][b] - r["H"]).max() < TOL_H, b
+        safe = np.abs(r["Hbar"] - tau) > BAND
+        want_next = np.concatenate([r["model_id"][1:], rg["next_model"][b][-1:]])
+        assert (rg["next_model"][b][safe] == want_next[safe]).all(), b
+    assert np.abs(rg["H"] - rp["H"]).max() < 2e-3
+    lock_large, grouped_large = st["steps_large"], sg["steps_large"]
+    print(f"large-model passes: lock step {lock_large}, grouped {grouped_large}", flush=True)
     e.close()

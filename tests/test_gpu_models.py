@@ -122,6 +122,41 @@ def test_batch_rows_are_independent(tiny):
         assert np.abs(one["H"][0] - both["H"][b]).max() < 1e-5
 
 
+def test_grouped_schedule_gives_the_same_rows(tiny):
+    """Rows are independent instances of the algorithm: letting small-model rows run ahead and
+    serving large-model rows in groups must reproduce the lock-step run row by row, whatever
+    the grouping thresholds, also when the run is cut into several decode calls."""
+    e, os_, ol = tiny
+    prompts = [si.prompt_np(s, "g", n, 512) for s, n in ((0, 16), (1, 9), (2, 23), (3, 12))]
+    tau = _calibrate_tau(os_, ol, prompts[0], 48, 5, 50)
+    e.set_gate(5, tau, 4)
+    e.set_schedule(False)
+    lock = e.generate(prompts, 48)
+    assert 0 < lock["model_id"].mean() < 1
+    ref0 = oracle.generate(os_, ol, prompts[0], 48, 5, tau, d_min=4)
+    assert (lock["tokens"][0] == ref0["tokens"]).all() and (lock["model_id"][0] == ref0["model_id"]).all()
+    try:
+        for hi, lo in ((0.5, 0.25), (1.0, 0.0), (0.26, 0.26)):
+            e.set_schedule(True, hi, lo)
+            got = e.generate(prompts, 48)
+            assert (got["tokens"] == lock["tokens"]).all(), (hi, lo)
+            assert (got["model_id"] == lock["model_id"]).all(), (hi, lo)
+            assert np.abs(got["H"] - lock["H"]).max() < 1e-5
+            assert np.abs(got["Hbar"] - lock["Hbar"]).max() < 1e-5
+            st = e.stats()
+            assert st["tokens_small"] + st["tokens_large"] == 4 * 48
+        # the same run in pieces: every row gets up to n tokens per call
+        e.set_schedule(True, 0.5, 0.25)
+        e.begin(prompts, 48)
+        for n in (1, 7, 13, 100):
+            e.decode(n)
+        got = e.fetch()
+        assert (got["tokens"] == lock["tokens"]).all() and (got["model_id"] == lock["model_id"]).all()
+        assert (got["lens"] == 48).all()
+    finally:
+        e.set_schedule(False)
+
+
 def test_catchup_invariance(tiny):
     """Logits after a catch-up equal that model's logits scored from scratch on the same tokens."""
     e, os_, ol = tiny
