@@ -387,7 +387,8 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
     const int NT = TB <= 1 ? 1 : (TB == 2 ? 2 : 4);
     int cfg = !big ? 1 : (NB >= 4 * 256 ? 4 : 2);       // 1: (4 waves, R=1)  4: (4, R=4)  2: (8 waves, R=2)  5: (4, R=4, split K)
     int grid = (NB + cfg - 1) / cfg;
-    if (cfg == 2 && TB <= 4 && EPI != EPI_LOGITS) {
+    // (the rotary / cache-append epilogue is too heavy to be left to one workgroup per group)
+    if (cfg == 2 && TB <= 4 && EPI != EPI_LOGITS && EPI != EPI_QKV) {
         const int NG = (NB + 3) / 4;
         int KS = std::min(kSplitKMax, std::max(1, (2 * h->n_cu + NG / 2) / NG));
         while (KS > 1 && (a.K / 32) / KS < 16) --KS;                   // a slab keeps at least 16 k tiles
@@ -401,9 +402,9 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
         case 11: EAD_LM(4, 1, 1, 8, false); break; case 12: EAD_LM(4, 1, 2, 6, false); break; case 14: EAD_LM(4, 1, 4, 4, false); break;
         case 21: EAD_LM(8, 2, 1, 8, false); break; case 22: EAD_LM(8, 2, 2, 6, false); break; case 24: EAD_LM(8, 2, 4, 3, false); break;
         case 41: EAD_LM(4, 4, 1, 6, false); break; case 42: EAD_LM(4, 4, 2, 4, false); break; case 44: EAD_LM(4, 4, 4, 3, false); break;
-        case 51: if constexpr (EPI != EPI_LOGITS) EAD_LM(4, 4, 1, 6, true); break;
-        case 52: if constexpr (EPI != EPI_LOGITS) EAD_LM(4, 4, 2, 4, true); break;
-        default: if constexpr (EPI != EPI_LOGITS) EAD_LM(4, 4, 4, 3, true); break;
+        case 51: if constexpr (EPI != EPI_LOGITS && EPI != EPI_QKV) EAD_LM(4, 4, 1, 6, true); break;
+        case 52: if constexpr (EPI != EPI_LOGITS && EPI != EPI_QKV) EAD_LM(4, 4, 2, 4, true); break;
+        default: if constexpr (EPI != EPI_LOGITS && EPI != EPI_QKV) EAD_LM(4, 4, 4, 3, true); break;
     }
 #undef EAD_LM
 }

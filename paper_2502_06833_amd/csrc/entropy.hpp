@@ -228,8 +228,8 @@ struct GateStepArgs {
 };
 
 // One workgroup per row, one wave per step of the launch: the waves finish the entropies
-// of their steps from the partials side by side, then one thread takes the steps in order
-// through the window and the switch rule (which make them sequential per row).
+// of their steps from the partials side by side; the window means follow side by side too,
+// and only the switch rule (a counter and a model per row) is taken step by step by one thread.
 constexpr int kGateMaxWindow = 4096;    // largest rolling window w (entries kept in LDS)
 
 __global__ __launch_bounds__(kGateMaxSteps * 64) void k_gate_step(GateStepArgs a) {
@@ -258,20 +258,37 @@ __global__ __launch_bounds__(kGateMaxSteps * 64) void k_gate_step(GateStepArgs a
     }
     __syncthreads();
     if (!a.st.ring) return;
+    // Window means of all steps side by side (thread s: step s), each summed oldest to newest
+    // as the definition reads: entropy number g of the row is s_H[g - n] if this launch
+    // produced it, else still in the ring.  Only the switch rule itself is sequential.
+    __shared__ float s_hb[kGateMaxSteps];
+    const int n = a.st.n[r], w = a.cfg.w;
+    if ((int)threadIdx.x < a.steps) {
+        const int g1 = n + (int)threadIdx.x, cnt = min(g1 + 1, w);
+        float sum = 0.f;
+        for (int g = g1 - cnt + 1; g <= g1; ++g) sum = sum + (g >= n ? s_H[g - n] : s_ring[g % w]);
+        s_hb[threadIdx.x] = sum / (float)cnt;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
-        int model = a.st.model[r], c = a.st.c[r], n = a.st.n[r];
+        int model = a.st.model[r], c = a.st.c[r];
         for (int s = 0; s < a.steps; ++s) {
             const size_t o = (size_t)s * a.rows + r;
             if (a.model_id_out) a.model_id_out[o] = (uint8_t)model;
-            const float hb = gate_update(s_ring, n, s_H[s], a.cfg, &model, &c);
-            ++n;
+            const float hb = s_hb[s];
+            ++c;
+            if (c >= a.cfg.d_min) {
+                if (model == 0 && hb > a.cfg.tau) { model = 1; c = 0; }
+                else if (model == 1 && hb <= a.cfg.tau) { model = 0; c = 0; }
+            }
             if (a.Hbar_out) a.Hbar_out[o] = hb;
             if (a.next_out) a.next_out[o] = (uint8_t)model;
         }
-        a.st.model[r] = model; a.st.c[r] = c; a.st.n[r] = n;
+        a.st.model[r] = model; a.st.c[r] = c; a.st.n[r] = n + a.steps;
     }
-    __syncthreads();
-    for (int i = threadIdx.x; i < a.cfg.w; i += blockDim.x) a.st.ring[(size_t)r * a.cfg.w + i] = s_ring[i];
+    // the ring keeps the last w entropies: slots of the newest min(steps, w) are distinct
+    for (int s = max(0, a.steps - w) + (int)threadIdx.x; s < a.steps; s += blockDim.x)
+        a.st.ring[(size_t)r * w + (n + s) % w] = s_H[s];
 }
 
 }  // namespace ead
