@@ -189,11 +189,11 @@ ead_status fail(ead_handle *h, ead_status st, const char *fmt, ...) {
 }
 
 enum ProfKind { PK_EMBED = 0, PK_PACK_ACT, PK_FMA_QKV, PK_FMA_RES, PK_FMA_SWIGLU, PK_FMA_LOGITS, PK_MFMA_QKV,
-                PK_MFMA_RES, PK_MFMA_SWIGLU, PK_MFMA_LOGITS, PK_ATTN_PARTIAL, PK_ATTN_COMBINE, PK_PLAN, PK_FINALIZE,
+                PK_MFMA_RES, PK_MFMA_SWIGLU, PK_MFMA_LOGITS, PK_ATTN, PK_PLAN, PK_FINALIZE,
                 PK_FUSED, PK_COUNT };
 const char *const kProfNames[PK_COUNT] = {"embed", "pack_act", "linear_fma_qkv", "linear_fma_res", "linear_fma_swiglu",
                                           "linear_fma_logits", "linear_mfma_qkv", "linear_mfma_res", "linear_mfma_swiglu",
-                                          "linear_mfma_logits", "attention", "attn_combine", "plan", "lm_finalize",
+                                          "linear_mfma_logits", "attention", "plan", "lm_finalize",
                                           "decode_fused"};
 
 // Brackets the launches made during its lifetime with two events (profiling mode only).
@@ -416,7 +416,7 @@ void launch_attn(ead_handle *h, int mi, AttnArgs<KT> &a, int G, int T, double kv
     const bool per_head = (long)T * a.n_kv_heads * a.max_splits <= 64;
     dim3 grid(a.max_splits, per_head ? a.n_heads : a.n_kv_heads, T);
     {
-        ProfScope ps(h, PK_ATTN_PARTIAL, mi, kv_bytes);
+        ProfScope ps(h, PK_ATTN, mi, kv_bytes);
 #define EAD_LA(G_) do { if (per_head) hipLaunchKernelGGL((k_attn<KT, HD, G_, 1>), grid, dim3(kAttnWaves * 64), 0, h->stream, a); \
                         else hipLaunchKernelGGL((k_attn<KT, HD, G_, G_>), grid, dim3(kAttnWaves * 64), 0, h->stream, a); } while (0)
         switch (G) { case 1: EAD_LA(1); break; case 2: EAD_LA(2); break; case 4: EAD_LA(4); break;
