@@ -74,6 +74,19 @@ def lib():
                                       C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_int32,
                                       C.c_int32, C.c_int32, C.POINTER(C.c_int32),
                                       C.POINTER(C.c_uint8), _FP, _FP]
+        L.oracle_generate_sampled.restype = C.c_int32
+        L.oracle_generate_sampled.argtypes = [C.POINTER(_CModel), C.POINTER(_CModel), C.POINTER(C.c_int32),
+                                              C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_int32,
+                                              C.c_int32, C.c_int32, C.c_float, C.c_uint64, C.c_int32,
+                                              C.POINTER(C.c_int32), C.POINTER(C.c_uint8), _FP, _FP]
+        L.oracle_philox4x32_10.restype = None
+        L.oracle_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+        L.oracle_uniform.restype = C.c_float
+        L.oracle_uniform.argtypes = [C.c_uint64, C.c_int32, C.c_int32, C.c_int32]
+        L.oracle_gumbel.restype = C.c_float
+        L.oracle_gumbel.argtypes = [C.c_uint64, C.c_int32, C.c_int32, C.c_int32]
+        L.oracle_sample.restype = C.c_int32
+        L.oracle_sample.argtypes = [_FP, C.c_int32, C.c_float, C.c_uint64, C.c_int32, C.c_int32]
         L.oracle_num_threads.restype = C.c_int32
         L.oracle_num_threads.argtypes = []
         _lib = L
@@ -193,26 +206,53 @@ class Model:
         return out
 
 
+def philox4x32_10(counter, key):
+    """One block of the counter-based generator behind the sampler (four 32-bit words)."""
+    c = (C.c_uint32 * 4)(*[int(x) & 0xFFFFFFFF for x in counter])
+    k = (C.c_uint32 * 2)(*[int(x) & 0xFFFFFFFF for x in key])
+    out = (C.c_uint32 * 4)()
+    lib().oracle_philox4x32_10(c, k, out)
+    return [int(x) for x in out]
+
+
+def uniform(seed: int, seq_index: int, token_index: int, i: int) -> float:
+    return float(lib().oracle_uniform(seed, seq_index, token_index, i))
+
+
+def gumbel(seed: int, seq_index: int, token_index: int, V: int) -> np.ndarray:
+    """The noise g_i = -ln(-ln u_i) the sampler adds to l_i / T, for i < V (float32)."""
+    L = lib()
+    return np.array([L.oracle_gumbel(seed, seq_index, token_index, i) for i in range(V)], dtype=np.float32)
+
+
+def sample(logits, temperature: float, seed: int, seq_index: int, token_index: int) -> int:
+    """y ~ softmax(logits / temperature) by the Gumbel-max identity; temperature <= 0: arg max."""
+    l = _f32(logits)
+    return int(lib().oracle_sample(_fp(l), l.size, C.c_float(temperature), seed, seq_index, token_index))
+
+
 def generate(small: Model, large: Model, prompt, max_new: int, w: int, tau: float,
-             d_min: int = 10, unit: int = NATS, eos_id: int = -1):
-    """Algorithm 1, greedy.  Returns dict(tokens, model_id, H, Hbar)."""
+             d_min: int = 10, unit: int = NATS, eos_id: int = -1, temperature: float = 0.0,
+             seed: int = 0, seq_index: int = 0):
+    """Algorithm 1 (greedy, or sampled at a temperature).  Returns dict(tokens, model_id, H, Hbar)."""
     p = np.ascontiguousarray(prompt, dtype=np.int32)
     tok = np.zeros(max_new, dtype=np.int32)
     mid = np.zeros(max_new, dtype=np.uint8)
     H = np.zeros(max_new, dtype=np.float32)
     Hb = np.zeros(max_new, dtype=np.float32)
-    n = lib().oracle_generate(C.byref(small.c), C.byref(large.c),
-                              p.ctypes.data_as(C.POINTER(C.c_int32)), p.size, max_new, w,
-                              C.c_float(tau), d_min, unit, eos_id,
-                              tok.ctypes.data_as(C.POINTER(C.c_int32)),
-                              mid.ctypes.data_as(C.POINTER(C.c_uint8)), _fp(H), _fp(Hb))
+    n = lib().oracle_generate_sampled(C.byref(small.c), C.byref(large.c),
+                                      p.ctypes.data_as(C.POINTER(C.c_int32)), p.size, max_new, w,
+                                      C.c_float(tau), d_min, unit, eos_id,
+                                      C.c_float(temperature), seed, seq_index,
+                                      tok.ctypes.data_as(C.POINTER(C.c_int32)),
+                                      mid.ctypes.data_as(C.POINTER(C.c_uint8)), _fp(H), _fp(Hb))
     if n < 0:
         raise ValueError(f"oracle_generate failed ({n})")
     return {"tokens": tok[:n], "model_id": mid[:n], "H": H[:n], "Hbar": Hb[:n]}
 
 
 def replay(small: Model, large: Model, tokens, model_id, prompt_len: int, w: int, tau: float,
-           d_min: int = 10, unit: int = NATS):
+           d_min: int = 10, unit: int = NATS, temperature: float = 0.0, seed: int = 0, seq_index: int = 0):
     """Teacher-forced pass along a given trajectory.
 
     tokens: prompt followed by the generated tokens; model_id[i]: the model that
@@ -230,6 +270,7 @@ def replay(small: Model, large: Model, tokens, model_id, prompt_len: int, w: int
             logits[m] = mdl.forward_dense(tokens[:-1])
     H = np.zeros(n, dtype=np.float32)
     am = np.zeros(n, dtype=np.int32)
+    choice = np.zeros(n, dtype=np.int32)
     Hbar = np.zeros(n, dtype=np.float32)
     nxt = np.zeros(n, dtype=np.uint8)
     c = 0
@@ -239,9 +280,10 @@ def replay(small: Model, large: Model, tokens, model_id, prompt_len: int, w: int
             c = 0
         h, a = entropy(logits[m][prompt_len + i - 1], unit)
         H[i], am[i] = h, a
+        choice[i] = sample(logits[m][prompt_len + i - 1], temperature, seed, seq_index, i) if temperature > 0 else a
         Hbar[i] = window_mean(H[: i + 1], w)
         nm, c = gate_step(m, c, float(Hbar[i]), tau, d_min)
         nxt[i] = nm
         if nm != m:
             c = 0
-    return {"H": H, "argmax": am, "Hbar": Hbar, "next_model": nxt, "logits": logits}
+    return {"H": H, "argmax": am, "choice": choice, "Hbar": Hbar, "next_model": nxt, "logits": logits}

@@ -21,7 +21,9 @@
  * brute force; hand-derived gate traces; the parameter-ratio column of the
  * paper's Table 1; the forward pass against an independent float64 NumPy
  * derivation, its single-token closed form, causality, rotary invariants and
- * the cached-vs-dense identity.  The paper's accuracy claims (benchmark scores,
+ * the cached-vs-dense identity; the sampler against the generator's published
+ * known-answer vectors, an independent integer re-implementation, chi-square
+ * tests of sampled frequencies against softmax(l/T), and its T -> 0 limit.  The paper's accuracy claims (benchmark scores,
  * best threshold range) need its dataset and trained weights: parity unpinned.
  */
 #include <math.h>
@@ -325,16 +327,86 @@ int32_t oracle_forward_dense(const oracle_model *m, const int32_t *tokens, int32
 }
 
 /* ------------------------------------------------------------------------- */
-/* Algorithm 1 with greedy decoding (token = argmax of the raw logits).       */
+/* Algorithm 1's sampling step: y ~ softmax(l / T) (temperature T > 0).       */
+/* Written as the Gumbel-max identity: with u_i independent uniforms on (0,1) */
+/* and g_i = -ln(-ln u_i), argmax_i (l_i / T + g_i) is distributed exactly as */
+/* softmax(l / T).  The entropy of Eq. 1-2 is still taken from the raw logits.*/
+/*                                                                            */
+/* The uniforms come from a counter-based generator, so that a draw is a pure */
+/* function of (seed, sequence, token index, vocabulary index) and needs no   */
+/* state: Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, "Parallel   */
+/* random numbers: as easy as 1, 2, 3", SC 2011).  One round maps the counter */
+/* (c0,c1,c2,c3) under the key (k0,k1) to                                     */
+/*   (hi(M1*c2) ^ c1 ^ k0, lo(M1*c2), hi(M0*c0) ^ c3 ^ k1, lo(M0*c0))         */
+/* and the key is bumped by the Weyl constants between rounds.                */
+/* key = the 64-bit seed; counter = (i / 4, token index, sequence index, 0);  */
+/* logit i uses output word i % 4.  u = (2k + 1) / 2^24 with k the top 23     */
+/* bits of the word: strictly inside (0, 1) and exact in float.               */
+/* The score l/T + g is formed in float with one fused multiply-add, because  */
+/* it decides an integer: both sides of a parity test must round it alike.    */
+/* ------------------------------------------------------------------------- */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; ++r) {
+        uint64_t p0 = M0 * c0, p1 = M1 * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += W0; k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+float oracle_uniform(uint64_t seed, int32_t seq_index, int32_t token_index, int32_t i)
+{
+    uint32_t ctr[4] = { (uint32_t)i >> 2, (uint32_t)token_index, (uint32_t)seq_index, 0u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) }, out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    uint32_t k = out[i & 3] >> 9;
+    return (float)(2u * k + 1u) * (1.0f / 16777216.0f);
+}
+
+float oracle_gumbel(uint64_t seed, int32_t seq_index, int32_t token_index, int32_t i)
+{
+    return -logf(-logf(oracle_uniform(seed, seq_index, token_index, i)));
+}
+
+/* y ~ softmax(l / T); T <= 0 selects greedy decoding.  Lowest index on ties. */
+int32_t oracle_sample(const float *l, int32_t V, float temperature, uint64_t seed,
+                      int32_t seq_index, int32_t token_index)
+{
+    int32_t best = 0;
+    if (!(temperature > 0.0f)) {
+        for (int32_t i = 1; i < V; ++i) if (l[i] > l[best]) best = i;
+        return best;
+    }
+    const float inv_t = 1.0f / temperature;
+    float bs = -INFINITY;
+    for (int32_t i = 0; i < V; ++i) {
+        float s = fmaf(l[i], inv_t, oracle_gumbel(seed, seq_index, token_index, i));
+        if (s > bs) { bs = s; best = i; }
+    }
+    return best;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Algorithm 1.  temperature <= 0: greedy (token = argmax of the raw logits); */
+/* otherwise the token is sampled as above (seq_index tells batch rows apart).*/
 /* Each model conditions on the whole sequence x + y: a model that was idle   */
 /* first consumes the tokens it has not seen (no entropy is recorded there).  */
 /* Outputs have room for max_new entries; returns the number generated, or    */
 /* a negative value on error.                                                 */
 /* ------------------------------------------------------------------------- */
-int32_t oracle_generate(const oracle_model *small, const oracle_model *large,
-                        const int32_t *prompt, int32_t n_prompt, int32_t max_new,
-                        int32_t w, float tau, int32_t d_min, int32_t unit, int32_t eos_id,
-                        int32_t *out_tokens, uint8_t *out_model, float *out_H, float *out_Hbar)
+int32_t oracle_generate_sampled(const oracle_model *small, const oracle_model *large,
+                                const int32_t *prompt, int32_t n_prompt, int32_t max_new,
+                                int32_t w, float tau, int32_t d_min, int32_t unit, int32_t eos_id,
+                                float temperature, uint64_t seed, int32_t seq_index,
+                                int32_t *out_tokens, uint8_t *out_model, float *out_H, float *out_Hbar)
 {
     if (small->vocab != large->vocab || n_prompt < 1 || w < 1 || d_min < 1) return -1;
     int32_t V = small->vocab, total = n_prompt + max_new;
@@ -353,7 +425,8 @@ int32_t oracle_generate(const oracle_model *small, const oracle_model *large,
             if (oracle_forward_cached(mdl[model], cc, seq[cc->len], last ? logits : NULL)) { rc = -2; goto done; }
         }
         int32_t tok;
-        float H = (float)oracle_entropy(logits, V, unit, &tok);
+        float H = (float)oracle_entropy(logits, V, unit, &tok);      /* entropy of the raw logits */
+        if (temperature > 0.0f) tok = oracle_sample(logits, V, temperature, seed, seq_index, n);
         W[n] = H;
         float Hbar = oracle_window_mean(W, n + 1, w);
         out_tokens[n] = tok; out_model[n] = (uint8_t)model; out_H[n] = H;
@@ -367,6 +440,15 @@ done:
     oracle_cache_free(cache[0]); oracle_cache_free(cache[1]);
     free(seq); free(logits); free(W);
     return rc;
+}
+
+int32_t oracle_generate(const oracle_model *small, const oracle_model *large,
+                        const int32_t *prompt, int32_t n_prompt, int32_t max_new,
+                        int32_t w, float tau, int32_t d_min, int32_t unit, int32_t eos_id,
+                        int32_t *out_tokens, uint8_t *out_model, float *out_H, float *out_Hbar)
+{
+    return oracle_generate_sampled(small, large, prompt, n_prompt, max_new, w, tau, d_min, unit, eos_id,
+                                   0.0f, 0u, 0, out_tokens, out_model, out_H, out_Hbar);
 }
 
 int32_t oracle_num_threads(void)
