@@ -173,6 +173,7 @@ def main():
                     help="grouped: small-model rows run ahead, large-model rows are served together")
     ap.add_argument("--sched-start", type=float, default=0.5, help="grouped: large model starts at this share of waiting rows")
     ap.add_argument("--sched-stop", type=float, default=0.25, help="grouped: ... and stops below this share")
+    ap.add_argument("--temperature", type=float, default=0.0, help="sample at this temperature (0 = greedy, the default)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for hardware byte counters)")
     args = ap.parse_args()
@@ -205,6 +206,8 @@ def main():
     log(f"[bench] handle created at {time.time() - t0:.1f}s")
     if args.fused is not None:
         e.set_fused(bool(args.fused))
+    if args.temperature > 0:
+        e.set_sampling(args.temperature, args.seed)
 
     if args.copy_probe:
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").fill_(1.0)
@@ -294,7 +297,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if ss.bf16 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "small": ss.name, "large": sl.name, "batch": batch,
                    "prompt_len": [int(plo), int(phi)], "window": w, "d_min": d_min, "tau_nats": tau,
-                   "vocab": ss.vocab, "schedule": args.schedule},
+                   "vocab": ss.vocab, "schedule": args.schedule, "temperature": args.temperature},
         "decode_hbm_gbs": algo_gbs, "decode_hbm_frac_of_peak": algo_gbs / HBM_PEAK_GBS,
         "large_token_share": st["large_share"], "param_ratio": st["param_ratio"], "switches": st["switches"],
         "host_syncs": st["host_syncs"], **extra, "roofline": roofline,

@@ -164,7 +164,9 @@ ead_status ead_score(ead_handle *h, int32_t which_model, const int32_t *tokens, 
 /* Algorithm 1 along a GIVEN trajectory: at generated position i the logits come
  * from model forced_model_id[row, i] (with whatever catch-up that model needs), the
  * token appended is forced_tokens[row, i], and the library reports what it computed:
- *   out_argmax [batch, n_new], out_entropy, out_window_mean as in ead_generate,
+ *   out_argmax [batch, n_new]: the token the library itself would have emitted there (the arg
+ *   max, or its sampled token while a temperature is set); out_entropy, out_window_mean as in
+ *   ead_generate,
  *   out_decision [batch, n_new]: the model Eq. 4 selects for the next token when the
  *   current model is forced_model_id[row, i] and the dwell counter follows the forced ids.
  * All arrays are host memory; prompts as in ead_generate. */
@@ -215,6 +217,17 @@ ead_status ead_reset_stats(ead_handle *h);
 /* Run only one model for every row (0 / 1), or follow the gate (-1, the default).
  * Used to time small-only and large-only decoding on the same prompts. */
 ead_status ead_force_model(ead_handle *h, int32_t which_model_or_minus1);
+/* Algorithm 1's sampling step.  temperature = 0 (default): greedy, the token is the arg max of
+ * the raw logits (lowest index on ties).  temperature > 0: the token is drawn from
+ * softmax(logits / temperature) inside the LM head's epilogue, as
+ * argmax_i (l_i / T + g_i) with g_i = -ln(-ln u_i) (Gumbel-max), u_i from Philox-4x32-10 keyed
+ * by `seed` with counter (i / 4, index of the generated token, row of the batch, 0) -- a run
+ * is reproducible from (seed, prompts).  Entropies are those of the raw logits either way
+ * (Section 3.1).  In ead_replay the forced tokens are followed; the tokens the library
+ * would have drawn are what it reports.  Takes effect from the next decode step.  The
+ * single-kernel decode path (ead_set_fused) decodes greedily and is not used while
+ * temperature > 0. */
+ead_status ead_set_sampling(ead_handle *h, float temperature, uint64_t seed);
 /* How rows of a batch are stepped.  grouped = 0 (default): lock step, every unfinished row
  * produces one token per step.  grouped = 1: rows are independent instances of Algorithm 1,
  * so rows served by the small model run ahead while rows that switched to the large model

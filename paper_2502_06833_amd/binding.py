@@ -83,6 +83,7 @@ _SIGNATURES = {
     "ead_force_model": (C.c_int, [C.c_void_p, C.c_int32]),
     "ead_set_fused": (C.c_int, [C.c_void_p, C.c_int32]),
     "ead_set_schedule": (C.c_int, [C.c_void_p, C.c_int32, C.c_float, C.c_float]),
+    "ead_set_sampling": (C.c_int, [C.c_void_p, C.c_float, C.c_uint64]),
     "ead_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),
     "ead_profile_read": (C.c_int, [C.c_void_p, C.POINTER(KernelProfile), C.c_int32, _I32P]),
 }
@@ -247,7 +248,8 @@ class EAD:
         self._check(lib().ead_replay(self._h, _ptr(flat, _I32P), _ptr(lens, _I32P), B, n, _ptr(ft, _I32P),
                                      _ptr(fm, _U8P), _ptr(am, _I32P), _ptr(H, _F32P), _ptr(Hb, _F32P),
                                      _ptr(dec, _U8P)))
-        return {"argmax": am, "H": H, "Hbar": Hb, "next_model": dec}
+        # "choice": the token the library itself would have emitted (arg max, or the sampled one)
+        return {"argmax": am, "choice": am, "H": H, "Hbar": Hb, "next_model": dec}
 
     def stats(self) -> dict:
         s = Stats()
@@ -256,6 +258,9 @@ class EAD:
 
     def set_schedule(self, grouped: bool, start_fraction: float = 0.5, stop_fraction: float = 0.25):
         self._check(lib().ead_set_schedule(self._h, 1 if grouped else 0, start_fraction, stop_fraction))
+
+    def set_sampling(self, temperature: float, seed: int = 0):
+        self._check(lib().ead_set_sampling(self._h, temperature, seed))
 
     def set_fused(self, on: bool):
         self._check(lib().ead_set_fused(self._h, 1 if on else 0))

@@ -135,7 +135,10 @@ __host__ __device__ __forceinline__ size_t tile_offset(int rb, int kc, int KC) {
 struct EntStat {
     float m, Z, S;
     int idx;
-    __device__ __forceinline__ void init() { m = -INFINITY; Z = 0.f; S = 0.f; idx = 0x7FFFFFFF; }
+    // sampling (Algorithm 1's y ~ softmax(l / T)): running maximum of the perturbed scores
+    // l_i / T + g_i and where it is (lowest index on ties); unused when decoding greedily
+    float gs; int gidx;
+    __device__ __forceinline__ void init() { m = -INFINITY; Z = 0.f; S = 0.f; idx = 0x7FFFFFFF; gs = -INFINITY; gidx = 0x7FFFFFFF; }
     __device__ __forceinline__ void merge(const EntStat &o) {
         if (o.Z == 0.f) return;                      // empty set
         if (Z == 0.f) { *this = o; return; }
@@ -145,6 +148,7 @@ struct EntStat {
         float nS = ea * (S + da * Z) + eb * (o.S + db * o.Z);
         float nZ = ea * Z + eb * o.Z;
         if (o.m > m || (o.m == m && o.idx < idx)) idx = o.idx;
+        if (o.gs > gs || (o.gs == gs && o.gidx < gidx)) { gs = o.gs; gidx = o.gidx; }
         m = M; Z = nZ; S = nS;
     }
 };
@@ -154,9 +158,40 @@ __device__ __forceinline__ EntStat wave_merge(EntStat s) {
         EntStat t;
         t.m = __shfl_xor(s.m, o, kWave); t.Z = __shfl_xor(s.Z, o, kWave);
         t.S = __shfl_xor(s.S, o, kWave); t.idx = __shfl_xor(s.idx, o, kWave);
+        t.gs = __shfl_xor(s.gs, o, kWave); t.gidx = __shfl_xor(s.gidx, o, kWave);
         s.merge(t);
     }
     return s;
+}
+
+// ---- sampling noise ------------------------------------------------------------------
+// Algorithm 1 samples y ~ softmax(l / T).  By the Gumbel-max identity that is
+// argmax_i (l_i / T + g_i) with g_i = -ln(-ln u_i) and u_i independent uniforms on (0, 1),
+// which folds into the LM head's running arg max: no pass over materialised logits.
+// The uniforms are a pure function of (seed, sequence, token index, vocabulary index):
+// Philox-4x32 with 10 rounds (Salmon et al., "Parallel random numbers: as easy as 1, 2, 3",
+// SC 2011), key = seed, counter = (i / 4, token index, sequence, 0), word i % 4;
+// u = (2k + 1) / 2^24 with k the word's top 23 bits (exact in fp32, never 0 or 1).
+struct Philox4 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
+    constexpr uint32_t kMul0 = 0xD2511F53u, kMul1 = 0xCD9E8D57u, kWeyl0 = 0x9E3779B9u, kWeyl1 = 0xBB67AE85u;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(kMul0, c0), lo0 = kMul0 * c0;
+        const uint32_t hi1 = __umulhi(kMul1, c2), lo1 = kMul1 * c2;
+        c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+        k0 += kWeyl0; k1 += kWeyl1;
+    }
+    return Philox4{c0, c1, c2, c3};
+}
+
+__device__ __forceinline__ float gumbel_noise(uint32_t k0, uint32_t k1, int seq, int token_index, int i) {
+    const Philox4 r = philox4x32_10((uint32_t)i >> 2, (uint32_t)token_index, (uint32_t)seq, 0u, k0, k1);
+    const int lane = i & 3;
+    const uint32_t word = lane == 0 ? r.x : (lane == 1 ? r.y : (lane == 2 ? r.z : r.w));
+    const float u = (float)(2u * (word >> 9) + 1u) * (1.0f / 16777216.0f);
+    return -logf(-logf(u));
 }
 
 }  // namespace ead

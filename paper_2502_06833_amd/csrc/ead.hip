@@ -168,6 +168,8 @@ struct ead_handle {
     std::vector<HostSeq> hs;
     int batch, max_new, began, replay, n_new, force_model, step;
     int sched_grouped = 0, sched_phase = 0; float sched_hi = 0.5f, sched_lo = 0.25f;
+    float samp_temp = 0.f; uint64_t samp_seed = 0;        // temperature 0: greedy
+    int scoring = 0;                                       // inside ead_score: logits of given tokens, nothing is sampled
     ead_stats stats;
     std::string err;
     // optional per-kernel event timing
@@ -510,6 +512,10 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         LinArgs<WT> g{};
         g.W = (const WT *)m.lm_head; g.Np = m.V; g.K = d; g.count = cnt + 1; g.rowmap = h->plan.lm_row;
         g.partials = h->lm_part; g.logits = dump_logits ? h->logits_dump : nullptr;
+        if (h->samp_temp > 0.f && !h->scoring) {
+            g.samp_inv_t = 1.0f / h->samp_temp; g.samp_k0 = (uint32_t)h->samp_seed; g.samp_k1 = (uint32_t)(h->samp_seed >> 32);
+            g.samp_seq = h->plan.lm_seq; g.samp_ngen = h->s.ngen;
+        }
         const int grid = std::min(m.V / 16, h->lm_grid);
         if (is_bf16 && n_lm > 2) {
             if constexpr (is_bf16) {
@@ -575,6 +581,7 @@ FinArgs make_fin(ead_handle *h, int m, bool score) {
     fa.score_mode = score ? 1 : 0; fa.sc_H = h->sc_H; fa.sc_arg = h->sc_arg;
     fa.model_id = m; fa.max_new = h->max_new; fa.eos_id = h->prm.eos_id; fa.replay = h->replay; fa.n_new = h->n_new;
     fa.force_model = h->force_model; fa.step = h->step;
+    fa.sampling = (!score && h->samp_temp > 0.f) ? 1 : 0;
     return fa;
 }
 
@@ -718,7 +725,7 @@ ead_status decode_pass(ead_handle *h, int m, int step, std::vector<char> &emitte
     const int T = host_plan(h, m, h->Tmax, 0, 1, false, step, &n_lm, &ctx_max, &rows, &complete);
     *T_out = T;
     if (T == 0) return EAD_OK;
-    if (T == 1 && n_lm == 1 && h->fused_on && h->mdl[m].fused_ok) {
+    if (T == 1 && n_lm == 1 && h->fused_on && h->mdl[m].fused_ok && !(h->samp_temp > 0.f)) {
         const double keys = keys_in_pass(h, m, rows);
         TRY(h->mdl[m].dtype == EAD_BF16 ? fused_step<bf16_t>(h, m, keys) : fused_step<float>(h, m, keys));
     } else {
@@ -1179,6 +1186,7 @@ ead_status ead_score(ead_handle *h, int32_t which, const int32_t *tokens, int32_
         if (tokens[i] < 0 || tokens[i] >= m.V) return fail(h, EAD_ERR_INVALID_ARG, "token %d out of range", i);
     hipStream_t st = h->stream;
     h->began = 0; h->batch = 1; h->replay = 0;
+    struct Scoring { ead_handle *h; Scoring(ead_handle *h_) : h(h_) { h->scoring = 1; } ~Scoring() { h->scoring = 0; } } scoring_guard(h);
     h->hs.assign(1, HostSeq{});
     HostSeq &s = h->hs[0];
     s.len = len; s.model = which; s.last_step = -1; s.ngen = 0; s.goal = 1;
@@ -1244,6 +1252,13 @@ ead_status ead_set_schedule(ead_handle *h, int32_t grouped, float start_fraction
         return fail(h, EAD_ERR_INVALID_ARG, "need 0 < start_fraction <= 1 and 0 <= stop_fraction <= start_fraction");
     h->sched_grouped = grouped ? 1 : 0; h->sched_phase = 0;
     if (grouped) { h->sched_hi = start_fraction; h->sched_lo = stop_fraction; }
+    return EAD_OK;
+}
+
+ead_status ead_set_sampling(ead_handle *h, float temperature, uint64_t seed) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    if (!(temperature >= 0.f) || !std::isfinite(temperature)) return fail(h, EAD_ERR_INVALID_ARG, "temperature must be finite and >= 0");
+    h->samp_temp = temperature; h->samp_seed = seed;
     return EAD_OK;
 }
 

@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256) void k_entropy_partial(EntArgs<T> a) {
         Z = wave_sum(Z); S2 = wave_sum(S2);
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) idx = min(idx, __shfl_xor(idx, o, kWave));
-        if ((tid & 63) == 0) { EntPartial e; e.m = gmx; e.Z = Z; e.S = S2; e.idx = idx; s_fin[tid >> 6] = e; }
+        if ((tid & 63) == 0) { EntPartial e; e.m = gmx; e.Z = Z; e.S = S2; e.idx = idx; e.gs = -INFINITY; e.gidx = 0x7FFFFFFF; s_fin[tid >> 6] = e; }
         __syncthreads();
         if (tid == 0) {
             EntPartial e;
@@ -166,6 +166,7 @@ __global__ __launch_bounds__(256) void k_entropy_partial(EntArgs<T> a) {
             e.Z = ((s_fin[0].Z + s_fin[1].Z) + s_fin[2].Z) + s_fin[3].Z;
             e.S = (((s_fin[0].S + s_fin[1].S) + s_fin[2].S) + s_fin[3].S) * kLn2;
             e.idx = min(min(s_fin[0].idx, s_fin[1].idx), min(s_fin[2].idx, s_fin[3].idx));
+            e.gs = -INFINITY; e.gidx = 0x7FFFFFFF;          // no sampling on materialised logits
             a.partials[item] = e;
         }
         item = __builtin_amdgcn_readfirstlane(nitem); it = nit;
@@ -184,7 +185,7 @@ __global__ __launch_bounds__(256) void k_entropy_partial(EntArgs<T> a) {
 __device__ __forceinline__ EntStat merge_partials(const EntPartial *p, int n) {
     EntStat st; st.init();
     for (int i = threadIdx.x & 63; i < n; i += 64) {
-        EntStat q; q.m = p[i].m; q.Z = p[i].Z; q.S = p[i].S; q.idx = p[i].idx;
+        EntStat q; q.m = p[i].m; q.Z = p[i].Z; q.S = p[i].S; q.idx = p[i].idx; q.gs = p[i].gs; q.gidx = p[i].gidx;
         st.merge(q);
     }
     return wave_merge(st);

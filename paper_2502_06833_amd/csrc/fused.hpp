@@ -573,6 +573,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_decode_fused(FusedArgs<WT> a)
             EntStat q;
             q.m = ld_coherent(&a.lm_part[i].m); q.Z = ld_coherent(&a.lm_part[i].Z);
             q.S = ld_coherent(&a.lm_part[i].S); q.idx = ld_coherent(&a.lm_part[i].idx);
+            q.gs = -INFINITY; q.gidx = 0x7FFFFFFF;      // this kernel decodes greedily (the host keeps sampled runs off it)
             r.merge(q);
         }
         r = wave_merge(r);

@@ -16,7 +16,7 @@ namespace ead {
 
 enum Epilogue { EPI_QKV = 0, EPI_RES = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
 
-struct EntPartial { float m, Z, S; int idx; };
+struct EntPartial { float m, Z, S; int idx; float gs; int gidx; };
 
 template <typename WT>
 struct LinArgs {
@@ -45,6 +45,10 @@ struct LinArgs {
     // LOGITS
     EntPartial *partials;   // [rows][gridDim.x]
     float *logits;          // optional dump [rows][Np]
+    // LOGITS with sampling: inverse temperature (0 = greedy), generator key, and where to find
+    // the sequence of LM row t and its count of generated tokens
+    float samp_inv_t; uint32_t samp_k0, samp_k1;
+    const int *samp_seq, *samp_ngen;
     // MFMA path with K split over KS workgroups per row-block group
     int KS;
     float *sk_part;         // [KS][groups][R][NT][256] partial sums
@@ -80,6 +84,8 @@ __device__ __forceinline__ EpiPre epi_prefetch(const LinArgs<WT> &a, int p, int 
             const int pp = p < NQ ? p : p - NQ;
             e.cs = a.rope[(size_t)e.pos * (hd >> 1) + ((pp % hd) >> 1)];
         }
+    } else if constexpr (EPI == EPI_LOGITS) {
+        if (a.samp_inv_t > 0.f) { e.seq = a.samp_seq[t]; e.pos = a.samp_ngen[e.seq]; }
     }
     return e;
 }
@@ -124,6 +130,10 @@ __device__ __forceinline__ void epilogue(const LinArgs<WT> &a, int p, int t, flo
     } else {                                          // EPI_LOGITS: fold the logit into (m, Z, S, argmax)
         if (!valid) return;
         if (a.logits) a.logits[(size_t)t * a.Np + p] = v;
+        if (a.samp_inv_t > 0.f) {                     // perturbed score l/T + g; rows come in rising order
+            const float sc = fmaf(v, a.samp_inv_t, gumbel_noise(a.samp_k0, a.samp_k1, pre.seq, pre.pos, p));
+            if (sc > st.gs) { st.gs = sc; st.gidx = p; }
+        }
         if (st.Z == 0.f) { st.m = v; st.Z = 1.f; st.S = 0.f; st.idx = p; }
         else if (v > st.m) {
             float d = st.m - v, e = __expf(d);
@@ -144,11 +154,13 @@ __device__ __forceinline__ void logits_flush(const LinArgs<WT> &a, int t, bool v
         EntStat q;
         q.m = __shfl_xor(st.m, o, kWave); q.Z = __shfl_xor(st.Z, o, kWave);
         q.S = __shfl_xor(st.S, o, kWave); q.idx = __shfl_xor(st.idx, o, kWave);
+        q.gs = __shfl_xor(st.gs, o, kWave); q.gidx = __shfl_xor(st.gidx, o, kWave);
         st.merge(q);
     }
     if (valid && (threadIdx.x & 15) == 0) {
         EntPartial *d = a.partials + (size_t)t * gridDim.x + blockIdx.x;
         put(&d->m, st.m, COH); put(&d->Z, st.Z, COH); put(&d->S, st.S, COH); put(&d->idx, st.idx, COH);
+        put(&d->gs, st.gs, COH); put(&d->gidx, st.gidx, COH);
     }
 }
 

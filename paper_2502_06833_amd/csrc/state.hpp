@@ -26,6 +26,7 @@ struct FinArgs {
     const EntPartial *partials; int n_part; int unit;
     int score_mode; float *sc_H; int *sc_arg;      // score: indexed by position
     int model_id, max_new, eos_id, replay, n_new, force_model, step;
+    int sampling;            // 1: the token is the sampled one (st.gidx), else the arg max
 };
 
 // Algorithm 1's bookkeeping for sequence b once the entropy statistics of its logits are
@@ -36,9 +37,10 @@ __device__ __forceinline__ void lm_finalize_seq(const FinArgs &a, int b, const E
     int next = cur, c = a.s.c[b];
     const float hb = gate_update(a.s.ring + (size_t)b * a.cfg.w, n, H, a.cfg, &next, &c);
     const size_t o = (size_t)b * a.s.cap + n;
-    a.s.out_tok[o] = st.idx; a.s.out_mid[o] = (uint8_t)cur; a.s.out_H[o] = H; a.s.out_Hbar[o] = hb;
+    const int choice = a.sampling ? st.gidx : st.idx;
+    a.s.out_tok[o] = choice; a.s.out_mid[o] = (uint8_t)cur; a.s.out_H[o] = H; a.s.out_Hbar[o] = hb;
     a.s.out_dec[o] = (uint8_t)next;
-    int tok = st.idx;
+    int tok = choice;
     if (a.replay) {
         tok = a.s.forced_tok[o];
         const int nxt = (n + 1 < a.n_new) ? a.s.forced_mid[o + 1] : cur;
