@@ -34,6 +34,9 @@ WORKLOADS = {
     "qwen_05b_14b_b32": ("qwen", 32, 256, 256, 256, 0.25, 10),
     "qwen_05b_14b_b64": ("qwen", 64, 128, 1024, 128, 0.25, 10),
     "tiny_fp32_b1": ("tiny", 1, 16, 16, 64, 0.40, 10),
+    # the paper's other pair shapes, batch 1
+    "llama_1b_3b_b1": ("llama_1b_3b", 1, 512, 512, 1024, 0.40, 10),
+    "qwen_15b_14b_b1": ("qwen_15b_14b", 1, 512, 512, 1024, 0.25, 10),
     # stand-alone entropy / arg-max / window / switch epilogue on materialised logits
     "entropy_gate_b64": (None, 64, 0, 0, 4096, None, 10),
 }

@@ -251,8 +251,8 @@ ead_status check_model(const ead_model_desc *m, const char *name) {
         return fail(nullptr, EAD_ERR_SHAPE, "%s model: head_dim must be 32, 64 or 128", name);
     if (m->n_heads % m->n_kv_heads) return fail(nullptr, EAD_ERR_SHAPE, "%s model: n_heads not a multiple of n_kv_heads", name);
     const int G = m->n_heads / m->n_kv_heads;
-    if (G != 1 && G != 2 && G != 4 && G != 5 && G != 7 && G != 8)
-        return fail(nullptr, EAD_ERR_SHAPE, "%s model: n_heads/n_kv_heads must be one of 1, 2, 4, 5, 7, 8", name);
+    if (G < 1 || G > 8)
+        return fail(nullptr, EAD_ERR_SHAPE, "%s model: n_heads/n_kv_heads must be between 1 and 8", name);
     if (m->dtype == EAD_F32 && (m->d_model > 4096 || m->d_ffn > 4096))
         return fail(nullptr, EAD_ERR_SHAPE, "%s model: float32 weights are supported up to width 4096", name);
     if (m->d_ffn > 15360 || m->d_model > 15360) return fail(nullptr, EAD_ERR_SHAPE, "%s model: width above 15360", name);
@@ -421,8 +421,8 @@ void launch_attn(ead_handle *h, int mi, AttnArgs<KT> &a, int G, int T, double kv
         ProfScope ps(h, PK_ATTN, mi, kv_bytes);
 #define EAD_LA(G_) do { if (per_head) hipLaunchKernelGGL((k_attn<KT, HD, G_, 1>), grid, dim3(kAttnWaves * 64), 0, h->stream, a); \
                         else hipLaunchKernelGGL((k_attn<KT, HD, G_, G_>), grid, dim3(kAttnWaves * 64), 0, h->stream, a); } while (0)
-        switch (G) { case 1: EAD_LA(1); break; case 2: EAD_LA(2); break; case 4: EAD_LA(4); break;
-                     case 5: EAD_LA(5); break; case 7: EAD_LA(7); break; default: EAD_LA(8); break; }
+        switch (G) { case 1: EAD_LA(1); break; case 2: EAD_LA(2); break; case 3: EAD_LA(3); break; case 4: EAD_LA(4); break;
+                     case 5: EAD_LA(5); break; case 6: EAD_LA(6); break; case 7: EAD_LA(7); break; default: EAD_LA(8); break; }
 #undef EAD_LA
     }
 }

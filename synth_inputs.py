@@ -218,13 +218,18 @@ TINY_S = ModelShape("tiny-s", 2, 128, 4, 4, 512, 512, 1e-5, 1e4, bf16=False)
 TINY_L = ModelShape("tiny-l", 4, 256, 8, 8, 1024, 512, 1e-5, 1e4, bf16=False)
 LLAMA_1B = ModelShape("llama-1b", 16, 2048, 32, 8, 8192, 128256, 1e-5, 5e5)
 LLAMA_8B = ModelShape("llama-8b", 32, 4096, 32, 8, 14336, 128256, 1e-5, 5e5)
+LLAMA_3B = ModelShape("llama-3b", 28, 3072, 24, 8, 8192, 128256, 1e-5, 5e5)
 QWEN_05B = ModelShape("qwen-0.5b", 24, 896, 14, 2, 4864, 151936, 1e-6, 1e6)
+QWEN_15B = ModelShape("qwen-1.5b", 28, 1536, 12, 2, 8960, 151936, 1e-6, 1e6)
 QWEN_14B = ModelShape("qwen-14b", 48, 5120, 40, 8, 13824, 151936, 1e-6, 1e6)
 
 PAIRS = {
     "tiny": (TINY_S, TINY_L),
     "llama": (LLAMA_1B, LLAMA_8B),
     "qwen": (QWEN_05B, QWEN_14B),
+    # the paper's other pairs (size ratios 3x and about 9x)
+    "llama_1b_3b": (LLAMA_1B, LLAMA_3B),
+    "qwen_15b_14b": (QWEN_15B, QWEN_14B),
 }
 
 

@@ -189,7 +189,7 @@ def test_eos_and_errors(tiny):
         e.generate([prompt] * 5, 4)                               # exceeds max_batch
 
 
-@pytest.mark.parametrize("pair,layers,T", [("llama", 2, 24), ("qwen", 2, 24)])
+@pytest.mark.parametrize("pair,layers,T", [("llama", 2, 24), ("qwen", 2, 24), ("llama_1b_3b", 2, 24), ("qwen_15b_14b", 2, 24)])
 def test_bf16_truncated_pair_score_and_replay(pair, layers, T):
     """Full-width, depth-truncated bf16 pairs: teacher-forced logits / entropy / arg max for
     single rows (FMA path) and 24-row chunks (MFMA path), then Algorithm 1 along the oracle's
