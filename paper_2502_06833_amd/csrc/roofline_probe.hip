@@ -2,7 +2,9 @@
 // with constant weights straight through the C ABI, decodes a few single-row steps with
 // each model, and runs one plain copy kernel of known size as the reference point for
 // byte counters.  Values do not matter for traffic, only shapes do.
-//   rocprofv3 --pmc FETCH_SIZE --output-format csv -d out -- ./roofline_probe
+//   rocprofv3 --pmc FETCH_SIZE --output-format csv -d out -- ./roofline_probe [steps] [batch] [prompt_len]
+// batch > 1 decodes that many identical rows together (the matrix-core path of the linear
+// layers), for counters of the batched kernels.
 #include <hip/hip_runtime.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -61,12 +63,14 @@ static void build(const Shape &s, Built &b) {
 
 int main(int argc, char **argv) {
     const int steps = argc > 1 ? atoi(argv[1]) : 4;
-    const int prompt_len = 512;
+    const int batch = argc > 2 ? atoi(argv[2]) : 1;
+    const int prompt_len = argc > 3 ? atoi(argv[3]) : 512;
+    if (steps < 1 || batch < 1 || batch > 256 || prompt_len < 1 || prompt_len > 4096) { fprintf(stderr, "usage: roofline_probe [steps] [batch<=256] [prompt_len<=4096]\n"); return 2; }
     Built S, L;
     build(Shape{16, 2048, 32, 8, 8192, 128256, 1e-5f, 5e5f}, S);
     build(Shape{32, 4096, 32, 8, 14336, 128256, 1e-5f, 5e5f}, L);
     CK(hipDeviceSynchronize());
-    ead_params p{5, 1e30f, 10, EAD_NATS, 1, prompt_len + 2 * steps + 8, -1, nullptr};
+    ead_params p{5, 1e30f, 10, EAD_NATS, batch, prompt_len + 2 * steps + 8, -1, nullptr};
     ead_handle *h = nullptr;
     if (ead_create(&S.d, &L.d, &p, &h) != EAD_OK) { fprintf(stderr, "ead_create: %s\n", ead_last_error(nullptr)); return 1; }
     // reference copy: 1 GiB read + 1 GiB written
@@ -78,15 +82,15 @@ int main(int argc, char **argv) {
         CK(hipDeviceSynchronize());
         CK(hipFree(a)); CK(hipFree(b));
     }
-    std::vector<int32_t> prompt(prompt_len);
-    for (int i = 0; i < prompt_len; ++i) prompt[i] = (i * 7919) % 128256;
-    const int32_t len = prompt_len;
+    std::vector<int32_t> prompt((size_t)prompt_len * batch);
+    for (size_t i = 0; i < prompt.size(); ++i) prompt[i] = (int32_t)((i * 7919) % 128256);
+    std::vector<int32_t> lens(batch, prompt_len);
     for (int which = 0; which < 2; ++which) {
-        if (ead_force_model(h, which) != EAD_OK || ead_begin(h, prompt.data(), &len, 1, steps) != EAD_OK ||
+        if (ead_force_model(h, which) != EAD_OK || ead_begin(h, prompt.data(), lens.data(), batch, steps) != EAD_OK ||
             ead_decode(h, steps) != EAD_OK) { fprintf(stderr, "decode: %s\n", ead_last_error(h)); return 1; }
     }
     ead_stats st; ead_get_stats(h, &st);
-    printf("probe done: %d steps per model, last run large tokens %lld\n", steps, (long long)st.tokens_large);
+    printf("probe done: %d steps per model, batch %d, last run large tokens %lld\n", steps, batch, (long long)st.tokens_large);
     ead_destroy(h);
     return 0;
 }
