@@ -109,6 +109,52 @@ def test_extreme_thresholds(tiny):
     e.force_model(-1)
 
 
+def test_degenerate_shapes_of_a_run(tiny):
+    """Prompts of a single token, a single new token, a window longer than the run, a window of
+    one with d_min = 1 (a catch-up in one direction or the other at almost every step), a run
+    that ends exactly at max_seq, and rows of one batch that end at different times (eos)."""
+    e, os_, ol = tiny
+    one = si.prompt_np(9, "one", 1, 512)
+    # single-token prompt: nothing to prefill, the first decode step feeds the only token
+    for w, d_min, n in ((5, 10, 12), (64, 2, 20), (1, 1, 30)):
+        tau = _calibrate_tau(os_, ol, one, n, w, 50)
+        ref = oracle.generate(os_, ol, one, n, w, tau, d_min=d_min)
+        e.set_gate(w, tau, d_min)
+        rp = e.replay([one], ref["tokens"], ref["model_id"])
+        assert np.abs(rp["H"][0] - ref["H"]).max() < 1e-4, (w, d_min)
+        assert np.abs(rp["Hbar"][0] - ref["Hbar"]).max() < 1e-4
+        assert (rp["argmax"][0] == ref["tokens"]).all()
+        if w == 1:
+            assert (np.diff(ref["model_id"].astype(int)) != 0).sum() >= 5      # the gate really flips
+            safe = np.abs(ref["Hbar"] - tau) > 1e-4
+            if safe.all():
+                out = e.generate([one], n)
+                assert (out["tokens"][0] == ref["tokens"]).all() and (out["model_id"][0] == ref["model_id"]).all()
+    # one new token
+    e.set_gate(5, 0.0, 10)
+    out = e.generate([si.prompt_np(9, "p", 7, 512)], 1)
+    ref = oracle.generate(os_, ol, si.prompt_np(9, "p", 7, 512), 1, 5, 0.0)
+    assert out["tokens"][0, 0] == ref["tokens"][0] and abs(out["H"][0, 0] - ref["H"][0]) < 1e-4
+    # exactly max_seq positions (the fixture's handle has max_seq = 128)
+    p100 = si.prompt_np(9, "long", 100, 512)
+    out = e.generate([p100], 28)
+    ref = oracle.generate(os_, ol, p100, 28, 5, 0.0)
+    assert (out["lens"] == 28).all() and np.abs(out["H"][0] - ref["H"]).max() < 1e-4
+    # rows that end at different times: eos = row 0's 4th token
+    prompts = [si.prompt_np(s, "eos", 10, 512) for s in (20, 21, 22)]
+    e.set_gate(5, 1e30, 10)
+    free = e.generate(prompts, 16)
+    eos = int(free["tokens"][0, 3])
+    e.set_gate(5, 1e30, 10, eos_id=eos)
+    cut = e.generate(prompts, 16)
+    for b in range(3):
+        hits = np.nonzero(free["tokens"][b] == eos)[0]
+        want = int(hits[0]) + 1 if len(hits) else 16
+        assert cut["lens"][b] == want, (b, cut["lens"], want)
+        assert (cut["tokens"][b, :want] == free["tokens"][b, :want]).all()
+    e.set_gate(5, 0.0, 10)
+
+
 def test_batch_rows_are_independent(tiny):
     e, os_, ol = tiny
     prompts = [si.prompt_np(s, "b", n, 512) for s, n in ((0, 16), (1, 9), (2, 23), (3, 16))]
