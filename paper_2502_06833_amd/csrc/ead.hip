@@ -69,9 +69,15 @@ __global__ __launch_bounds__(256) void k_copy(const WT *src, WT *dst, size_t n) 
     if (i < n) dst[i] = src[i];
 }
 
+constexpr int kAllowWords = 8;       // sequences a host-side allow mask can name (64 per word)
+
 struct PlanArgs {
     SeqState s; Plan p;
     int batch, m, budget, limit_off, lm_mode, ignore_model, step;
+    // When the two models' passes run side by side on two streams, the other stream may be changing
+    // the state of ITS sequences while this plan is built.  The host names the sequences of this
+    // pass (their state is at rest); all others are left out whatever their state reads.
+    int use_allow; unsigned long long allow[kAllowWords];
 };
 
 // Rows of one forward pass of model m: for every sequence that m serves, the positions
@@ -84,7 +90,8 @@ __global__ __launch_bounds__(256) void k_plan(PlanArgs a) {
     if (tid == 0) {
         int off = 0, nlm = 0;
         for (int b = 0; b < a.batch; ++b) {
-            const bool active = !a.s.done[b] && (a.ignore_model || a.s.model[b] == a.m) &&
+            const bool allowed = !a.use_allow || ((a.allow[b >> 6] >> (b & 63)) & 1ull);
+            const bool active = allowed && !a.s.done[b] && (a.ignore_model || a.s.model[b] == a.m) &&
                                 (a.step < 0 || a.s.last_step[b] != a.step) &&
                                 (a.ignore_model || a.s.ngen[b] < a.s.goal[b]);
             const int target = a.s.len[b] - a.limit_off, have = a.s.kvlen[a.m * a.s.max_batch + b];
@@ -150,6 +157,20 @@ struct HostSeq { int len, kvlen[2], model, c, ngen, done, last_step, goal; };
 
 }  // namespace
 
+// Everything one forward pass writes besides the per-sequence state and its model's KV cache.
+// There are two sets, and the second has a stream of its own, so that a pass of the small model
+// and a pass of the large model can run side by side (they serve disjoint sequences).
+struct LaneSet {
+    hipStream_t stream = nullptr;
+    float *x = nullptr, *q = nullptr, *o = nullptr, *hbuf = nullptr;
+    bf16_t *xp_a = nullptr, *xp_o = nullptr, *xp_h = nullptr, *xl_a = nullptr, *xl_o = nullptr, *xl_h = nullptr;
+    float *sk_part = nullptr; int *sk_tickets = nullptr;
+    float *part_o = nullptr; float2 *part_ml = nullptr; int *tickets = nullptr; EntPartial *lm_part = nullptr;
+    Plan plan{};
+    int *rb_model = nullptr, *rb_done = nullptr;      // pinned: what the host reads back after a pass
+    hipEvent_t done_ev = nullptr;
+};
+
 struct ead_handle {
     Model mdl[2];
     ead_params prm;
@@ -161,6 +182,7 @@ struct ead_handle {
     float *sk_part; int *sk_tickets;     // split-K partial sums of the MFMA path
     float *part_o; float2 *part_ml; int *tickets; EntPartial *lm_part; float *logits_dump; float *sc_H; int *sc_arg;
     int *h_model, *h_done;   // pinned
+    LaneSet lanes[2]; int cur_lane = 0, two_lanes = 0; hipStream_t lane1_stream = nullptr;
     // fused single-row decode
     long long *trace = nullptr;
     float *att_o; float2 *att_ml; unsigned *bar_mem; int *abort_flag; unsigned bar_epoch = 0; int fused_on = 0, fused_grid = 0;
@@ -188,6 +210,27 @@ ead_status fail(ead_handle *h, ead_status st, const char *fmt, ...) {
     va_list ap; va_start(ap, fmt); vsnprintf(buf, sizeof buf, fmt, ap); va_end(ap);
     if (h) h->err = buf; else g_create_error = buf;
     return st;
+}
+
+// the scratch set and stream the launches that follow use
+void use_lane(ead_handle *h, int i) {
+    if (!h->two_lanes) i = 0;
+    const LaneSet &l = h->lanes[i];
+    h->stream = l.stream;
+    h->x = l.x; h->q = l.q; h->o = l.o; h->hbuf = l.hbuf;
+    h->xp_a = l.xp_a; h->xp_o = l.xp_o; h->xp_h = l.xp_h; h->xl_a = l.xl_a; h->xl_o = l.xl_o; h->xl_h = l.xl_h;
+    h->sk_part = l.sk_part; h->sk_tickets = l.sk_tickets;
+    h->part_o = l.part_o; h->part_ml = l.part_ml; h->tickets = l.tickets; h->lm_part = l.lm_part;
+    h->plan = l.plan;
+    h->cur_lane = i;
+}
+void save_lane(ead_handle *h, int i) {
+    LaneSet &l = h->lanes[i];
+    l.x = h->x; l.q = h->q; l.o = h->o; l.hbuf = h->hbuf;
+    l.xp_a = h->xp_a; l.xp_o = h->xp_o; l.xp_h = h->xp_h; l.xl_a = h->xl_a; l.xl_o = h->xl_o; l.xl_h = h->xl_h;
+    l.sk_part = h->sk_part; l.sk_tickets = h->sk_tickets;
+    l.part_o = h->part_o; l.part_ml = h->part_ml; l.tickets = h->tickets; l.lm_part = h->lm_part;
+    l.plan = h->plan;
 }
 
 enum ProfKind { PK_EMBED = 0, PK_PACK_ACT, PK_FMA_QKV, PK_FMA_RES, PK_FMA_SWIGLU, PK_FMA_LOGITS, PK_MFMA_QKV,
@@ -632,8 +675,13 @@ int host_plan(ead_handle *h, int m, int budget, int limit_off, int lm_mode, bool
     return off;
 }
 
-void launch_plan(ead_handle *h, int m, int budget, int limit_off, int lm_mode, bool ignore_model, int step) {
-    PlanArgs pa{h->s, h->plan, h->batch, m, budget, limit_off, lm_mode, ignore_model ? 1 : 0, step};
+void launch_plan(ead_handle *h, int m, int budget, int limit_off, int lm_mode, bool ignore_model, int step,
+                 const std::vector<int> *rows = nullptr) {
+    PlanArgs pa{h->s, h->plan, h->batch, m, budget, limit_off, lm_mode, ignore_model ? 1 : 0, step, 0, {0}};
+    if (rows && h->two_lanes) {          // name the sequences of this pass (see PlanArgs)
+        pa.use_allow = 1;
+        for (int b = 0; b < h->batch; ++b) if ((*rows)[b] > 0) pa.allow[b >> 6] |= 1ull << (b & 63);
+    }
     ProfScope ps(h, PK_PLAN, m, 0.0);
     hipLaunchKernelGGL(k_plan, dim3(1), dim3(256), 3 * h->batch * sizeof(int), h->stream, pa);
 }
@@ -669,6 +717,8 @@ ead_status validate_prompts(ead_handle *h, const int32_t *toks, const int32_t *l
 }
 
 ead_status begin_impl(ead_handle *h, const int32_t *toks, const int32_t *lens, int batch, int max_new) {
+    use_lane(h, 0);
+    if (h->two_lanes) HIP_TRY(h, hipStreamSynchronize(h->lanes[1].stream));
     TRY(validate_prompts(h, toks, lens, batch, max_new));
     hipStream_t st = h->stream;
     const int MB = h->s.max_batch, MS = h->s.max_seq;
@@ -725,11 +775,11 @@ ead_status decode_pass(ead_handle *h, int m, int step, std::vector<char> &emitte
     const int T = host_plan(h, m, h->Tmax, 0, 1, false, step, &n_lm, &ctx_max, &rows, &complete);
     *T_out = T;
     if (T == 0) return EAD_OK;
-    if (T == 1 && n_lm == 1 && h->fused_on && h->mdl[m].fused_ok && !(h->samp_temp > 0.f)) {
+    if (T == 1 && n_lm == 1 && h->batch == 1 && h->fused_on && h->mdl[m].fused_ok && !(h->samp_temp > 0.f)) {
         const double keys = keys_in_pass(h, m, rows);
         TRY(h->mdl[m].dtype == EAD_BF16 ? fused_step<bf16_t>(h, m, keys) : fused_step<float>(h, m, keys));
     } else {
-        launch_plan(h, m, h->Tmax, 0, 1, false, step);
+        launch_plan(h, m, h->Tmax, 0, 1, false, step, &rows);
         TRY(run_pass(h, m, T, n_lm, ctx_max, false, rows));
         if (n_lm > 0) launch_finalize(h, m, n_lm, false);
     }
@@ -752,8 +802,12 @@ ead_status decode_pass(ead_handle *h, int m, int step, std::vector<char> &emitte
 // Advance the host's copy of the state of the rows that produced a token, and learn from the
 // device which model serves them next -- only when that can have changed (a row's counter has
 // reached d_min, or an end-of-sequence id can end it).
-ead_status after_tokens(ead_handle *h, const std::vector<char> &emitted) {
-    hipStream_t st = h->stream;
+// The read-back goes through the current lane's stream; all_lanes: rows of both lanes produced
+// tokens (lock step), so the other lane's stream is waited for first.
+ead_status after_tokens(ead_handle *h, const std::vector<char> &emitted, bool all_lanes) {
+    LaneSet &ln = h->lanes[h->cur_lane];
+    hipStream_t st = ln.stream;
+    int *rb_model = ln.rb_model, *rb_done = ln.rb_done;
     bool need_sync = h->prm.eos_id >= 0;
     for (int b = 0; b < h->batch; ++b) {
         if (!emitted[b]) continue;
@@ -772,20 +826,22 @@ ead_status after_tokens(ead_handle *h, const std::vector<char> &emitted) {
             if (nxt != s.model) { s.model = nxt; s.c = 0; h->stats.switches++; }
         }
     } else if (need_sync && h->force_model < 0) {
-        HIP_TRY(h, hipMemcpyAsync(h->h_model, h->s.model, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
-        HIP_TRY(h, hipMemcpyAsync(h->h_done, h->s.done, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
+        if (all_lanes && h->two_lanes) HIP_TRY(h, hipStreamSynchronize(h->lanes[1 - h->cur_lane].stream));
+        HIP_TRY(h, hipMemcpyAsync(rb_model, h->s.model, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
+        HIP_TRY(h, hipMemcpyAsync(rb_done, h->s.done, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
         HIP_TRY(h, hipStreamSynchronize(st));
         h->stats.host_syncs++;
         for (int b = 0; b < h->batch; ++b) {
             HostSeq &s = h->hs[b];
-            if (!emitted[b]) continue;
-            if (h->h_done[b]) s.done = 1;
-            if (h->h_model[b] != s.model) { s.model = h->h_model[b]; s.c = 0; h->stats.switches++; }
+            if (!emitted[b]) continue;              // entries of rows in flight on the other lane are not at rest
+            if (rb_done[b]) s.done = 1;
+            if (rb_model[b] != s.model) { s.model = rb_model[b]; s.c = 0; h->stats.switches++; }
         }
     } else if (need_sync) {
-        HIP_TRY(h, hipMemcpyAsync(h->h_done, h->s.done, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
+        if (all_lanes && h->two_lanes) HIP_TRY(h, hipStreamSynchronize(h->lanes[1 - h->cur_lane].stream));
+        HIP_TRY(h, hipMemcpyAsync(rb_done, h->s.done, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
         HIP_TRY(h, hipStreamSynchronize(st));
-        for (int b = 0; b < h->batch; ++b) if (h->h_done[b]) h->hs[b].done = 1;
+        for (int b = 0; b < h->batch; ++b) if (emitted[b] && rb_done[b]) h->hs[b].done = 1;
     }
     return EAD_OK;
 }
@@ -798,6 +854,7 @@ ead_status after_tokens(ead_handle *h, const std::vector<char> &emitted) {
 // wait for it and keeps running until fewer than `lo` do (rows stay on it for at least d_min
 // tokens, so its passes come in bursts).  No row's arithmetic depends on the schedule.
 ead_status decode_grouped(ead_handle *h, int n_tokens) {
+    use_lane(h, 0);
     hipStream_t st = h->stream;
     std::vector<int> goal(h->s.max_batch, 0);
     for (int b = 0; b < h->batch; ++b) {
@@ -806,27 +863,84 @@ ead_status decode_grouped(ead_handle *h, int n_tokens) {
         goal[b] = s.goal;
     }
     HIP_TRY(h, hipMemcpyAsync(h->s.goal, goal.data(), h->s.max_batch * sizeof(int), hipMemcpyHostToDevice, st));
-    HIP_TRY(h, hipStreamSynchronize(st));      // `goal` leaves scope
-    std::vector<char> emitted(h->batch);
-    for (;;) {
-        int n[2] = {0, 0};
+    HIP_TRY(h, hipStreamSynchronize(st));      // `goal` leaves scope; the other lane starts after this too
+    auto waiting = [&](int n[2]) {
+        n[0] = n[1] = 0;
         for (int b = 0; b < h->batch; ++b) {
             const HostSeq &s = h->hs[b];
             if (!s.done && s.ngen < s.goal) n[s.model ? 1 : 0]++;
         }
-        const int N = n[0] + n[1];
-        if (N == 0) break;
-        if (n[1] == 0) h->sched_phase = 0;
-        else if (n[0] == 0) h->sched_phase = 1;
-        else if (h->sched_phase == 1 && (float)n[1] < h->sched_lo * (float)N) h->sched_phase = 0;
-        else if (h->sched_phase == 0 && (float)n[1] >= h->sched_hi * (float)N) h->sched_phase = 1;
-        const int m = h->sched_phase;
-        std::fill(emitted.begin(), emitted.end(), 0);
-        int T = 0;
-        TRY(decode_pass(h, m, -1, emitted, &T));
-        if (T == 0) return fail(h, EAD_ERR_STATE, "scheduler found no work for model %d", m);
-        TRY(after_tokens(h, emitted));
-        h->step++;
+    };
+    if (!h->two_lanes) {
+        // one pass at a time: the small model while the large one gathers rows, then the large one
+        std::vector<char> emitted(h->batch);
+        for (;;) {
+            int n[2];
+            waiting(n);
+            const int N = n[0] + n[1];
+            if (N == 0) break;
+            if (n[1] == 0) h->sched_phase = 0;
+            else if (n[0] == 0) h->sched_phase = 1;
+            else if (h->sched_phase == 1 && (float)n[1] < h->sched_lo * (float)N) h->sched_phase = 0;
+            else if (h->sched_phase == 0 && (float)n[1] >= h->sched_hi * (float)N) h->sched_phase = 1;
+            const int m = h->sched_phase;
+            std::fill(emitted.begin(), emitted.end(), 0);
+            int T = 0;
+            TRY(decode_pass(h, m, -1, emitted, &T));
+            if (T == 0) return fail(h, EAD_ERR_STATE, "scheduler found no work for model %d", m);
+            TRY(after_tokens(h, emitted, false));
+            h->step++;
+        }
+    } else {
+        // Two lanes: the small model's passes (bound by latency) and the large model's (bound by
+        // bandwidth) run side by side on their own streams and scratch.  A lane takes a new pass
+        // as soon as its last one has been read back; rows change lanes when the host has seen
+        // their switch.  The large lane still waits until enough rows have gathered.
+        std::vector<char> em[2] = {std::vector<char>(h->batch), std::vector<char>(h->batch)};
+        bool busy[2] = {false, false};
+        for (;;) {
+            int n[2];
+            waiting(n);                               // rows of a busy lane count as waiting for it: they are in its pass
+            const int N = n[0] + n[1];
+            if (N == 0 && !busy[0] && !busy[1]) break;
+            if (!busy[1]) {
+                if (n[1] == 0) h->sched_phase = 0;
+                else if (n[0] == 0 && !busy[0]) h->sched_phase = 1;
+                else if (h->sched_phase == 1 && (float)n[1] < h->sched_lo * (float)N) h->sched_phase = 0;
+                else if (h->sched_phase == 0 && (float)n[1] >= h->sched_hi * (float)N) h->sched_phase = 1;
+            }
+            for (int m = 1; m >= 0; --m) {
+                if (busy[m] || n[m] == 0 || (m == 1 && h->sched_phase != 1)) continue;
+                use_lane(h, m);
+                std::fill(em[m].begin(), em[m].end(), 0);
+                int T = 0;
+                TRY(decode_pass(h, m, -1, em[m], &T));
+                if (T == 0) return fail(h, EAD_ERR_STATE, "scheduler found no work for model %d", m);
+                HIP_TRY(h, hipEventRecord(h->lanes[m].done_ev, h->lanes[m].stream));
+                busy[m] = true;
+            }
+            if (!busy[0] && !busy[1]) return fail(h, EAD_ERR_STATE, "scheduler stalled with %d rows waiting", N);
+            // whichever lane finishes first is read back first
+            int fin = -1;
+            if (busy[0] && busy[1]) {
+                for (;;) {
+                    hipError_t q0 = hipEventQuery(h->lanes[0].done_ev);
+                    if (q0 == hipSuccess) { fin = 0; break; }
+                    if (q0 != hipErrorNotReady) HIP_TRY(h, q0);
+                    hipError_t q1 = hipEventQuery(h->lanes[1].done_ev);
+                    if (q1 == hipSuccess) { fin = 1; break; }
+                    if (q1 != hipErrorNotReady) HIP_TRY(h, q1);
+                }
+            } else {
+                fin = busy[0] ? 0 : 1;
+                HIP_TRY(h, hipEventSynchronize(h->lanes[fin].done_ev));
+            }
+            use_lane(h, fin);
+            TRY(after_tokens(h, em[fin], false));
+            busy[fin] = false;
+            h->step++;
+        }
+        use_lane(h, 0);
     }
     // pauses end here: rows may run to the bound of the run again
     for (int b = 0; b < h->batch; ++b) { h->hs[b].goal = h->max_new; goal[b] = h->max_new; }
@@ -837,28 +951,47 @@ ead_status decode_grouped(ead_handle *h, int n_tokens) {
 
 ead_status decode_impl(ead_handle *h, int n_steps) {
     if (!h->began) return fail(h, EAD_ERR_STATE, "ead_decode before ead_begin");
+    use_lane(h, 0);
     hipStream_t st = h->stream;
     std::vector<char> emitted(h->batch);
     if (h->sched_grouped) {
         TRY(decode_grouped(h, n_steps));
         n_steps = 0;
     }
+    bool used_prev[2] = {false, false};
     for (int it = 0; it < n_steps; ++it) {
         const int step = h->step;
         std::fill(emitted.begin(), emitted.end(), 0);
         bool any = false;
+        // The two models serve disjoint rows: their passes go to two streams and run side by side.
+        // A row may change lanes from one step to the next without the host having waited (its
+        // next model can be known in advance), so a lane first waits for the other lane's
+        // previous step; the passes of one step still overlap.
+        bool used[2] = {false, false};
         for (int m = 0; m < 2; ++m) {
+            use_lane(h, m);
             for (;;) {
+                std::vector<int> probe_rows; std::vector<char> probe_complete;
+                int n_lm = 0, ctx_max = 0;
+                if (h->two_lanes && !used[m] && used_prev[1 - m] &&
+                    host_plan(h, m, h->Tmax, 0, 1, false, step, &n_lm, &ctx_max, &probe_rows, &probe_complete) > 0)
+                    HIP_TRY(h, hipStreamWaitEvent(h->lanes[m].stream, h->lanes[1 - m].done_ev, 0));
                 int T = 0;
                 TRY(decode_pass(h, m, step, emitted, &T));
                 if (T == 0) break;
-                any = true;
+                any = true; used[m] = true;
             }
         }
+        if (h->two_lanes)
+            for (int m = 0; m < 2; ++m)
+                if (used[m]) HIP_TRY(h, hipEventRecord(h->lanes[m].done_ev, h->lanes[m].stream));
+        used_prev[0] = used[0]; used_prev[1] = used[1];
+        use_lane(h, 0);
         if (!any) break;
-        TRY(after_tokens(h, emitted));
+        TRY(after_tokens(h, emitted, true));
         h->step++;
     }
+    if (h->two_lanes) HIP_TRY(h, hipStreamSynchronize(h->lanes[1].stream));
     HIP_TRY(h, hipStreamSynchronize(st));
     int err = 0, aborted = 0;
     HIP_TRY(h, hipMemcpy(&aborted, h->abort_flag, sizeof(int), hipMemcpyDeviceToHost));
@@ -980,7 +1113,13 @@ const char *ead_last_error(const ead_handle *h) { return h ? h->err.c_str() : g_
 
 void ead_destroy(ead_handle *h) {
     if (!h) return;
-    (void)hipStreamSynchronize(h->stream);
+    (void)hipStreamSynchronize(h->lanes[0].stream);
+    if (h->lane1_stream) { (void)hipStreamSynchronize(h->lane1_stream); (void)hipStreamDestroy(h->lane1_stream); }
+    for (auto &l : h->lanes) {
+        if (l.rb_model) (void)hipHostFree(l.rb_model);
+        if (l.rb_done) (void)hipHostFree(l.rb_done);
+        if (l.done_ev) (void)hipEventDestroy(l.done_ev);
+    }
     for (void *p : h->allocs) (void)hipFree(p);
     if (h->h_model) (void)hipHostFree(h->h_model);
     if (h->h_done) (void)hipHostFree(h->h_done);
@@ -1032,28 +1171,51 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
         TRY(dmalloc(h, &s.out_H, (size_t)MB * MS)); TRY(dmalloc(h, &s.out_Hbar, (size_t)MB * MS));
         TRY(dmalloc(h, &s.out_dec, (size_t)MB * MS));
         TRY(dmalloc(h, &s.forced_tok, (size_t)MB * MS)); TRY(dmalloc(h, &s.forced_mid, (size_t)MB * MS));
-        TRY(dmalloc(h, &h->plan.hdr, (size_t)4)); TRY(dmalloc(h, &h->plan.row_seq, (size_t)h->Tmax));
-        TRY(dmalloc(h, &h->plan.row_pos, (size_t)h->Tmax));
-        TRY(dmalloc(h, &h->plan.lm_row, (size_t)h->Tmax)); TRY(dmalloc(h, &h->plan.lm_seq, (size_t)h->Tmax));
         const Model &a = h->mdl[0], &b = h->mdl[1];
         const size_t dmax = std::max(a.d, b.d), qmax = std::max(a.H * a.hd, b.H * b.hd), fmax_ = std::max(a.F, b.F);
         const size_t T = h->Tmax;
-        TRY(dmalloc(h, &h->x, T * dmax)); TRY(dmalloc(h, &h->q, T * qmax)); TRY(dmalloc(h, &h->o, T * qmax));
-        TRY(dmalloc(h, &h->hbuf, T * fmax_));
-        TRY(dmalloc(h, &h->xp_a, T * dmax)); TRY(dmalloc(h, &h->xp_o, T * qmax)); TRY(dmalloc(h, &h->xp_h, T * fmax_));
-        TRY(dmalloc(h, &h->xl_a, T * dmax)); TRY(dmalloc(h, &h->xl_o, T * qmax)); TRY(dmalloc(h, &h->xl_h, T * fmax_));
-        HIP_TRY(h, hipMemsetAsync(h->xl_a, 0, T * dmax * 2, h->stream));
-        HIP_TRY(h, hipMemsetAsync(h->xl_o, 0, T * qmax * 2, h->stream));
-        HIP_TRY(h, hipMemsetAsync(h->xl_h, 0, T * fmax_ * 2, h->stream));
-        HIP_TRY(h, hipMemsetAsync(h->xp_a, 0, T * dmax * 2, h->stream));
-        HIP_TRY(h, hipMemsetAsync(h->xp_o, 0, T * qmax * 2, h->stream));
-        HIP_TRY(h, hipMemsetAsync(h->xp_h, 0, T * fmax_ * 2, h->stream));
-        TRY(dmalloc(h, &h->part_o, (size_t)h->items_max * qmax)); TRY(dmalloc(h, &h->part_ml, (size_t)h->items_max * std::max(a.H, b.H)));
-        TRY(dmalloc(h, &h->tickets, (size_t)h->Tmax * std::max(a.H, b.H)));
-        TRY(dmalloc(h, &h->sk_part, kSplitKFloats)); TRY(dmalloc(h, &h->sk_tickets, (size_t)kSplitKGroups));
-        HIP_TRY(h, hipMemsetAsync(h->sk_tickets, 0, kSplitKGroups * sizeof(int), h->stream));
-        HIP_TRY(h, hipMemsetAsync(h->tickets, 0, (size_t)h->Tmax * std::max(a.H, b.H) * sizeof(int), h->stream));
-        TRY(dmalloc(h, &h->lm_part, std::max((size_t)std::max<size_t>(MB, h->score_rows) * h->lm_grid, (size_t)256 * kFusedRbChunk)));
+        // per-lane scratch: allocated twice when two passes may run side by side
+        auto alloc_lane = [&]() -> ead_status {
+            TRY(dmalloc(h, &h->plan.hdr, (size_t)4)); TRY(dmalloc(h, &h->plan.row_seq, (size_t)h->Tmax));
+            TRY(dmalloc(h, &h->plan.row_pos, (size_t)h->Tmax));
+            TRY(dmalloc(h, &h->plan.lm_row, (size_t)h->Tmax)); TRY(dmalloc(h, &h->plan.lm_seq, (size_t)h->Tmax));
+            TRY(dmalloc(h, &h->x, T * dmax)); TRY(dmalloc(h, &h->q, T * qmax)); TRY(dmalloc(h, &h->o, T * qmax));
+            TRY(dmalloc(h, &h->hbuf, T * fmax_));
+            TRY(dmalloc(h, &h->xp_a, T * dmax)); TRY(dmalloc(h, &h->xp_o, T * qmax)); TRY(dmalloc(h, &h->xp_h, T * fmax_));
+            TRY(dmalloc(h, &h->xl_a, T * dmax)); TRY(dmalloc(h, &h->xl_o, T * qmax)); TRY(dmalloc(h, &h->xl_h, T * fmax_));
+            HIP_TRY(h, hipMemsetAsync(h->xl_a, 0, T * dmax * 2, h->stream));
+            HIP_TRY(h, hipMemsetAsync(h->xl_o, 0, T * qmax * 2, h->stream));
+            HIP_TRY(h, hipMemsetAsync(h->xl_h, 0, T * fmax_ * 2, h->stream));
+            HIP_TRY(h, hipMemsetAsync(h->xp_a, 0, T * dmax * 2, h->stream));
+            HIP_TRY(h, hipMemsetAsync(h->xp_o, 0, T * qmax * 2, h->stream));
+            HIP_TRY(h, hipMemsetAsync(h->xp_h, 0, T * fmax_ * 2, h->stream));
+            TRY(dmalloc(h, &h->part_o, (size_t)h->items_max * qmax)); TRY(dmalloc(h, &h->part_ml, (size_t)h->items_max * std::max(a.H, b.H)));
+            TRY(dmalloc(h, &h->tickets, (size_t)h->Tmax * std::max(a.H, b.H)));
+            TRY(dmalloc(h, &h->sk_part, kSplitKFloats)); TRY(dmalloc(h, &h->sk_tickets, (size_t)kSplitKGroups));
+            HIP_TRY(h, hipMemsetAsync(h->sk_tickets, 0, kSplitKGroups * sizeof(int), h->stream));
+            HIP_TRY(h, hipMemsetAsync(h->tickets, 0, (size_t)h->Tmax * std::max(a.H, b.H) * sizeof(int), h->stream));
+            TRY(dmalloc(h, &h->lm_part, std::max((size_t)std::max<size_t>(MB, h->score_rows) * h->lm_grid, (size_t)256 * kFusedRbChunk)));
+            return EAD_OK;
+        };
+        h->two_lanes = (MB > 1 && MB <= 64 * kAllowWords) ? 1 : 0;
+        TRY(alloc_lane());
+        save_lane(h, 0);
+        h->lanes[0].stream = h->stream;
+        if (h->two_lanes) {
+            TRY(alloc_lane());
+            save_lane(h, 1);
+            HIP_TRY(h, hipStreamCreateWithFlags(&h->lane1_stream, hipStreamNonBlocking));   // default priority
+            h->lanes[1].stream = h->lane1_stream;
+        }
+        for (int i = 0; i < (h->two_lanes ? 2 : 1); ++i) {
+            HIP_TRY(h, hipHostMalloc((void **)&h->lanes[i].rb_model, std::max<size_t>(MB, 64) * sizeof(int), hipHostMallocDefault));
+            HIP_TRY(h, hipHostMalloc((void **)&h->lanes[i].rb_done, std::max<size_t>(MB, 64) * sizeof(int), hipHostMallocDefault));
+            HIP_TRY(h, hipEventCreateWithFlags(&h->lanes[i].done_ev, hipEventDisableTiming));
+        }
+        {
+            const int keep = h->two_lanes;      // use_lane maps every lane to 0 when there is one
+            h->two_lanes = 1; use_lane(h, 0); h->two_lanes = keep;
+        }
         TRY(dmalloc(h, &h->logits_dump, (size_t)h->score_rows * a.V));
         TRY(dmalloc(h, &h->sc_H, (size_t)MS)); TRY(dmalloc(h, &h->sc_arg, (size_t)MS));
         {
@@ -1184,6 +1346,7 @@ ead_status ead_score(ead_handle *h, int32_t which, const int32_t *tokens, int32_
     Model &m = h->mdl[which];
     for (int i = 0; i < len; ++i)
         if (tokens[i] < 0 || tokens[i] >= m.V) return fail(h, EAD_ERR_INVALID_ARG, "token %d out of range", i);
+    use_lane(h, 0);
     hipStream_t st = h->stream;
     h->began = 0; h->batch = 1; h->replay = 0;
     struct Scoring { ead_handle *h; Scoring(ead_handle *h_) : h(h_) { h->scoring = 1; } ~Scoring() { h->scoring = 0; } } scoring_guard(h);
@@ -1271,6 +1434,7 @@ ead_status ead_set_fused(ead_handle *h, int32_t on) {
 ead_status ead_profile_enable(ead_handle *h, int32_t on) {
     if (!h) return EAD_ERR_INVALID_ARG;
     HIP_TRY(h, hipStreamSynchronize(h->stream));
+    if (h->two_lanes) HIP_TRY(h, hipStreamSynchronize(h->lanes[1].stream));
     prof_collect(h);
     memset(h->prof_ms, 0, sizeof h->prof_ms); memset(h->prof_bytes, 0, sizeof h->prof_bytes); memset(h->prof_n, 0, sizeof h->prof_n);
     h->prof_on = on ? 1 : 0;
@@ -1280,6 +1444,7 @@ ead_status ead_profile_enable(ead_handle *h, int32_t on) {
 ead_status ead_profile_read(ead_handle *h, ead_kernel_profile *out, int32_t capacity, int32_t *n_out) {
     if (!h || !out || !n_out || capacity < 0) return EAD_ERR_INVALID_ARG;
     HIP_TRY(h, hipStreamSynchronize(h->stream));
+    if (h->two_lanes) HIP_TRY(h, hipStreamSynchronize(h->lanes[1].stream));
     prof_collect(h);
     int n = 0;
     for (int c = 0; c < PK_COUNT * 2 && n < capacity; ++c) {
