@@ -432,6 +432,24 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
     const int NT = TB <= 1 ? 1 : (TB == 2 ? 2 : 4);
     int cfg = !big ? 1 : (NB >= 4 * 256 ? 4 : 2);       // 1: (4 waves, R=1)  4: (4, R=4)  2: (8 waves, R=2)  5: (4, R=4, split K)
     int grid = (NB + cfg - 1) / cfg;
+    if constexpr (EPI == EPI_SWIGLU || EPI == EPI_RES) {
+        // more than 64 rows: 128 rows per sweep, activation tiles shared through LDS.  Matrices with
+        // few row blocks are split along K over workgroups when one sweep covers the pass.
+        if (big && TB > 4) {
+            const int NG = (NB + 7) / 8;
+            if (cfg == 4) {
+                hipLaunchKernelGGL((k_linear_mfma_wide<2, 5, EPI, false>), dim3(NG), dim3(256), 0, h->stream, a);
+                return;
+            }
+            int KS = std::min(kSplitKMax, std::max(1, (h->n_cu + NG / 2) / NG));
+            while (KS > 1 && (a.K / 32) / KS < 16) --KS;
+            if (TB <= kWideTok && KS > 1 && (size_t)KS * NG * 8 * kWideTok * 256 <= kSplitKFloats && NG <= kSplitKGroups) {
+                a.KS = KS; a.sk_part = h->sk_part; a.sk_tickets = h->sk_tickets;
+                hipLaunchKernelGGL((k_linear_mfma_wide<2, 5, EPI, true>), dim3(NG * KS), dim3(256), 0, h->stream, a);
+                return;
+            }
+        }
+    }
     // (the rotary / cache-append epilogue is too heavy to be left to one workgroup per group)
     if (cfg == 2 && TB <= 4 && EPI != EPI_LOGITS && EPI != EPI_QKV) {
         const int NG = (NB + 3) / 4;
@@ -1160,7 +1178,7 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
         h->Tmax = (h->Tmax + 15) & ~15;
         h->items_max = std::max(h->Tmax, 2048);
         h->lm_grid = 1024;
-        h->score_rows = 64;
+        h->score_rows = 160;         // rows per teacher-forced pass (two 128-row sweeps at most)
         SeqState &s = h->s;
         s.max_batch = MB; s.max_seq = MS; s.cap = MS;
         TRY(dmalloc(h, &s.tokens, (size_t)MB * MS)); TRY(dmalloc(h, &s.len, (size_t)MB)); TRY(dmalloc(h, &s.kvlen, (size_t)2 * MB));

@@ -487,6 +487,164 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma(LinArgs<bf16_t> a) {
 }
 
 // ------------------------------------------------------------------------------------
+// MFMA path for passes of more than 64 token rows (catch-up chunks of many rows, prompt
+// prefill): 128 token rows per sweep over the weights.  The activation tiles of a k step
+// (16 KB for 128 rows, hi + lo) no longer fit a wave's registers next to a fetch ring, and every
+// wave needs all of them, so the four waves of a workgroup walk K together: each fetches a
+// quarter of the step's activation tiles (ring of DA steps, like its R weight tiles), the
+// quarters meet in LDS (two buffers, one barrier per step), and every wave multiplies its own
+// 16 R weight rows with all 128 token rows.  No sums cross waves; a wave turns its accumulators
+// to the epilogue's (token column, weight row) order through a private 1 KB of LDS.
+// Each output element still accumulates its k tiles in ascending order, lo before hi.
+// ------------------------------------------------------------------------------------
+constexpr int kWideTok = 8;          // token blocks (of 16 rows) per sweep
+
+template <int R, int DA, int EPI, bool SK = false>
+__global__ __launch_bounds__(256) void k_linear_mfma_wide(LinArgs<bf16_t> a) {
+    constexpr int NT = kWideTok, BT = 2 * NT / 4;      // activation tiles a wave fetches per step
+    __shared__ __attribute__((aligned(16))) bf16_t s_b[2][2 * NT][512];
+    __shared__ __attribute__((aligned(16))) float s_t[4][64][4];
+    __shared__ int s_ticket;
+    const int K = a.K, KCfull = K >> 5, NB = a.Np >> 4, NG = (NB + 4 * R - 1) / (4 * R);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int T = *a.count;
+    const int TB = (T + 15) >> 4;
+    if (TB == 0) return;
+    // SK: workgroup (g, ks) takes slab ks of K for group g (one sweep only: TB <= NT); the slabs'
+    // sums meet in memory and the workgroup that arrives last adds them in slab order
+    const int KS = SK ? a.KS : 1;
+    const int g = SK ? (int)blockIdx.x / KS : (int)blockIdx.x, ks = SK ? (int)blockIdx.x % KS : 0;
+    const int kbase = (ks * KCfull) / KS, KC = ((ks + 1) * KCfull) / KS - kbase;     // this workgroup's k tiles
+    EntStat st; st.init();            // unused by the epilogues this kernel is built for
+
+    for (int tb0 = 0; tb0 < TB; tb0 += NT) {
+        f32x4_t acc[R][NT];
+        const bf16_t *wp[R], *bp[BT];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int b = 0; b < NT; ++b) acc[r][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            wp[r] = a.W + tile_offset(min((g * 4 + wave) * R + r, NB - 1), kbase, KCfull) + lane * 8;
+        }
+#pragma unroll
+        for (int q = 0; q < BT; ++q) {           // tile j of the step: j < NT hi of token block j, else lo of block j - NT
+            const int jt = wave * BT + q, blk = min(tb0 + (jt < NT ? jt : jt - NT), TB - 1);
+            bp[q] = (jt < NT ? a.xp : a.xp_lo) + tile_offset(blk, kbase, KCfull) + lane * 8;
+        }
+        Vec8<bf16_t> wa[DA][R], ba[DA][BT];
+        auto issue = [&](int s, int i) __attribute__((always_inline)) {
+            const size_t off = (size_t)min(i, KC - 1) * 512;
+#pragma unroll
+            for (int q = 0; q < BT; ++q) ba[s][q].load(bp[q] + off);
+#pragma unroll
+            for (int r = 0; r < R; ++r) wa[s][r].load_stream(wp[r] + off);
+        };
+#pragma unroll
+        for (int s = 0; s < DA; ++s) {
+            issue(s, s);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        for (int i0 = 0; i0 < KC; i0 += DA) {
+#pragma unroll
+            for (int s = 0; s < DA; ++s) {
+                const int i = i0 + s;
+                if (i < KC) {                                  // uniform over the workgroup
+                    bf16_t (*buf)[512] = s_b[i & 1];
+#pragma unroll
+                    for (int q = 0; q < BT; ++q)
+                        *reinterpret_cast<u32x4_t *>(&buf[wave * BT + q][lane * 8]) = ba[s][q].raw;
+                    __syncthreads();
+#pragma unroll
+                    for (int b = 0; b < NT; ++b) {
+                        const u32x4_t hi = *reinterpret_cast<const u32x4_t *>(&buf[b][lane * 8]);
+                        const u32x4_t lo = *reinterpret_cast<const u32x4_t *>(&buf[NT + b][lane * 8]);
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+                            acc[r][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf16x8_t, wa[s][r].raw), __builtin_bit_cast(bf16x8_t, lo), acc[r][b], 0, 0, 0);
+                            acc[r][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf16x8_t, wa[s][r].raw), __builtin_bit_cast(bf16x8_t, hi), acc[r][b], 0, 0, 0);
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                issue(s, i + DA);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // epilogue: lane L holds weight rows 4*(L/16)..+3 of token column L%16; the epilogue wants
+        // neighbouring lanes to hold neighbouring weight rows of one token column
+        auto finish = [&](int r, int b, f32x4_t d) __attribute__((always_inline)) {
+            const int rb = (g * 4 + wave) * R + r;
+            EpiPre pre[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int e = k * 64 + lane, c = e >> 4, j = e & 15, t = (tb0 + b) * 16 + c;
+                pre[k] = epi_prefetch<bf16_t, EPI>(a, rb * 16 + j, t, rb < NB && tb0 + b < TB && t < T);
+            }
+            *reinterpret_cast<float4 *>(&s_t[wave][lane][0]) = make_float4(d[0], d[1], d[2], d[3]);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int e = k * 64 + lane, c = e >> 4, j = e & 15, t = (tb0 + b) * 16 + c;
+                const float v = s_t[wave][c + 16 * (j >> 2)][j & 3];
+                epilogue<bf16_t, EPI>(a, rb * 16 + j, t, v, rb < NB && tb0 + b < TB && t < T, st, pre[k]);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        };
+        if constexpr (!SK) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int b = 0; b < NT; ++b) finish(r, b, acc[r][b]);
+        } else {
+            // partial sums of this slab, one 16-byte store per lane and (row block, token block)
+            const size_t slab = (size_t)NG * 4 * R * NT * 64;              // float4 entries per slab
+            float4 *part = reinterpret_cast<float4 *>(a.sk_part);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int b = 0; b < NT; ++b) {
+                    float *dst = reinterpret_cast<float *>(part + (size_t)ks * slab + ((((size_t)g * 4 + wave) * R + r) * NT + b) * 64 + lane);
+                    st_coherent(dst, acc[r][b][0]); st_coherent(dst + 1, acc[r][b][1]);
+                    st_coherent(dst + 2, acc[r][b][2]); st_coherent(dst + 3, acc[r][b][3]);
+                }
+            wait_stores();
+            __syncthreads();
+            if (tid == 0) s_ticket = __hip_atomic_fetch_add(a.sk_tickets + g, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            if (s_ticket == KS - 1) {
+                if (tid == 0) st_coherent(a.sk_tickets + g, 0);
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int b = 0; b < NT; ++b) {
+                        float pv[kSplitKMax][4];
+#pragma unroll
+                        for (int q = 0; q < kSplitKMax; ++q) {
+                            const float *src = reinterpret_cast<const float *>(part + (size_t)min(q, KS - 1) * slab + ((((size_t)g * 4 + wave) * R + r) * NT + b) * 64 + lane);
+                            pv[q][0] = ld_coherent(src); pv[q][1] = ld_coherent(src + 1);
+                            pv[q][2] = ld_coherent(src + 2); pv[q][3] = ld_coherent(src + 3);
+                        }
+                        f32x4_t d = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int q = 0; q < kSplitKMax; ++q)
+                            if (q < KS) { d[0] += pv[q][0]; d[1] += pv[q][1]; d[2] += pv[q][2]; d[3] += pv[q][3]; }
+                        finish(r, b, d);
+                        __builtin_amdgcn_sched_barrier(0);        // one block's loads in flight at a time
+                    }
+            }
+        }
+        __syncthreads();                 // the activation buffers are reused by the next sweep
+    }
+}
+
+// ------------------------------------------------------------------------------------
 // fp32 activations -> bf16 activation tiles, optionally through RMSNorm.
 // One workgroup per token row; rows >= count (padding of the last 16-row block) are zeroed.
 // ------------------------------------------------------------------------------------

@@ -235,15 +235,16 @@ def test_eos_and_errors(tiny):
         e.generate([prompt] * 5, 4)                               # exceeds max_batch
 
 
-@pytest.mark.parametrize("pair,layers,T", [("llama", 2, 24), ("qwen", 2, 24), ("llama_1b_3b", 2, 24), ("qwen_15b_14b", 2, 24)])
+@pytest.mark.parametrize("pair,layers,T", [("llama", 2, 24), ("qwen", 2, 24), ("llama_1b_3b", 2, 24), ("qwen_15b_14b", 2, 24),
+                                           ("llama", 2, 150), ("qwen", 2, 77)])   # > 64 rows: 128-row sweeps
 def test_bf16_truncated_pair_score_and_replay(pair, layers, T):
     """Full-width, depth-truncated bf16 pairs: teacher-forced logits / entropy / arg max for
-    single rows (FMA path) and 24-row chunks (MFMA path), then Algorithm 1 along the oracle's
-    trajectory including catch-ups."""
+    single rows (FMA path) and chunks of 24 to 150 rows (MFMA paths), then Algorithm 1 along
+    the oracle's trajectory including catch-ups."""
     ead = _ead()
     ss, sl = (s.truncated(layers) for s in si.PAIRS[pair])
     Ws, Wl, os_, ol = _pair(ss, sl)
-    e = ead.EAD(ss, Ws, sl, Wl, window=5, tau=0.0, d_min=4, max_batch=2, max_seq=96)
+    e = ead.EAD(ss, Ws, sl, Wl, window=5, tau=0.0, d_min=4, max_batch=2, max_seq=max(96, T + 8))
     toks = si.prompt_np(0, pair, T, ss.vocab)
     refs = {}
     for which, om in ((0, os_), (1, ol)):
