@@ -422,7 +422,7 @@ void launch_valu(ead_handle *h, int mi, LinArgs<WT> &a, int T, int grid) {
 //    workgroups as possible.
 // NT token blocks per pass follow T; the ring depth D follows the register budget.
 constexpr int kSplitKGroups = 4096;                     // arrival counters
-constexpr size_t kSplitKFloats = (size_t)4 << 20;      // partial sums: KS * Np * 64 floats at most
+constexpr size_t kSplitKFloats = (size_t)8 << 20;      // partial sums: KS slabs of (padded Np) x 128 floats at most
 
 template <int EPI>
 void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap = 0) {
@@ -432,20 +432,22 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
     const int NT = TB <= 1 ? 1 : (TB == 2 ? 2 : 4);
     int cfg = !big ? 1 : (NB >= 4 * 256 ? 4 : 2);       // 1: (4 waves, R=1)  4: (4, R=4)  2: (8 waves, R=2)  5: (4, R=4, split K)
     int grid = (NB + cfg - 1) / cfg;
-    if constexpr (EPI == EPI_SWIGLU || EPI == EPI_RES) {
+    if constexpr (EPI != EPI_LOGITS) {
         // more than 64 rows: 128 rows per sweep, activation tiles shared through LDS.  Matrices with
-        // few row blocks are split along K over workgroups when one sweep covers the pass.
+        // few row blocks are split along K over workgroups when one sweep covers the pass; a second
+        // kernel adds the slabs in order and runs the epilogue.
         if (big && TB > 4) {
             const int NG = (NB + 7) / 8;
-            if (cfg == 4) {
+            if (cfg == 4 && EPI != EPI_QKV) {
                 hipLaunchKernelGGL((k_linear_mfma_wide<2, 5, EPI, false>), dim3(NG), dim3(256), 0, h->stream, a);
                 return;
             }
             int KS = std::min(kSplitKMax, std::max(1, (h->n_cu + NG / 2) / NG));
             while (KS > 1 && (a.K / 32) / KS < 16) --KS;
-            if (TB <= kWideTok && KS > 1 && (size_t)KS * NG * 8 * kWideTok * 256 <= kSplitKFloats && NG <= kSplitKGroups) {
-                a.KS = KS; a.sk_part = h->sk_part; a.sk_tickets = h->sk_tickets;
+            if (TB <= kWideTok && KS > 1 && (size_t)KS * NG * 8 * kWideTok * 256 <= kSplitKFloats) {
+                a.KS = KS; a.sk_part = h->sk_part;
                 hipLaunchKernelGGL((k_linear_mfma_wide<2, 5, EPI, true>), dim3(NG * KS), dim3(256), 0, h->stream, a);
+                hipLaunchKernelGGL((k_sk_merge<EPI>), dim3((NB * kWideTok + 3) / 4), dim3(256), 0, h->stream, a, NG * 8);
                 return;
             }
         }

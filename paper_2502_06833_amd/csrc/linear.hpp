@@ -497,6 +497,34 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma(LinArgs<bf16_t> a) {
 // to the epilogue's (token column, weight row) order through a private 1 KB of LDS.
 // Each output element still accumulates its k tiles in ascending order, lo before hi.
 // ------------------------------------------------------------------------------------
+// One 16 x 16 block of results in the matrix cores' layout (lane L: weight rows 4*(L/16)..+3 of
+// token column L%16) -> the epilogue, which wants neighbouring lanes to hold neighbouring weight
+// rows of one token column.  s_tw: 1 KB of LDS owned by the calling wave.
+template <int EPI>
+__device__ __forceinline__ void block_epilogue(const LinArgs<bf16_t> &a, float (*s_tw)[4], int rb, int tb, f32x4_t d,
+                                               bool ok, int T, int lane) {
+    EntStat st; st.init();            // unused by the epilogues this is built for
+    EpiPre pre[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int e = k * 64 + lane, c = e >> 4, j = e & 15, t = tb * 16 + c;
+        pre[k] = epi_prefetch<bf16_t, EPI>(a, rb * 16 + j, t, ok && t < T);
+    }
+    *reinterpret_cast<float4 *>(&s_tw[lane][0]) = make_float4(d[0], d[1], d[2], d[3]);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int e = k * 64 + lane, c = e >> 4, j = e & 15, t = tb * 16 + c;
+        const float v = s_tw[c + 16 * (j >> 2)][j & 3];
+        epilogue<bf16_t, EPI>(a, rb * 16 + j, t, v, ok && t < T, st, pre[k]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 constexpr int kWideTok = 8;          // token blocks (of 16 rows) per sweep
 
 template <int R, int DA, int EPI, bool SK = false>
@@ -504,15 +532,14 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wide(LinArgs<bf16_t> a) {
     constexpr int NT = kWideTok, BT = 2 * NT / 4;      // activation tiles a wave fetches per step
     __shared__ __attribute__((aligned(16))) bf16_t s_b[2][2 * NT][512];
     __shared__ __attribute__((aligned(16))) float s_t[4][64][4];
-    __shared__ int s_ticket;
     const int K = a.K, KCfull = K >> 5, NB = a.Np >> 4, NG = (NB + 4 * R - 1) / (4 * R);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int T = *a.count;
     const int TB = (T + 15) >> 4;
     if (TB == 0) return;
-    // SK: workgroup (g, ks) takes slab ks of K for group g (one sweep only: TB <= NT); the slabs'
-    // sums meet in memory and the workgroup that arrives last adds them in slab order
+    // SK: workgroup (g, ks) takes slab ks of K for group g (one sweep only: TB <= NT) and leaves
+    // its sums in memory for k_sk_merge
     const int KS = SK ? a.KS : 1;
     const int g = SK ? (int)blockIdx.x / KS : (int)blockIdx.x, ks = SK ? (int)blockIdx.x % KS : 0;
     const int kbase = (ks * KCfull) / KS, KC = ((ks + 1) * KCfull) / KS - kbase;     // this workgroup's k tiles
@@ -555,93 +582,76 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wide(LinArgs<bf16_t> a) {
                     for (int q = 0; q < BT; ++q)
                         *reinterpret_cast<u32x4_t *>(&buf[wave * BT + q][lane * 8]) = ba[s][q].raw;
                     __syncthreads();
+                    // all fragments of the step are requested before the first product, and
+                    // neighbouring products go to different accumulators: with one wave per SIMD
+                    // nothing else hides the LDS latency or the matrix cores' result latency
+                    u32x4_t fr[2 * NT];                        // lo of blocks 0..NT-1, then hi
 #pragma unroll
-                    for (int b = 0; b < NT; ++b) {
-                        const u32x4_t hi = *reinterpret_cast<const u32x4_t *>(&buf[b][lane * 8]);
-                        const u32x4_t lo = *reinterpret_cast<const u32x4_t *>(&buf[NT + b][lane * 8]);
+                    for (int b = 0; b < 2 * NT; ++b)
+                        fr[b] = *reinterpret_cast<const u32x4_t *>(&buf[b < NT ? NT + b : b - NT][lane * 8]);
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int r = 0; r < R; ++r) {
-                            acc[r][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                __builtin_bit_cast(bf16x8_t, wa[s][r].raw), __builtin_bit_cast(bf16x8_t, lo), acc[r][b], 0, 0, 0);
-                            acc[r][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                __builtin_bit_cast(bf16x8_t, wa[s][r].raw), __builtin_bit_cast(bf16x8_t, hi), acc[r][b], 0, 0, 0);
-                        }
-                    }
+                    for (int b = 0; b < 2 * NT; ++b)
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+                            acc[r][b % NT] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf16x8_t, wa[s][r].raw), __builtin_bit_cast(bf16x8_t, fr[b]), acc[r][b % NT], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 issue(s, i + DA);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        // epilogue: lane L holds weight rows 4*(L/16)..+3 of token column L%16; the epilogue wants
-        // neighbouring lanes to hold neighbouring weight rows of one token column
-        auto finish = [&](int r, int b, f32x4_t d) __attribute__((always_inline)) {
-            const int rb = (g * 4 + wave) * R + r;
-            EpiPre pre[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int e = k * 64 + lane, c = e >> 4, j = e & 15, t = (tb0 + b) * 16 + c;
-                pre[k] = epi_prefetch<bf16_t, EPI>(a, rb * 16 + j, t, rb < NB && tb0 + b < TB && t < T);
-            }
-            *reinterpret_cast<float4 *>(&s_t[wave][lane][0]) = make_float4(d[0], d[1], d[2], d[3]);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int e = k * 64 + lane, c = e >> 4, j = e & 15, t = (tb0 + b) * 16 + c;
-                const float v = s_t[wave][c + 16 * (j >> 2)][j & 3];
-                epilogue<bf16_t, EPI>(a, rb * 16 + j, t, v, rb < NB && tb0 + b < TB && t < T, st, pre[k]);
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        };
         if constexpr (!SK) {
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int b = 0; b < NT; ++b) finish(r, b, acc[r][b]);
+                for (int b = 0; b < NT; ++b) {
+                    const int rb = (g * 4 + wave) * R + r;
+                    block_epilogue<EPI>(a, s_t[wave], rb, tb0 + b, acc[r][b], rb < NB && tb0 + b < TB, T, lane);
+                }
         } else {
-            // partial sums of this slab, one 16-byte store per lane and (row block, token block)
-            const size_t slab = (size_t)NG * 4 * R * NT * 64;              // float4 entries per slab
-            float4 *part = reinterpret_cast<float4 *>(a.sk_part);
+            // this slab's sums: [slab][row block][token block][component 4][lane 64], so that the 64
+            // lanes of one store write 256 contiguous bytes; k_sk_merge adds the slabs in order
+            const size_t slab = (size_t)NG * 4 * R * NT * 256;             // floats per slab
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int b = 0; b < NT; ++b) {
-                    float *dst = reinterpret_cast<float *>(part + (size_t)ks * slab + ((((size_t)g * 4 + wave) * R + r) * NT + b) * 64 + lane);
-                    st_coherent(dst, acc[r][b][0]); st_coherent(dst + 1, acc[r][b][1]);
-                    st_coherent(dst + 2, acc[r][b][2]); st_coherent(dst + 3, acc[r][b][3]);
-                }
-            wait_stores();
-            __syncthreads();
-            if (tid == 0) s_ticket = __hip_atomic_fetch_add(a.sk_tickets + g, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __syncthreads();
-            if (s_ticket == KS - 1) {
-                if (tid == 0) st_coherent(a.sk_tickets + g, 0);
-#pragma unroll
-                for (int r = 0; r < R; ++r)
-#pragma unroll
-                    for (int b = 0; b < NT; ++b) {
-                        float pv[kSplitKMax][4];
-#pragma unroll
-                        for (int q = 0; q < kSplitKMax; ++q) {
-                            const float *src = reinterpret_cast<const float *>(part + (size_t)min(q, KS - 1) * slab + ((((size_t)g * 4 + wave) * R + r) * NT + b) * 64 + lane);
-                            pv[q][0] = ld_coherent(src); pv[q][1] = ld_coherent(src + 1);
-                            pv[q][2] = ld_coherent(src + 2); pv[q][3] = ld_coherent(src + 3);
-                        }
-                        f32x4_t d = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                        for (int q = 0; q < kSplitKMax; ++q)
-                            if (q < KS) { d[0] += pv[q][0]; d[1] += pv[q][1]; d[2] += pv[q][2]; d[3] += pv[q][3]; }
-                        finish(r, b, d);
-                        __builtin_amdgcn_sched_barrier(0);        // one block's loads in flight at a time
+                    const int rb = (g * 4 + wave) * R + r;
+                    if (rb < NB && b < TB) {
+                        float *dst = a.sk_part + (size_t)ks * slab + ((size_t)rb * NT + b) * 256 + lane;
+                        st_coherent(dst, acc[r][b][0]); st_coherent(dst + 64, acc[r][b][1]); st_coherent(dst + 128, acc[r][b][2]); st_coherent(dst + 192, acc[r][b][3]);
                     }
-            }
+                }
         }
         __syncthreads();                 // the activation buffers are reused by the next sweep
     }
+}
+
+// Sum of the K slabs that k_linear_mfma_wide<..., SK = true> left in memory, in slab order, then
+// the epilogue.  One wave per 16 x 16 block; grid = ceil(row blocks * kWideTok / 4) workgroups.
+template <int EPI>
+__global__ __launch_bounds__(256) void k_sk_merge(LinArgs<bf16_t> a, int NGR /* row blocks incl. padding */) {
+    constexpr int NT = kWideTok;
+    __shared__ __attribute__((aligned(16))) float s_t[4][64][4];
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int NB = a.Np >> 4, T = *a.count, TB = (T + 15) >> 4, KS = a.KS;
+    const int blk = blockIdx.x * 4 + wave, rb = blk / NT, b = blk % NT;
+    if (rb >= NB || b >= TB) return;
+    const size_t slab = (size_t)NGR * NT * 256;
+    const float *src = a.sk_part + ((size_t)rb * NT + b) * 256 + lane;
+    float pv[kSplitKMax][4];
+#pragma unroll
+    for (int q = 0; q < kSplitKMax; ++q) {
+        const float *sq = src + (size_t)min(q, KS - 1) * slab;
+        pv[q][0] = sq[0]; pv[q][1] = sq[64]; pv[q][2] = sq[128]; pv[q][3] = sq[192];
+    }
+    f32x4_t d = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int q = 0; q < kSplitKMax; ++q)
+        if (q < KS) { d[0] += pv[q][0]; d[1] += pv[q][1]; d[2] += pv[q][2]; d[3] += pv[q][3]; }
+    block_epilogue<EPI>(a, s_t[wave], rb, b, d, true, T, lane);
 }
 
 // ------------------------------------------------------------------------------------

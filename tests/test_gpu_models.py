@@ -236,7 +236,7 @@ def test_eos_and_errors(tiny):
 
 
 @pytest.mark.parametrize("pair,layers,T", [("llama", 2, 24), ("qwen", 2, 24), ("llama_1b_3b", 2, 24), ("qwen_15b_14b", 2, 24),
-                                           ("llama", 2, 150), ("qwen", 2, 77)])   # > 64 rows: 128-row sweeps
+                                           ("llama", 2, 150), ("qwen", 2, 77), ("llama", 2, 120)])   # > 64 rows: 128-row sweeps, K split over workgroups up to 128
 def test_bf16_truncated_pair_score_and_replay(pair, layers, T):
     """Full-width, depth-truncated bf16 pairs: teacher-forced logits / entropy / arg max for
     single rows (FMA path) and chunks of 24 to 150 rows (MFMA paths), then Algorithm 1 along
