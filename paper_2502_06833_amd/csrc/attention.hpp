@@ -33,11 +33,10 @@ constexpr float kNegBig = -1e30f;
 
 template <int HD>
 __device__ __forceinline__ void attn_store(float *out, bf16_t *out_tiles, bf16_t *out_tiles_lo, int t, int H,
-                                           int col, float r) {
+                                           int col, float r, int TB) {
     if (out) out[(size_t)t * H * HD + col] = r;
     if (out_tiles) {
-        const int KC = (H * HD) >> 5;
-        const size_t off = tile_offset(t >> 4, col >> 5, KC) + (size_t)(((t & 15) + 16 * ((col & 31) >> 3)) * 8 + (col & 7));
+        const size_t off = act_tile_offset(t >> 4, col >> 5, TB) + (size_t)(((t & 15) + 16 * ((col & 31) >> 3)) * 8 + (col & 7));
         split_bf16(r, out_tiles[off].u, out_tiles_lo[off].u);
     }
 }
@@ -214,7 +213,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void k_attn(AttnArgs<KT> a) {
             acc += s_o[w][g][dd] * c;
         }
         const int h = h0 + g;
-        if (nsplit == 1) attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, h * HD + dd, acc / L);
+        if (nsplit == 1) attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, h * HD + dd, acc / L, (count + 15) >> 4);
         else {
             const size_t item = ((size_t)t * H + h) * a.max_splits + split;
             st_coherent(a.part_o + item * HD + dd, acc);
@@ -254,7 +253,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void k_attn(AttnArgs<KT> a) {
             L += ll[sp] * c;
             acc += oo[sp] * c;
         }
-        attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, h * HD + dd, acc / L);
+        attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, h * HD + dd, acc / L, (count + 15) >> 4);
     }
 }
 

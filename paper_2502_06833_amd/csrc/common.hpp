@@ -128,6 +128,13 @@ __device__ __forceinline__ float wave_max(float v) {
 __host__ __device__ __forceinline__ size_t tile_offset(int rb, int kc, int KC) {
     return ((size_t)rb * (size_t)KC + (size_t)kc) * 512;
 }
+// Activation tiles (16 token rows x 32 columns, same inner layout, the B operand) are ordered
+// the other way round: tile (tb, kc) of a pass with TB token blocks sits at (kc * TB + tb) * 512.
+// Every workgroup of a linear kernel reads the same TB tiles in the same k step; side by side
+// they spread over the memory channels, whereas K/32 tiles apart they fall on one or two.
+__host__ __device__ __forceinline__ size_t act_tile_offset(int tb, int kc, int TB) {
+    return ((size_t)kc * (size_t)TB + (size_t)tb) * 512;
+}
 
 // ---- online soft-max statistics for the entropy (Eq. 1-2) ------------------------------
 // For a set of logits: m = max, Z = sum exp(l-m), S = sum exp(l-m)(l-m), plus the arg max

@@ -433,20 +433,20 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
     int cfg = !big ? 1 : (NB >= 4 * 256 ? 4 : 2);       // 1: (4 waves, R=1)  4: (4, R=4)  2: (8 waves, R=2)  5: (4, R=4, split K)
     int grid = (NB + cfg - 1) / cfg;
     if constexpr (EPI != EPI_LOGITS) {
-        // more than 64 rows: 128 rows per sweep, activation tiles shared through LDS.  Matrices with
-        // few row blocks are split along K over workgroups when one sweep covers the pass; a second
+        // more than 64 rows: 128 rows per sweep, weight tiles shared through LDS.  Matrices with few
+        // row blocks are split along K over workgroups when one sweep covers the pass; a second
         // kernel adds the slabs in order and runs the epilogue.
         if (big && TB > 4) {
             const int NG = (NB + 7) / 8;
             if (cfg == 4 && EPI != EPI_QKV) {
-                hipLaunchKernelGGL((k_linear_mfma_wide<2, 5, EPI, false>), dim3(NG), dim3(256), 0, h->stream, a);
+                hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false>), dim3(NG), dim3(256), 0, h->stream, a);
                 return;
             }
             int KS = std::min(kSplitKMax, std::max(1, (h->n_cu + NG / 2) / NG));
             while (KS > 1 && (a.K / 32) / KS < 16) --KS;
             if (TB <= kWideTok && KS > 1 && (size_t)KS * NG * 8 * kWideTok * 256 <= kSplitKFloats) {
                 a.KS = KS; a.sk_part = h->sk_part;
-                hipLaunchKernelGGL((k_linear_mfma_wide<2, 5, EPI, true>), dim3(NG * KS), dim3(256), 0, h->stream, a);
+                hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, true>), dim3(NG * KS), dim3(256), 0, h->stream, a);
                 hipLaunchKernelGGL((k_sk_merge<EPI>), dim3((NB * kWideTok + 3) / 4), dim3(256), 0, h->stream, a, NG * 8);
                 return;
             }
@@ -556,7 +556,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
             if constexpr (is_bf16) {
                 PackArgs pa{h->x, d, cnt, nullptr, ly.g_ffn, m.eps, h->xp_a, h->xl_a, d};
                 { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa); }
-                c.xp = h->xp_a; c.xp_lo = h->xl_a; c.out_tiles = h->xp_h; c.out_tiles_lo = h->xl_h; c.out_KC = F / 32;
+                c.xp = h->xp_a; c.xp_lo = h->xl_a; c.out_tiles = h->xp_h; c.out_tiles_lo = h->xl_h; c.tbs = T16 / 16;
                 launch_mfma<EPI_SWIGLU>(h, mi, c, T);
             }
         } else {

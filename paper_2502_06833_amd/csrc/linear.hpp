@@ -36,7 +36,7 @@ struct LinArgs {
     const WT *res_embed;    // RES, optional: the residual is this embedding row instead of out (first layer)
     bf16_t *out_tiles;      // SWIGLU, optional: h as bf16 tiles (high parts) for the next MFMA layer
     bf16_t *out_tiles_lo;   //   and low parts
-    int out_KC;             //   K/32 of that consumer
+    int tbs;                // token blocks of the pass, (count + 15) / 16: the stride of activation tiles (xp, out_tiles) along k
     // QKV
     WT *kcache, *vcache;    // this layer's cache, [seq][kv_head][max_seq][hd]
     const int *row_seq, *row_pos;
@@ -102,7 +102,7 @@ __device__ __forceinline__ void epilogue(const LinArgs<WT> &a, int p, int t, flo
             int i = p >> 1;
             if (a.out) put(a.out + (size_t)t * a.ldo + i, h, COH);
             if (a.out_tiles) {
-                size_t off = tile_offset(t >> 4, i >> 5, a.out_KC) + (size_t)(((t & 15) + 16 * ((i & 31) >> 3)) * 8 + (i & 7));
+                size_t off = act_tile_offset(t >> 4, i >> 5, a.tbs) + (size_t)(((t & 15) + 16 * ((i & 31) >> 3)) * 8 + (i & 7));
                 split_bf16(h, a.out_tiles[off].u, a.out_tiles_lo[off].u);
             }
         }
@@ -340,7 +340,7 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma(LinArgs<bf16_t> a) {
         const bf16_t *xh[NT], *xl[NT];
 #pragma unroll
         for (int b = 0; b < NT; ++b) {       // token blocks past the end repeat the last one; their results are dropped
-            const size_t o = tile_offset(min(tb0 + b, TB - 1), kc0, KC) + lane * 8;
+            const size_t o = act_tile_offset(min(tb0 + b, TB - 1), kc0, TB) + lane * 8;
             xh[b] = a.xp + o; xl[b] = a.xp_lo + o;
         }
         const int gstep = SK ? NG : (int)gridDim.x;
@@ -357,11 +357,11 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma(LinArgs<bf16_t> a) {
             // k tile i of the wave's range into ring slot s; past the end the last tile is
             // fetched again (from cache) and not used, so no branch surrounds the loads
             auto issue = [&](int s, int i) __attribute__((always_inline)) {
-                const size_t off = (size_t)max(min(i, nsteps - 1), 0) * 512;
+                const size_t off = (size_t)max(min(i, nsteps - 1), 0) * 512, xoff = off * TB;
 #pragma unroll
                 for (int r = 0; r < R; ++r) wa[s][r].load_stream(wp[r] + off);
 #pragma unroll
-                for (int b = 0; b < NT; ++b) { xa[s][b].load(xh[b] + off); la[s][b].load(xl[b] + off); }
+                for (int b = 0; b < NT; ++b) { xa[s][b].load(xh[b] + xoff); la[s][b].load(xl[b] + xoff); }
             };
 #pragma unroll
             for (int s = 0; s < D; ++s) {    // in slot order: the waits below count on it
@@ -527,45 +527,47 @@ __device__ __forceinline__ void block_epilogue(const LinArgs<bf16_t> &a, float (
 
 constexpr int kWideTok = 8;          // token blocks (of 16 rows) per sweep
 
-template <int R, int DA, int EPI, bool SK = false>
-__global__ __launch_bounds__(256) void k_linear_mfma_wide(LinArgs<bf16_t> a) {
-    constexpr int NT = kWideTok, BT = 2 * NT / 4;      // activation tiles a wave fetches per step
-    __shared__ __attribute__((aligned(16))) bf16_t s_b[2][2 * NT][512];
+// Passes of more than 64 rows: a workgroup takes 8 row blocks and 128 token rows per sweep; each of
+// its four waves owns two token blocks and all 8 row blocks.  A wave's activation fragments (hi and lo
+// of its two blocks) come straight from memory in the matrix cores' operand layout and are never
+// shared; the step's 8 weight tiles, of which each wave fetches two, go through LDS (8 KB read per
+// wave and step; sharing the activation tiles instead, with a row-block pair per wave, reads 16 KB
+// and is no faster).  SK: workgroup (g, ks) takes slab ks of K for group g (one sweep only: TB <= 8)
+// and leaves its sums in memory for k_sk_merge.
+template <int DA, int EPI, bool SK = false>
+__global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
+    constexpr int NT = kWideTok, RG = 8;               // token blocks per sweep, row blocks per workgroup
+    __shared__ __attribute__((aligned(16))) bf16_t s_w[2][RG][512];
     __shared__ __attribute__((aligned(16))) float s_t[4][64][4];
-    const int K = a.K, KCfull = K >> 5, NB = a.Np >> 4, NG = (NB + 4 * R - 1) / (4 * R);
+    const int K = a.K, KCfull = K >> 5, NB = a.Np >> 4, NG = (NB + RG - 1) / RG;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int T = *a.count;
     const int TB = (T + 15) >> 4;
     if (TB == 0) return;
-    // SK: workgroup (g, ks) takes slab ks of K for group g (one sweep only: TB <= NT) and leaves
-    // its sums in memory for k_sk_merge
     const int KS = SK ? a.KS : 1;
     const int g = SK ? (int)blockIdx.x / KS : (int)blockIdx.x, ks = SK ? (int)blockIdx.x % KS : 0;
     const int kbase = (ks * KCfull) / KS, KC = ((ks + 1) * KCfull) / KS - kbase;     // this workgroup's k tiles
-    EntStat st; st.init();            // unused by the epilogues this kernel is built for
 
     for (int tb0 = 0; tb0 < TB; tb0 += NT) {
-        f32x4_t acc[R][NT];
-        const bf16_t *wp[R], *bp[BT];
+        f32x4_t acc[RG][2];
+        const bf16_t *wp[2], *bp[4];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
+        for (int j = 0; j < RG; ++j) acc[j][0] = acc[j][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int b = 0; b < NT; ++b) acc[r][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            wp[r] = a.W + tile_offset(min((g * 4 + wave) * R + r, NB - 1), kbase, KCfull) + lane * 8;
+        for (int q = 0; q < 2; ++q) {
+            wp[q] = a.W + tile_offset(min(g * RG + wave * 2 + q, NB - 1), kbase, KCfull) + lane * 8;
+            const int blk = min(tb0 + wave * 2 + q, TB - 1);
+            bp[q] = a.xp_lo + act_tile_offset(blk, kbase, TB) + lane * 8;          // lo of block q, then hi
+            bp[2 + q] = a.xp + act_tile_offset(blk, kbase, TB) + lane * 8;
         }
-#pragma unroll
-        for (int q = 0; q < BT; ++q) {           // tile j of the step: j < NT hi of token block j, else lo of block j - NT
-            const int jt = wave * BT + q, blk = min(tb0 + (jt < NT ? jt : jt - NT), TB - 1);
-            bp[q] = (jt < NT ? a.xp : a.xp_lo) + tile_offset(blk, kbase, KCfull) + lane * 8;
-        }
-        Vec8<bf16_t> wa[DA][R], ba[DA][BT];
+        Vec8<bf16_t> wa[DA][2], ba[DA][4];
         auto issue = [&](int s, int i) __attribute__((always_inline)) {
             const size_t off = (size_t)min(i, KC - 1) * 512;
 #pragma unroll
-            for (int q = 0; q < BT; ++q) ba[s][q].load(bp[q] + off);
+            for (int q = 0; q < 2; ++q) wa[s][q].load_stream(wp[q] + off);
 #pragma unroll
-            for (int r = 0; r < R; ++r) wa[s][r].load_stream(wp[r] + off);
+            for (int q = 0; q < 4; ++q) ba[s][q].load(bp[q] + off * TB);
         };
 #pragma unroll
         for (int s = 0; s < DA; ++s) {
@@ -577,25 +579,25 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wide(LinArgs<bf16_t> a) {
             for (int s = 0; s < DA; ++s) {
                 const int i = i0 + s;
                 if (i < KC) {                                  // uniform over the workgroup
-                    bf16_t (*buf)[512] = s_b[i & 1];
+                    bf16_t (*buf)[512] = s_w[i & 1];
 #pragma unroll
-                    for (int q = 0; q < BT; ++q)
-                        *reinterpret_cast<u32x4_t *>(&buf[wave * BT + q][lane * 8]) = ba[s][q].raw;
+                    for (int q = 0; q < 2; ++q)
+                        *reinterpret_cast<u32x4_t *>(&buf[wave * 2 + q][lane * 8]) = wa[s][q].raw;
                     __syncthreads();
-                    // all fragments of the step are requested before the first product, and
-                    // neighbouring products go to different accumulators: with one wave per SIMD
-                    // nothing else hides the LDS latency or the matrix cores' result latency
-                    u32x4_t fr[2 * NT];                        // lo of blocks 0..NT-1, then hi
+                    u32x4_t fw[RG];
 #pragma unroll
-                    for (int b = 0; b < 2 * NT; ++b)
-                        fr[b] = *reinterpret_cast<const u32x4_t *>(&buf[b < NT ? NT + b : b - NT][lane * 8]);
+                    for (int j = 0; j < RG; ++j) fw[j] = *reinterpret_cast<const u32x4_t *>(&buf[j][lane * 8]);
                     __builtin_amdgcn_sched_barrier(0);
+                    // lo products of all 16 accumulators, then the hi products: neighbouring
+                    // products never wait for each other's result
 #pragma unroll
-                    for (int b = 0; b < 2 * NT; ++b)
+                    for (int h = 0; h < 2; ++h)
 #pragma unroll
-                        for (int r = 0; r < R; ++r)
-                            acc[r][b % NT] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                __builtin_bit_cast(bf16x8_t, wa[s][r].raw), __builtin_bit_cast(bf16x8_t, fr[b]), acc[r][b % NT], 0, 0, 0);
+                        for (int j = 0; j < RG; ++j)
+#pragma unroll
+                            for (int q = 0; q < 2; ++q)
+                                acc[j][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                    __builtin_bit_cast(bf16x8_t, fw[j]), __builtin_bit_cast(bf16x8_t, ba[s][h * 2 + q].raw), acc[j][q], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 issue(s, i + DA);
@@ -604,32 +606,31 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wide(LinArgs<bf16_t> a) {
         }
         if constexpr (!SK) {
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+            for (int j = 0; j < RG; ++j)
 #pragma unroll
-                for (int b = 0; b < NT; ++b) {
-                    const int rb = (g * 4 + wave) * R + r;
-                    block_epilogue<EPI>(a, s_t[wave], rb, tb0 + b, acc[r][b], rb < NB && tb0 + b < TB, T, lane);
+                for (int q = 0; q < 2; ++q) {
+                    const int rb = g * RG + j, tb = tb0 + wave * 2 + q;
+                    block_epilogue<EPI>(a, s_t[wave], rb, tb, acc[j][q], rb < NB && tb < TB, T, lane);
                 }
         } else {
-            // this slab's sums: [slab][row block][token block][component 4][lane 64], so that the 64
-            // lanes of one store write 256 contiguous bytes; k_sk_merge adds the slabs in order
-            const size_t slab = (size_t)NG * 4 * R * NT * 256;             // floats per slab
+            const size_t slab = (size_t)NG * RG * NT * 256;                // floats per slab
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+            for (int j = 0; j < RG; ++j)
 #pragma unroll
-                for (int b = 0; b < NT; ++b) {
-                    const int rb = (g * 4 + wave) * R + r;
+                for (int q = 0; q < 2; ++q) {
+                    const int rb = g * RG + j, b = wave * 2 + q;
                     if (rb < NB && b < TB) {
                         float *dst = a.sk_part + (size_t)ks * slab + ((size_t)rb * NT + b) * 256 + lane;
-                        st_coherent(dst, acc[r][b][0]); st_coherent(dst + 64, acc[r][b][1]); st_coherent(dst + 128, acc[r][b][2]); st_coherent(dst + 192, acc[r][b][3]);
+                        st_coherent(dst, acc[j][q][0]); st_coherent(dst + 64, acc[j][q][1]);
+                        st_coherent(dst + 128, acc[j][q][2]); st_coherent(dst + 192, acc[j][q][3]);
                     }
                 }
         }
-        __syncthreads();                 // the activation buffers are reused by the next sweep
+        __syncthreads();                 // the weight buffers are reused by the next sweep
     }
 }
 
-// Sum of the K slabs that k_linear_mfma_wide<..., SK = true> left in memory, in slab order, then
+// Sum of the K slabs that k_linear_mfma_wt<..., SK = true> left in memory, in slab order, then
 // the epilogue.  One wave per 16 x 16 block; grid = ceil(row blocks * kWideTok / 4) workgroups.
 template <int EPI>
 __global__ __launch_bounds__(256) void k_sk_merge(LinArgs<bf16_t> a, int NGR /* row blocks incl. padding */) {
@@ -695,7 +696,7 @@ __global__ __launch_bounds__(256) void k_pack_act(PackArgs a) {
                 f[4] *= inv * g1.x; f[5] *= inv * g1.y; f[6] *= inv * g1.z; f[7] *= inv * g1.w;
             }
         }
-        const size_t off = tile_offset(t >> 4, k >> 5, KC) + (size_t)(((t & 15) + 16 * ((k & 31) >> 3)) * 8);
+        const size_t off = act_tile_offset(t >> 4, k >> 5, (T + 15) >> 4) + (size_t)(((t & 15) + 16 * ((k & 31) >> 3)) * 8);
         float hi[8], lo[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) { hi[e] = bf16_to_f32(f32_to_bf16(f[e])); lo[e] = f[e] - hi[e]; }
