@@ -421,6 +421,7 @@ void launch_valu(ead_handle *h, int mi, LinArgs<WT> &a, int T, int grid) {
 //  * small matrices are latency-bound: one row block per four-wave workgroup, as many
 //    workgroups as possible.
 // NT token blocks per pass follow T; the ring depth D follows the register budget.
+constexpr float kSmallLaneMin = 0.3f;                  // grouped schedule, two lanes: see decode_grouped
 constexpr int kSplitKGroups = 4096;                     // arrival counters
 constexpr size_t kSplitKFloats = (size_t)8 << 20;      // partial sums: KS slabs of (padded Np) x 128 floats at most
 
@@ -931,6 +932,10 @@ ead_status decode_grouped(ead_handle *h, int n_tokens) {
             }
             for (int m = 1; m >= 0; --m) {
                 if (busy[m] || n[m] == 0 || (m == 1 && h->sched_phase != 1)) continue;
+                // a small pass costs the same 170 launches for 5 rows as for 50 and slows the
+                // large pass beside it: while the large lane is busy the small lane waits until
+                // kSmallLaneMin of the unfinished rows are ready for it
+                if (m == 0 && busy[1] && (float)n[0] < kSmallLaneMin * (float)N) continue;
                 use_lane(h, m);
                 std::fill(em[m].begin(), em[m].end(), 0);
                 int T = 0;
