@@ -16,6 +16,7 @@ template <typename KT>
 struct AttnArgs {
     const float *q;            // [T, H*hd]
     const KT *kcache, *vcache; // this layer: [seq][kv_head][max_seq][hd]
+    const KT *vtcache;         // V once more, transposed in tiles per (seq, kv_head) (vt_offset; k_attn_mfma), or null
     const int *count, *row_seq, *row_pos;
     int n_heads, n_kv_heads, max_seq;
     int chunk;                 // keys per split
@@ -256,5 +257,240 @@ __global__ __launch_bounds__(kAttnWaves * 64) void k_attn(AttnArgs<KT> a) {
         attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, h * HD + dd, acc / L, (count + 15) >> 4);
     }
 }
+
+// ------------------------------------------------------------------------------------
+// The same attention on the matrix cores, for passes of many rows.  With G query heads per
+// KV head the kernel above spends about 5 G arithmetic instructions per byte of K/V and is
+// bound by them from G = 4 up; here scores and weighted sums are 16x16x32 products.
+//
+// A workgroup (8 waves) takes one (group of rows, KV head, key split).  A group is up to
+// RQ = 16 / G consecutive rows of one sequence (a catch-up chunk, cut at positions that are
+// multiples of RQ): their RQ * G query vectors are the 16 columns of every product, so the
+// sequence's K and V are streamed once for all of them.  Row t leads a group unless row
+// t - 1 belongs to the same sequence and pos_t is not a multiple of RQ; other rows' workgroups
+// exit at once.
+//
+// Per block of 32 keys a wave forms S^T = K Q^T (keys x columns; A = 16 key rows of K as they
+// lie in the cache, B = Q^T, q as a bf16 hi + lo pair) in two tiles whose rows are interleaved
+// (tile 0: keys 0-3, 8-11, ..; tile 1: keys 4-7, 12-15, ..): lane group l/16 then holds the
+// scores of keys 8 (l/16) .. +7 of its column, which is the B operand layout of the second
+// product O^T += V^T P^T (hd x columns; A = 16 rows of the transposed V copy, 8 consecutive
+// keys per lane; p as a bf16 hi + lo pair).  Online soft-max per column; columns live in
+// lane % 16 in S^T and in O^T alike, so the rescale stays inside the lane.  Waves, then key
+// splits, are merged as in k_attn.
+// ------------------------------------------------------------------------------------
+constexpr int kAttnMfmaWaves = 8;
+
+template <int HD, int G>
+__global__ __launch_bounds__(kAttnMfmaWaves * 64) void k_attn_mfma(AttnArgs<bf16_t> a) {
+    constexpr int RQ = 16 / G;            // rows per group
+    constexpr int KC = HD / 32;           // k steps of the score product
+    constexpr int HB = HD / 16;           // row tiles of O^T
+    __shared__ float s_o[kAttnMfmaWaves][HD / 2][17];     // the waves' sums meet here, one half of hd at a time
+    __shared__ float s_m[kAttnMfmaWaves][16], s_l[kAttnMfmaWaves][16];
+    __shared__ int s_ticket;
+    const int t = blockIdx.z, tz = gridDim.z;
+    // everything the grouping needs is requested at once (indices clamped to the launch's rows)
+    const int count = *a.count, pos = a.row_pos[t], prev = a.row_seq[max(t - 1, 0)];
+    int rs[RQ];
+#pragma unroll
+    for (int i = 0; i < RQ; ++i) rs[i] = a.row_seq[min(t + i, tz - 1)];
+    if (t >= count) return;
+    const int seq = rs[0];
+    if (t > 0 && prev == seq && pos % RQ != 0) return;                     // its group's leader serves this row
+    int n = 1;
+#pragma unroll
+    for (int i = 1; i < RQ; ++i)
+        if (n == i && t + i < count && rs[i] == seq && (pos + i) % RQ != 0) n = i + 1;
+    const int kvh = blockIdx.y, split = blockIdx.x;
+    const int nkeys = pos + n;                                             // keys of the group's last row
+    const int k0 = split * a.chunk;
+    if (k0 >= nkeys) return;
+    const int k1 = min(k0 + a.chunk, nkeys);
+    const int nsplit = (nkeys + a.chunk - 1) / a.chunk;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 15, lg = lane >> 4;
+    const int H = a.n_heads;
+    const int cr = col / G, cg = col % G;                                  // the column's row in the group and query head
+    const bool col_ok = cr < n;
+    const int lim = col_ok ? pos + cr : -1;                                // last key the column may see
+
+    // Q^T fragments: column col, hd elements kc*32 + lg*8 .. +8, scaled, as bf16 hi + lo
+    bf16x8_t qh[KC], ql[KC];
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+        float f[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (col_ok) {
+            const float *qp = a.q + (size_t)(t + cr) * H * HD + (size_t)(kvh * G + cg) * HD + kc * 32 + lg * 8;
+            const float4 x0 = *reinterpret_cast<const float4 *>(qp), x1 = *reinterpret_cast<const float4 *>(qp + 4);
+            f[0] = x0.x; f[1] = x0.y; f[2] = x0.z; f[3] = x0.w; f[4] = x1.x; f[5] = x1.y; f[6] = x1.z; f[7] = x1.w;
+        }
+        u32x4_t h4, l4;
+        uint32_t hw[8], lw[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { uint16_t hi, lo; split_bf16(f[e] * a.scale, hi, lo); hw[e] = hi; lw[e] = lo; }
+        h4 = u32x4_t{hw[0] | (hw[1] << 16), hw[2] | (hw[3] << 16), hw[4] | (hw[5] << 16), hw[6] | (hw[7] << 16)};
+        l4 = u32x4_t{lw[0] | (lw[1] << 16), lw[2] | (lw[3] << 16), lw[4] | (lw[5] << 16), lw[6] | (lw[7] << 16)};
+        qh[kc] = __builtin_bit_cast(bf16x8_t, h4); ql[kc] = __builtin_bit_cast(bf16x8_t, l4);
+    }
+
+    const size_t base = ((size_t)seq * a.n_kv_heads + kvh) * (size_t)a.max_seq * HD;
+    const bf16_t *kbase = a.kcache + base + lg * 8;                        // + key * HD + kc * 32
+    const bf16_t *vbase = a.vtcache + base + col * 32 + lg * 8;           // + tile (hb, block) * 512, see vt_offset
+    // row r of score tile 0 is key 8 (r / 4) + r % 4 of the block, of tile 1 that key + 4
+    const int krow = 8 * (col >> 2) + (col & 3);
+
+    f32x4_t acc[HB];
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) acc[hb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m = kNegBig, lsum = 0.f;
+
+    auto request = [&](Vec8<bf16_t> (&kx)[2][KC], Vec8<bf16_t> (&vx)[HB], int kb) __attribute__((always_inline)) {
+        // blocks and keys past the end of the split are read from its last block / key and masked
+        const int kbc = min(kb, ((k1 - 1 - k0) & ~31) + k0);
+#pragma unroll
+        for (int ti = 0; ti < 2; ++ti) {
+            const int key = min(kbc + krow + 4 * ti, k1 - 1);
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) kx[ti][kc].load(kbase + (size_t)key * HD + kc * 32);
+        }
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) vx[hb].load(vbase + ((size_t)hb * (a.max_seq >> 5) + (kbc >> 5)) * 512);
+    };
+    auto take = [&](const Vec8<bf16_t> (&kx)[2][KC], const Vec8<bf16_t> (&vx)[HB], int kb) __attribute__((always_inline)) {
+        f32x4_t s0 = f32x4_t{0.f, 0.f, 0.f, 0.f}, s1 = s0;
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kx[0][kc].raw), ql[kc], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kx[1][kc].raw), ql[kc], s1, 0, 0, 0);
+        }
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kx[0][kc].raw), qh[kc], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kx[1][kc].raw), qh[kc], s1, 0, 0, 0);
+        }
+        // this lane: keys kb + 8 lg + e, e = 0..7 (s0 holds e < 4), of column col
+        float sc[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+        bool ok[8];
+        float mc = kNegBig;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int key = kb + 8 * lg + e;
+            ok[e] = key < k1 && key <= lim;
+            sc[e] = ok[e] ? sc[e] : kNegBig;
+            mc = fmaxf(mc, sc[e]);
+        }
+        mc = fmaxf(mc, __shfl_xor(mc, 16, kWave));
+        mc = fmaxf(mc, __shfl_xor(mc, 32, kWave));
+        const float mn = fmaxf(m, mc);
+        const float corr = __expf(m - mn);               // 1 while the column has seen no key
+        m = mn;
+        float ps = 0.f;
+        uint32_t hw[8], lw[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float p = ok[e] ? __expf(sc[e] - mn) : 0.f;
+            ps += p;
+            uint16_t hi, lo; split_bf16(p, hi, lo); hw[e] = hi; lw[e] = lo;
+        }
+        lsum = lsum * corr + ps;
+        const bf16x8_t ph = __builtin_bit_cast(bf16x8_t, u32x4_t{hw[0] | (hw[1] << 16), hw[2] | (hw[3] << 16), hw[4] | (hw[5] << 16), hw[6] | (hw[7] << 16)});
+        const bf16x8_t pl = __builtin_bit_cast(bf16x8_t, u32x4_t{lw[0] | (lw[1] << 16), lw[2] | (lw[3] << 16), lw[4] | (lw[5] << 16), lw[6] | (lw[7] << 16)});
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) {
+            acc[hb][0] *= corr; acc[hb][1] *= corr; acc[hb][2] *= corr; acc[hb][3] *= corr;
+        }
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) acc[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vx[hb].raw), pl, acc[hb], 0, 0, 0);
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) acc[hb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vx[hb].raw), ph, acc[hb], 0, 0, 0);
+    };
+    {
+        Vec8<bf16_t> ka[2][KC], va[HB], kb2[2][KC], vb2[HB];
+        constexpr int STEP = kAttnMfmaWaves * 32;
+        int kb = k0 + wave * 32;
+        request(ka, va, kb);
+        while (kb < k1) {
+            request(kb2, vb2, kb + STEP);
+            __builtin_amdgcn_sched_barrier(0);
+            take(ka, va, kb);
+            kb += STEP;
+            if (kb >= k1) break;
+            request(ka, va, kb + STEP);
+            __builtin_amdgcn_sched_barrier(0);
+            take(kb2, vb2, kb);
+            kb += STEP;
+        }
+    }
+    // the column's sum over the four lane groups (m is already the same in all of them)
+    lsum += __shfl_xor(lsum, 16, kWave);
+    lsum += __shfl_xor(lsum, 32, kWave);
+    // the waves meet in LDS.  acc[hb][j]: hd = hb*16 + 4*lg + j, column col
+    if (lg == 0) { s_m[wave][col] = m; s_l[wave][col] = lsum; }
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        if (half) __syncthreads();
+#pragma unroll
+        for (int hb = 0; hb < HB / 2; ++hb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s_o[wave][hb * 16 + 4 * lg + j][col] = acc[half * (HB / 2) + hb][j];
+        __syncthreads();
+        for (int e = tid; e < n * G * (HD / 2); e += kAttnMfmaWaves * 64) {
+            const int c = e / (HD / 2), dl = e % (HD / 2), dd = half * (HD / 2) + dl;    // column (row in group * G + head), hd element
+            float M = kNegBig;
+#pragma unroll
+            for (int w = 0; w < kAttnMfmaWaves; ++w) M = fmaxf(M, s_m[w][c]);
+            float L = 0.f, o = 0.f;
+#pragma unroll
+            for (int w = 0; w < kAttnMfmaWaves; ++w) {
+                const float cw = __expf(s_m[w][c] - M);
+                L += s_l[w][c] * cw;
+                o += s_o[w][dl][c] * cw;
+            }
+            const int tr = t + c / G, h = kvh * G + c % G;
+            if (nsplit == 1) attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, tr, H, h * HD + dd, o / L, (count + 15) >> 4);
+            else {
+                const size_t item = ((size_t)tr * H + h) * a.max_splits + split;
+                st_coherent(a.part_o + item * HD + dd, o);
+                if (dd == 0) {
+                    float *ml = reinterpret_cast<float *>(a.part_ml + item);
+                    st_coherent(ml, M); st_coherent(ml + 1, L);
+                }
+            }
+        }
+    }
+    if (nsplit == 1) return;
+    wait_stores();
+    __syncthreads();
+    int *tk = a.tickets + t * a.n_kv_heads + kvh;
+    if (tid == 0) s_ticket = __hip_atomic_fetch_add(tk, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_ticket != nsplit - 1) return;
+    if (tid == 0) st_coherent(tk, 0);
+    for (int e = tid; e < n * G * HD; e += kAttnMfmaWaves * 64) {
+        const int c = e / HD, dd = e % HD, tr = t + c / G, h = kvh * G + c % G;
+        const size_t item0 = ((size_t)tr * H + h) * a.max_splits;
+        float mm[kAttnMaxSplits], ll[kAttnMaxSplits], oo[kAttnMaxSplits];
+#pragma unroll
+        for (int sp = 0; sp < kAttnMaxSplits; ++sp) {
+            if (sp < nsplit) {
+                const float *ml = reinterpret_cast<const float *>(a.part_ml + item0 + sp);
+                mm[sp] = ld_coherent(ml); ll[sp] = ld_coherent(ml + 1);
+                oo[sp] = ld_coherent(a.part_o + (item0 + sp) * HD + dd);
+            } else { mm[sp] = kNegBig; ll[sp] = 0.f; oo[sp] = 0.f; }
+        }
+        float M = kNegBig;
+#pragma unroll
+        for (int sp = 0; sp < kAttnMaxSplits; ++sp) M = fmaxf(M, mm[sp]);
+        float L = 0.f, o = 0.f;
+#pragma unroll
+        for (int sp = 0; sp < kAttnMaxSplits; ++sp) {
+            const float cw = __expf(mm[sp] - M);
+            L += ll[sp] * cw;
+            o += oo[sp] * cw;
+        }
+        attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, tr, H, h * HD + dd, o / L, (count + 15) >> 4);
+    }
+}
+
 
 }  // namespace ead

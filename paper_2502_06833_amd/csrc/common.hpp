@@ -136,6 +136,14 @@ __host__ __device__ __forceinline__ size_t act_tile_offset(int tb, int kc, int T
     return ((size_t)kc * (size_t)TB + (size_t)tb) * 512;
 }
 
+// Transposed copy of V for the matrix-core attention, per (sequence, KV head): tiles of 16 hd
+// rows x 32 positions, 1 KB each, ordered [hd / 16][pos / 32]; inside a tile [hd % 16][pos % 32].
+// A tile is the A operand of the 16x16x32 product that contracts over keys, read by one
+// contiguous 1 KB load.  max_seq is a multiple of 32.
+__host__ __device__ __forceinline__ size_t vt_offset(int dim, int pos, int max_seq) {
+    return (((size_t)(dim >> 4) * (size_t)(max_seq >> 5) + (size_t)(pos >> 5)) * 16 + (size_t)(dim & 15)) * 32 + (size_t)(pos & 31);
+}
+
 // ---- online soft-max statistics for the entropy (Eq. 1-2) ------------------------------
 // For a set of logits: m = max, Z = sum exp(l-m), S = sum exp(l-m)(l-m), plus the arg max
 // (lowest index on ties).  H = ln Z - S/Z.  merge() combines two disjoint sets.

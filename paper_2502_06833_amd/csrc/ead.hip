@@ -141,7 +141,7 @@ __global__ __launch_bounds__(64) void k_entropy_finalize(const EntPartial *parti
 // ======================================================================================
 // host structures
 // ======================================================================================
-struct Layer { void *wqkv, *wo, *wgu, *wdown; float *g_attn, *g_ffn; void *kcache, *vcache; };
+struct Layer { void *wqkv, *wo, *wgu, *wdown; float *g_attn, *g_ffn; void *kcache, *vcache, *vtcache; };
 
 struct Model {
     int L, d, H, KV, hd, F, V, dtype;
@@ -346,7 +346,15 @@ ead_status build_model(ead_handle *h, const ead_model_desc *src, Model *m, int m
         HIP_TRY(h, hipMemcpyAsync(ly.g_ffn, src->norm_ffn[l], d * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
         WT *kc = nullptr, *vc = nullptr;
         TRY(dmalloc(h, &kc, cache_elems)); TRY(dmalloc(h, &vc, cache_elems));
-        ly.kcache = kc; ly.vcache = vc;
+        ly.kcache = kc; ly.vcache = vc; ly.vtcache = nullptr;
+        if (std::is_same<WT, bf16_t>::value && max_seq % 32 == 0) {
+            // the matrix-core attention reads whole 32-key blocks of this copy and multiplies what lies
+            // past a row's last key by zero: it must never hold anything but finite values
+            WT *vt = nullptr;
+            TRY(dmalloc(h, &vt, cache_elems));
+            HIP_TRY(h, hipMemsetAsync(vt, 0, cache_elems * sizeof(WT), h->stream));
+            ly.vtcache = vt;
+        }
     }
     // rotary table in double precision: angle = pos * theta^(-2i/hd)
     std::vector<float2> tab((size_t)max_seq * (hd / 2));
@@ -370,7 +378,7 @@ ead_status build_model(ead_handle *h, const ead_model_desc *src, Model *m, int m
             mats.push_back({(const WT *)ly.wo, d / 16, NQ / 32, 0});
             mats.push_back({(const WT *)ly.wgu, 2 * m->F / 16, d / 32, 0});
             mats.push_back({(const WT *)ly.wdown, d / 16, m->F / 32, 0});
-            lys.push_back({ly.g_attn, ly.g_ffn, (WT *)ly.kcache, (WT *)ly.vcache});
+            lys.push_back({ly.g_attn, ly.g_ffn, (WT *)ly.kcache, (WT *)ly.vcache, (WT *)ly.vtcache});
         }
         mats.push_back({(const WT *)m->lm_head, m->V / 16, d / 32, 0});
         m->n_mats = (int)mats.size();
@@ -481,6 +489,17 @@ void launch_attn(ead_handle *h, int mi, AttnArgs<KT> &a, int G, int T, double kv
     // one per KV head, so K and V are streamed once for the heads that share them
     const bool per_head = (long)T * a.n_kv_heads * a.max_splits <= 64;
     dim3 grid(a.max_splits, per_head ? a.n_heads : a.n_kv_heads, T);
+    if constexpr (std::is_same<KT, bf16_t>::value) {
+        // many rows: scores and weighted sums on the matrix cores, rows of one sequence grouped
+        if (!per_head && a.vtcache) {
+            ProfScope ps(h, PK_ATTN, mi, kv_bytes);
+#define EAD_LM_(G_) hipLaunchKernelGGL((k_attn_mfma<HD, G_>), grid, dim3(kAttnMfmaWaves * 64), 0, h->stream, a)
+            switch (G) { case 1: EAD_LM_(1); break; case 2: EAD_LM_(2); break; case 3: EAD_LM_(3); break; case 4: EAD_LM_(4); break;
+                         case 5: EAD_LM_(5); break; case 6: EAD_LM_(6); break; case 7: EAD_LM_(7); break; default: EAD_LM_(8); break; }
+#undef EAD_LM_
+            return;
+        }
+    }
     {
         ProfScope ps(h, PK_ATTN, mi, kv_bytes);
 #define EAD_LA(G_) do { if (per_head) hipLaunchKernelGGL((k_attn<KT, HD, G_, 1>), grid, dim3(kAttnWaves * 64), 0, h->stream, a); \
@@ -515,6 +534,10 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
     while ((long)T * m.KV * ((ctx_max + chunk - 1) / chunk) > 1024 && chunk < 65536) chunk <<= 1;
     while ((ctx_max + chunk - 1) / chunk > kAttnMaxSplits) chunk <<= 1;
     while ((long)T * ((ctx_max + chunk - 1) / chunk) > h->items_max) chunk <<= 1;
+    // the matrix-core kernel (many rows) is bound by the latency of its short chains of loads, one
+    // workgroup per compute unit at a time: fewer, longer workgroups
+    if (is_bf16 && m.layers[0].vtcache && (long)T * m.KV * ((ctx_max + chunk - 1) / chunk) > 64)
+        while ((long)T * m.KV * ((ctx_max + chunk - 1) / chunk) > 2 * h->n_cu && chunk < 65536) chunk <<= 1;
     const int max_splits = (ctx_max + chunk - 1) / chunk;
 
     for (int l = 0; l < m.L; ++l) {
@@ -522,7 +545,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         // ---- RMSNorm + QKV + rotary + KV append ----
         LinArgs<WT> a{};
         a.W = (const WT *)ly.wqkv; a.Np = NQ + 2 * NK; a.K = d; a.count = cnt; a.out = h->q; a.ldo = NQ;
-        a.kcache = (WT *)ly.kcache; a.vcache = (WT *)ly.vcache; a.row_seq = h->plan.row_seq; a.row_pos = h->plan.row_pos;
+        a.kcache = (WT *)ly.kcache; a.vcache = (WT *)ly.vcache; a.vtcache = (WT *)ly.vtcache; a.row_seq = h->plan.row_seq; a.row_pos = h->plan.row_pos;
         a.rope = m.rope; a.n_heads = m.H; a.n_kv_heads = m.KV; a.hd = hd; a.max_seq = h->s.max_seq;
         if (mfma) {
             if constexpr (is_bf16) {
@@ -537,7 +560,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         }
         // ---- attention ----
         AttnArgs<WT> at{};
-        at.q = h->q; at.kcache = (const WT *)ly.kcache; at.vcache = (const WT *)ly.vcache; at.count = cnt;
+        at.q = h->q; at.kcache = (const WT *)ly.kcache; at.vcache = (const WT *)ly.vcache; at.vtcache = (const WT *)ly.vtcache; at.count = cnt;
         at.row_seq = h->plan.row_seq; at.row_pos = h->plan.row_pos; at.n_heads = m.H; at.n_kv_heads = m.KV;
         at.max_seq = h->s.max_seq; at.chunk = chunk; at.max_splits = max_splits; at.scale = 1.0f / sqrtf((float)hd);
         at.part_o = h->part_o; at.part_ml = h->part_ml; at.tickets = h->tickets;
@@ -723,7 +746,7 @@ ead_status validate_prompts(ead_handle *h, const int32_t *toks, const int32_t *l
     if (!toks || !lens) return fail(h, EAD_ERR_INVALID_ARG, "null prompt pointer");
     if (batch < 1 || max_new < 1) return fail(h, EAD_ERR_INVALID_ARG, "batch and max_new_tokens must be >= 1");
     if (batch > h->prm.max_batch) return fail(h, EAD_ERR_SEQ_OVERFLOW, "batch %d exceeds max_batch %d", batch, h->prm.max_batch);
-    if (max_new > h->s.cap) return fail(h, EAD_ERR_SEQ_OVERFLOW, "max_new_tokens %d exceeds max_seq %d", max_new, h->s.cap);
+    if (max_new > h->prm.max_seq) return fail(h, EAD_ERR_SEQ_OVERFLOW, "max_new_tokens %d exceeds max_seq %d", max_new, h->prm.max_seq);
     size_t off = 0;
     for (int b = 0; b < batch; ++b) {
         if (lens[b] < 1) return fail(h, EAD_ERR_INVALID_ARG, "prompt %d is empty", b);
@@ -1175,7 +1198,9 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
     h->cfg = GateCfg{p->window, p->tau, p->d_min};
     ead_status rc = EAD_OK;
     auto body = [&]() -> ead_status {
-        const int MB = p->max_batch, MS = p->max_seq;
+        // internal strides are rounded up to whole 32-key blocks (the matrix-core attention reads such
+        // blocks of the transposed V copy); the caller's limit stays p->max_seq
+        const int MB = p->max_batch, MS = (p->max_seq + 31) & ~31;
         TRY(small_model->dtype == EAD_BF16 ? build_model<bf16_t>(h, small_model, &h->mdl[0], MB, MS)
                                            : build_model<float>(h, small_model, &h->mdl[0], MB, MS));
         TRY(large_model->dtype == EAD_BF16 ? build_model<bf16_t>(h, large_model, &h->mdl[1], MB, MS)

@@ -87,7 +87,7 @@ template <typename WT>
 struct FusedMat { const WT *W; int NB, KC; int stop_after; };   // stop_after: cursor pauses behind it
 
 template <typename WT>
-struct FusedLayer { const float *g_attn, *g_ffn; WT *kcache, *vcache; };
+struct FusedLayer { const float *g_attn, *g_ffn; WT *kcache, *vcache, *vtcache; };
 
 template <typename WT>
 struct FusedArgs {
@@ -533,7 +533,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_decode_fused(FusedArgs<WT> a)
             if (l == 0) stage_norm_embed<WT>(xs, s_red, emb, a.d, ly.g_attn, a.eps);
             else stage_norm(xs, s_red, a.x, a.d, ly.g_attn, a.eps);
             epi = EPI_QKV;
-            p.Np = NQ + 2 * NK; p.K = a.d; p.out = a.q; p.ldo = NQ; p.kcache = ly.kcache; p.vcache = ly.vcache;
+            p.Np = NQ + 2 * NK; p.K = a.d; p.out = a.q; p.ldo = NQ; p.kcache = ly.kcache; p.vcache = ly.vcache; p.vtcache = ly.vtcache;
             p.row_seq = &s_plan[0]; p.row_pos = &s_plan[1]; p.rope = a.rope; p.n_heads = a.H; p.n_kv_heads = a.KV;
             p.hd = HD; p.max_seq = a.fin.s.max_seq;
         } else if (kind == 2) {                 // output projection + residual

@@ -39,6 +39,7 @@ struct LinArgs {
     int tbs;                // token blocks of the pass, (count + 15) / 16: the stride of activation tiles (xp, out_tiles) along k
     // QKV
     WT *kcache, *vcache;    // this layer's cache, [seq][kv_head][max_seq][hd]
+    WT *vtcache;            // optional second copy of V, transposed in tiles (vt_offset): the matrix-core attention contracts over keys
     const int *row_seq, *row_pos;
     const float2 *rope;     // [max_seq][hd/2] (cos, sin)
     int n_heads, n_kv_heads, hd, max_seq;
@@ -126,6 +127,7 @@ __device__ __forceinline__ void epilogue(const LinArgs<WT> &a, int p, int t, flo
             int pp = p - NQ - NK, head = pp / hd, dim = pp % hd;
             size_t o = (((size_t)pre.seq * a.n_kv_heads + head) * a.max_seq + pos) * hd + dim;
             put(a.vcache + o, from_f32<WT>(v), COH);
+            if (a.vtcache) put(a.vtcache + ((size_t)pre.seq * a.n_kv_heads + head) * hd * a.max_seq + vt_offset(dim, pos, a.max_seq), from_f32<WT>(v), COH);
         }
     } else {                                          // EPI_LOGITS: fold the logit into (m, Z, S, argmax)
         if (!valid) return;
