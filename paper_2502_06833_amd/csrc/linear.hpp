@@ -51,6 +51,7 @@ struct LinArgs {
     float samp_inv_t; uint32_t samp_k0, samp_k1;
     const int *samp_seq, *samp_ngen;
     // MFMA path with K split over KS workgroups per row-block group
+    int tb_base;            // k_linear_mfma_wt with split K, k_sk_merge: first token block of the sweep this launch takes
     int KS;
     float *sk_part;         // [KS][groups][R][NT][256] partial sums
     int *sk_tickets;        // [groups] arrival counters, zero between launches
@@ -551,7 +552,7 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
     const int g = SK ? (int)blockIdx.x / KS : (int)blockIdx.x, ks = SK ? (int)blockIdx.x % KS : 0;
     const int kbase = (ks * KCfull) / KS, KC = ((ks + 1) * KCfull) / KS - kbase;     // this workgroup's k tiles
 
-    for (int tb0 = 0; tb0 < TB; tb0 += NT) {
+    for (int tb0 = SK ? a.tb_base : 0; tb0 < TB; tb0 += SK ? TB : NT) {       // split K: one sweep per launch
         f32x4_t acc[RG][2];
         const bf16_t *wp[2], *bp[4];
 #pragma unroll
@@ -621,7 +622,7 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
                     const int rb = g * RG + j, b = wave * 2 + q;
-                    if (rb < NB && b < TB) {
+                    if (rb < NB && tb0 + b < TB) {
                         float *dst = a.sk_part + (size_t)ks * slab + ((size_t)rb * NT + b) * 256 + lane;
                         st_coherent(dst, acc[j][q][0]); st_coherent(dst + 64, acc[j][q][1]);
                         st_coherent(dst + 128, acc[j][q][2]); st_coherent(dst + 192, acc[j][q][3]);
@@ -641,7 +642,7 @@ __global__ __launch_bounds__(256) void k_sk_merge(LinArgs<bf16_t> a, int NGR /* 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int NB = a.Np >> 4, T = *a.count, TB = (T + 15) >> 4, KS = a.KS;
     const int blk = blockIdx.x * 4 + wave, rb = blk / NT, b = blk % NT;
-    if (rb >= NB || b >= TB) return;
+    if (rb >= NB || a.tb_base + b >= TB) return;
     const size_t slab = (size_t)NGR * NT * 256;
     const float *src = a.sk_part + ((size_t)rb * NT + b) * 256 + lane;
     float pv[kSplitKMax][4];
@@ -654,7 +655,7 @@ __global__ __launch_bounds__(256) void k_sk_merge(LinArgs<bf16_t> a, int NGR /* 
 #pragma unroll
     for (int q = 0; q < kSplitKMax; ++q)
         if (q < KS) { d[0] += pv[q][0]; d[1] += pv[q][1]; d[2] += pv[q][2]; d[3] += pv[q][3]; }
-    block_epilogue<EPI>(a, s_t[wave], rb, b, d, true, T, lane);
+    block_epilogue<EPI>(a, s_t[wave], rb, a.tb_base + b, d, true, T, lane);
 }
 
 // ------------------------------------------------------------------------------------
