@@ -39,7 +39,12 @@ WORKLOADS = {
     "qwen_15b_14b_b1": ("qwen_15b_14b", 1, 512, 512, 1024, 0.25, 10),
     # stand-alone entropy / arg-max / window / switch epilogue on materialised logits
     "entropy_gate_b64": (None, 64, 0, 0, 4096, None, 10),
+    # prompt prefill of both models (the step before the decode path): steps = repetitions
+    "prefill_qwen_b64": ("qwen", 64, 128, 1024, 4, None, 10),
+    "prefill_llama_b8": ("llama", 8, 512, 512, 8, None, 10),
 }
+
+MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
 
 def log(*a):
@@ -109,6 +114,59 @@ def measured_traffic(workload, kernel):
     if rec.get("kernel") != kernel or rec.get("kernel_source_sha256_16") != h.hexdigest()[:16]:
         return None
     return rec["traffic_bytes_per_launch"]
+
+
+def linear_params(shape):
+    """Parameters of the per-layer matrices (what a prompt position multiplies; no embedding, no LM head)."""
+    hd = shape.d_model // shape.n_heads
+    per_layer = shape.d_model * (shape.n_heads + 2 * shape.n_kv_heads) * hd + shape.n_heads * hd * shape.d_model \
+        + 3 * shape.d_model * shape.d_ffn
+    return per_layer * shape.n_layers
+
+
+def bench_prefill(args):
+    """Prompt prefill of both models (ead_begin): every prompt position but the last through all layers of
+    the small and of the large model, in passes of up to 1024 rows; no LM head.  Reported against the dense
+    bf16 matrix-core peak with the algorithmic flops 2 * parameters * positions (the second product per
+    weight tile, for the low parts of the activations, is not counted) plus the causal attention flops."""
+    import torch
+    import paper_2502_06833_amd as ead
+    pair, batch, plo, phi, dsteps, _, d_min = WORKLOADS[args.workload]
+    reps = args.steps or dsteps
+    ss, sl = si.PAIRS[pair]
+    Ws = si.model_weights_torch(ss, args.seed, "cuda")
+    Wl = si.model_weights_torch(sl, args.seed, "cuda")
+    prompts = make_prompts(args.seed, batch, plo, phi, ss.vocab)
+    e = ead.EAD(ss, Ws, sl, Wl, window=5, tau=0.0, d_min=d_min, max_batch=batch, max_seq=max(len(p) for p in prompts) + 16)
+    del Ws, Wl
+    torch.cuda.empty_cache()
+    for _ in range(max(1, min(args.warmup, 2))):
+        e.begin(prompts, 8)
+    torch.cuda.synchronize()
+    a = time.perf_counter()
+    for _ in range(reps):
+        e.begin(prompts, 8)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - a) / reps
+    n_pos = sum(len(p) - 1 for p in prompts)
+    flops = 0.0
+    for sh in (ss, sl):
+        hd = sh.d_model // sh.n_heads
+        flops += 2.0 * linear_params(sh) * n_pos
+        flops += sum(4.0 * sh.n_layers * sh.n_heads * hd * (len(p) - 1) * len(p) / 2.0 for p in prompts)
+    tfl = flops / dt / 1e12
+    log(f"[bench] prefill: {n_pos} prompt positions through both models in {dt * 1e3:.1f} ms = {n_pos / dt:.0f} positions/s, "
+        f"{tfl:.0f} Tflop/s algorithmic ({tfl / MFMA_PEAK_TFLOPS:.1%} of the dense bf16 peak)")
+    out = {"metric": "prompt positions/s at 1 GPU (prefill of both models)", "value": n_pos / dt, "unit": "positions/s",
+           "n_gpus": 1, "steps": reps, "warmup": min(args.warmup, 2), "ms_per_step": dt * 1e3, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": args.workload, "small": ss.name, "large": sl.name, "batch": batch,
+                      "prompt_len": [plo, phi], "positions": n_pos},
+           "roofline": {"bound": "mfma", "achieved": tfl, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": tfl / MFMA_PEAK_TFLOPS, "traffic": None},
+           "cpu_baseline": None}
+    e.close()
+    print(json.dumps(out), flush=True)
 
 
 def bench_entropy_gate(args):
@@ -190,6 +248,8 @@ def main():
         sys.exit("bench.py needs a GPU")
     if args.workload == "entropy_gate_b64":
         return bench_entropy_gate(args)
+    if args.workload.startswith("prefill_"):
+        return bench_prefill(args)
     pair, batch, plo, phi, dsteps, target, d_min = WORKLOADS[args.workload]
     steps = args.steps or dsteps
     warmup = args.warmup

@@ -448,7 +448,9 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
         if (big && TB > 4) {
             const int NG = (NB + 7) / 8;
             if (cfg == 4 && EPI != EPI_QKV) {
-                hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false>), dim3(NG), dim3(256), 0, h->stream, a);
+                a.sweeps = (TB + kWideTok - 1) / kWideTok;
+                const int grid_wt = a.sweeps > 1 ? (NG + 7) / 8 * 8 * a.sweeps : NG;
+                hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false>), dim3(grid_wt), dim3(256), 0, h->stream, a);
                 return;
             }
             int KS = std::min(kSplitKMax, std::max(1, (h->n_cu + NG / 2) / NG));

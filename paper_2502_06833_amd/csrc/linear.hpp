@@ -52,6 +52,7 @@ struct LinArgs {
     const int *samp_seq, *samp_ngen;
     // MFMA path with K split over KS workgroups per row-block group
     int tb_base;            // k_linear_mfma_wt with split K, k_sk_merge: first token block of the sweep this launch takes
+    int sweeps;             // k_linear_mfma_wt without split K: > 1 = one workgroup per (row-block group, 128-row sweep)
     int KS;
     float *sk_part;         // [KS][groups][R][NT][256] partial sums
     int *sk_tickets;        // [groups] arrival counters, zero between launches
@@ -549,10 +550,19 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
     const int TB = (T + 15) >> 4;
     if (TB == 0) return;
     const int KS = SK ? a.KS : 1;
-    const int g = SK ? (int)blockIdx.x / KS : (int)blockIdx.x, ks = SK ? (int)blockIdx.x % KS : 0;
+    int g = SK ? (int)blockIdx.x / KS : (int)blockIdx.x, tb_first = SK ? a.tb_base : 0;
+    const int ks = SK ? (int)blockIdx.x % KS : 0;
+    const bool one_sweep = SK || a.sweeps > 1;
+    if (!SK && a.sweeps > 1) {
+        // workgroup id -> (group, sweep) such that the sweeps of one group run at about the same time on
+        // one XCD (id % 8) and find the group's weight tiles in its L2
+        const int q = (int)blockIdx.x >> 3, r = (int)blockIdx.x & 7;
+        g = (q / a.sweeps) * 8 + r; tb_first = (q % a.sweeps) * NT;
+        if (g >= NG || tb_first >= TB) return;
+    }
     const int kbase = (ks * KCfull) / KS, KC = ((ks + 1) * KCfull) / KS - kbase;     // this workgroup's k tiles
 
-    for (int tb0 = SK ? a.tb_base : 0; tb0 < TB; tb0 += SK ? TB : NT) {       // split K: one sweep per launch
+    for (int tb0 = tb_first; tb0 < TB; tb0 += one_sweep ? TB : NT) {
         f32x4_t acc[RG][2];
         const bf16_t *wp[2], *bp[4];
 #pragma unroll
