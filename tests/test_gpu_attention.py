@@ -1,0 +1,76 @@
+"""Matrix-core attention (passes of many rows) at long contexts: several key splits, groups of
+rows of one sequence that share a pass over its K/V, ragged group boundaries.  Narrow bf16
+models keep the oracle fast; the weights are drawn wider than usual (std 0.05) so that the
+attention weights are far from uniform and a wrong key or column mapping shows in the logits.
+Head layouts: G = 2 with head dim 32 (8 rows per group) and G = 3 with head dim 64 (5 rows per
+group); G = 4, 5, 7 with head dims 64 and 128 are covered at short contexts by the
+depth-truncated pairs of test_gpu_models.py."""
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+TOL_LOGIT, TOL_H, BAND = 2e-2, 1e-2, 1e-2
+
+ATT_S = si.ModelShape("att-s", 2, 256, 8, 4, 512, 512, 1e-5, 1e4, bf16=True)
+ATT_L = si.ModelShape("att-l", 2, 384, 6, 2, 768, 512, 1e-5, 1e4, bf16=True)
+
+
+@pytest.fixture(scope="module")
+def att():
+    import paper_2502_06833_amd as ead
+    Ws = si.model_weights_torch(ATT_S, 0, "cuda", 0.05)
+    Wl = si.model_weights_torch(ATT_L, 0, "cuda", 0.05)
+    os_ = oracle.Model(ATT_S, {k: v.float().cpu().numpy() for k, v in Ws.items()})
+    ol = oracle.Model(ATT_L, {k: v.float().cpu().numpy() for k, v in Wl.items()})
+    e = ead.EAD(ATT_S, Ws, ATT_L, Wl, window=5, tau=0.0, d_min=16, max_batch=3, max_seq=1250)
+    yield e, os_, ol
+    e.close()
+
+
+def test_long_context_scoring_against_oracle(att):
+    """1100 teacher-forced positions per model in passes of 160 rows: every row group but the
+    first and the last of a pass is full, contexts run from 1 to 1100 keys."""
+    e, os_, ol = att
+    toks = si.prompt_np(2, "att-long", 1100, ATT_S.vocab)
+    for which, om in ((0, os_), (1, ol)):
+        ref = om.forward_dense(toks)
+        out = e.score(which, toks)
+        err = np.abs(out["logits"] - ref).max(axis=1) / np.abs(ref).max(axis=1)
+        Hr, ar = oracle.entropy_rows(ref)
+        print(f"model {which}: logits rel err {err.max():.2e}, H err {np.abs(out['H'] - Hr).max():.2e}, "
+              f"H range {Hr.min():.2f}..{Hr.max():.2f}", flush=True)
+        assert err.max() < TOL_LOGIT
+        assert np.abs(out["H"] - Hr).max() < TOL_H
+        top2 = np.sort(ref, axis=1)
+        clear = (top2[:, -1] - top2[:, -2]) > 2 * TOL_LOGIT * np.abs(ref).max(axis=1)
+        assert (out["argmax"][clear] == ar[clear]).all()
+        assert Hr.max() - Hr.min() > 0.05            # the attention is not uniform: the test can see a wrong key
+
+
+def test_catchups_over_several_key_splits_against_oracle(att):
+    """Prompts of 1100, 700 and 37 tokens decoded together along the oracle's trajectories: every
+    switch makes the other model catch up 16 or more rows at contexts beyond 1024 keys (three key
+    splits of 512, merged by the last workgroup to arrive; row groups cut at multiples of 8 and 5)."""
+    e, os_, ol = att
+    prompts = [si.prompt_np(3, f"att{b}", n, ATT_S.vocab) for b, n in enumerate((1100, 700, 37))]
+    n_new, d_min = 56, 16
+    probe = oracle.generate(os_, ol, prompts[0], n_new, 5, 1e30, d_min=d_min)
+    tau = float(np.percentile(probe["Hbar"], 45))
+    refs = [oracle.generate(os_, ol, p, n_new, 5, tau, d_min=d_min) for p in prompts]
+    print("large share per row:", [float(r["model_id"].mean()) for r in refs], flush=True)
+    assert any(0.0 < r["model_id"].mean() < 1.0 for r in refs)         # at least one row switches
+    e.set_gate(5, tau, d_min)
+    rp = e.replay(prompts, np.stack([r["tokens"] for r in refs]), np.stack([r["model_id"] for r in refs]))
+    for b, r in enumerate(refs):
+        print(f"  row {b}: H err {np.abs(rp['H'][b] - r['H']).max():.2e}", flush=True)
+        assert np.abs(rp["H"][b] - r["H"]).max() < TOL_H
+        assert np.abs(rp["Hbar"][b] - r["Hbar"]).max() < TOL_H
+        safe = np.abs(r["Hbar"] - tau) > BAND
+        want_next = np.concatenate([r["model_id"][1:], rp["next_model"][b][-1:]])
+        assert (rp["next_model"][b][safe] == want_next[safe]).all()
+    st = e.stats()
+    assert st["catchup_rows_large"] >= 16
