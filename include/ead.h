@@ -109,7 +109,10 @@ typedef struct {
 
 /* Build a handle for a model pair (Algorithm 1's M_S, M_L, tau, w, d_min).
  * Copies both models into the library's layout and allocates KV caches for
- * max_batch x max_seq positions per model.  Errors: INVALID_ARG, SHAPE,
+ * max_batch x max_seq positions per model (max_seq rounded up to a multiple of
+ * 32 internally; in the weight dtype; bf16 models keep V a second time,
+ * transposed, for the matrix-core attention: 1.5 x the K + V bytes in all).
+ * Errors: INVALID_ARG, SHAPE,
  * VOCAB_MISMATCH, OOM, NO_DEVICE, DEVICE.  *out is NULL on error. */
 ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *large_model,
                       const ead_params *params, ead_handle **out);
