@@ -455,9 +455,8 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
             }
             int KS = std::min(kSplitKMax, std::max(1, (h->n_cu + NG / 2) / NG));
             while (KS > 1 && (a.K / 32) / KS < 16) --KS;
-            // (longer passes -- prefill, teacher-forced scoring -- take one launch pair per sweep for the
-            // residual projections; their QKV projection is faster 64 rows at a time)
-            if ((TB <= kWideTok || EPI == EPI_RES) && KS > 1 && (size_t)KS * NG * 8 * kWideTok * 256 <= kSplitKFloats) {
+            // (longer passes -- prefill, teacher-forced scoring -- take one launch pair per sweep)
+            if (KS > 1 && (size_t)KS * NG * 8 * kWideTok * 256 <= kSplitKFloats) {
                 a.KS = KS; a.sk_part = h->sk_part;
                 for (a.tb_base = 0; a.tb_base < TB; a.tb_base += kWideTok) {
                     hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, true>), dim3(NG * KS), dim3(256), 0, h->stream, a);
