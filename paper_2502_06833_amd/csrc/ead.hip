@@ -442,25 +442,32 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
     int cfg = !big ? 1 : (NB >= 4 * 256 ? 4 : 2);       // 1: (4 waves, R=1)  4: (4, R=4)  2: (8 waves, R=2)  5: (4, R=4, split K)
     int grid = (NB + cfg - 1) / cfg;
     if constexpr (EPI != EPI_LOGITS) {
-        // more than 64 rows: 128 rows per sweep, weight tiles shared through LDS.  Matrices with few
-        // row blocks are split along K over workgroups when one sweep covers the pass; a second
-        // kernel adds the slabs in order and runs the epilogue.
-        if (big && TB > 4) {
-            const int NG = (NB + 7) / 8;
+        // more than 32 rows: 64 or 128 rows per sweep, weight tiles shared through LDS.  Matrices with few
+        // row blocks are split along K over workgroups; a second kernel adds the slabs in order and
+        // runs the epilogue.  Longer passes (prefill, teacher-forced scoring) take one launch pair per
+        // sweep, or one workgroup per (group, sweep) where K is not split.
+        // (the QKV projection of 33-64 rows stays with the 64-row kernel below: 37 against 42 us)
+        if (big && TB > 2 && !(EPI == EPI_QKV && TB <= 4)) {
+            const int NG = (NB + 7) / 8, nt = TB > 4 ? kWideTok : 4;
             if (cfg == 4 && EPI != EPI_QKV) {
-                a.sweeps = (TB + kWideTok - 1) / kWideTok;
+                a.sweeps = (TB + nt - 1) / nt;
                 const int grid_wt = a.sweeps > 1 ? (NG + 7) / 8 * 8 * a.sweeps : NG;
-                hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false>), dim3(grid_wt), dim3(256), 0, h->stream, a);
+                if (nt == 4) hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, 1>), dim3(grid_wt), dim3(256), 0, h->stream, a);
+                else hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, 2>), dim3(grid_wt), dim3(256), 0, h->stream, a);
                 return;
             }
             int KS = std::min(kSplitKMax, std::max(1, (h->n_cu + NG / 2) / NG));
             while (KS > 1 && (a.K / 32) / KS < 16) --KS;
-            // (longer passes -- prefill, teacher-forced scoring -- take one launch pair per sweep)
-            if (KS > 1 && (size_t)KS * NG * 8 * kWideTok * 256 <= kSplitKFloats) {
+            if (KS > 1 && (size_t)KS * NG * 8 * nt * 256 <= kSplitKFloats) {
                 a.KS = KS; a.sk_part = h->sk_part;
-                for (a.tb_base = 0; a.tb_base < TB; a.tb_base += kWideTok) {
-                    hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, true>), dim3(NG * KS), dim3(256), 0, h->stream, a);
-                    hipLaunchKernelGGL((k_sk_merge<EPI>), dim3((NB * kWideTok + 3) / 4), dim3(256), 0, h->stream, a, NG * 8);
+                for (a.tb_base = 0; a.tb_base < TB; a.tb_base += nt) {
+                    if (nt == 4) {
+                        hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, true, 1>), dim3(NG * KS), dim3(256), 0, h->stream, a);
+                        hipLaunchKernelGGL((k_sk_merge<EPI, 4>), dim3((NB * 4 + 3) / 4), dim3(256), 0, h->stream, a, NG * 8);
+                    } else {
+                        hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, true, 2>), dim3(NG * KS), dim3(256), 0, h->stream, a);
+                        hipLaunchKernelGGL((k_sk_merge<EPI, kWideTok>), dim3((NB * kWideTok + 3) / 4), dim3(256), 0, h->stream, a, NG * 8);
+                    }
                 }
                 return;
             }

@@ -531,16 +531,16 @@ __device__ __forceinline__ void block_epilogue(const LinArgs<bf16_t> &a, float (
 
 constexpr int kWideTok = 8;          // token blocks (of 16 rows) per sweep
 
-// Passes of more than 64 rows: a workgroup takes 8 row blocks and 128 token rows per sweep; each of
-// its four waves owns two token blocks and all 8 row blocks.  A wave's activation fragments (hi and lo
+// Passes of more than 32 rows: a workgroup takes 8 row blocks and 64 TPW token rows per sweep; each of
+// its four waves owns TPW (1 or 2) token blocks and all 8 row blocks.  A wave's activation fragments (hi and lo
 // of its two blocks) come straight from memory in the matrix cores' operand layout and are never
 // shared; the step's 8 weight tiles, of which each wave fetches two, go through LDS (8 KB read per
 // wave and step; sharing the activation tiles instead, with a row-block pair per wave, reads 16 KB
 // and is no faster).  SK: workgroup (g, ks) takes slab ks of K for group g (one sweep only: TB <= 8)
 // and leaves its sums in memory for k_sk_merge.
-template <int DA, int EPI, bool SK = false>
+template <int DA, int EPI, bool SK = false, int TPW = 2>
 __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
-    constexpr int NT = kWideTok, RG = 8;               // token blocks per sweep, row blocks per workgroup
+    constexpr int NT = 4 * TPW, RG = 8;                // token blocks per sweep (TPW per wave), row blocks per workgroup
     __shared__ __attribute__((aligned(16))) bf16_t s_w[2][RG][512];
     __shared__ __attribute__((aligned(16))) float s_t[4][64][4];
     const int K = a.K, KCfull = K >> 5, NB = a.Np >> 4, NG = (NB + RG - 1) / RG;
@@ -563,24 +563,28 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
     const int kbase = (ks * KCfull) / KS, KC = ((ks + 1) * KCfull) / KS - kbase;     // this workgroup's k tiles
 
     for (int tb0 = tb_first; tb0 < TB; tb0 += one_sweep ? TB : NT) {
-        f32x4_t acc[RG][2];
-        const bf16_t *wp[2], *bp[4];
+        f32x4_t acc[RG][TPW];
+        const bf16_t *wp[2], *bp[2 * TPW];
 #pragma unroll
-        for (int j = 0; j < RG; ++j) acc[j][0] = acc[j][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < RG; ++j)
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+            for (int q = 0; q < TPW; ++q) acc[j][q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
             wp[q] = a.W + tile_offset(min(g * RG + wave * 2 + q, NB - 1), kbase, KCfull) + lane * 8;
-            const int blk = min(tb0 + wave * 2 + q, TB - 1);
+#pragma unroll
+        for (int q = 0; q < TPW; ++q) {
+            const int blk = min(tb0 + wave * TPW + q, TB - 1);
             bp[q] = a.xp_lo + act_tile_offset(blk, kbase, TB) + lane * 8;          // lo of block q, then hi
-            bp[2 + q] = a.xp + act_tile_offset(blk, kbase, TB) + lane * 8;
+            bp[TPW + q] = a.xp + act_tile_offset(blk, kbase, TB) + lane * 8;
         }
-        Vec8<bf16_t> wa[DA][2], ba[DA][4];
+        Vec8<bf16_t> wa[DA][2], ba[DA][2 * TPW];
         auto issue = [&](int s, int i) __attribute__((always_inline)) {
             const size_t off = (size_t)min(i, KC - 1) * 512;
 #pragma unroll
             for (int q = 0; q < 2; ++q) wa[s][q].load_stream(wp[q] + off);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) ba[s][q].load(bp[q] + off * TB);
+            for (int q = 0; q < 2 * TPW; ++q) ba[s][q].load(bp[q] + off * TB);
         };
 #pragma unroll
         for (int s = 0; s < DA; ++s) {
@@ -608,9 +612,9 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
 #pragma unroll
                         for (int j = 0; j < RG; ++j)
 #pragma unroll
-                            for (int q = 0; q < 2; ++q)
+                            for (int q = 0; q < TPW; ++q)
                                 acc[j][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    __builtin_bit_cast(bf16x8_t, fw[j]), __builtin_bit_cast(bf16x8_t, ba[s][h * 2 + q].raw), acc[j][q], 0, 0, 0);
+                                    __builtin_bit_cast(bf16x8_t, fw[j]), __builtin_bit_cast(bf16x8_t, ba[s][h * TPW + q].raw), acc[j][q], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 issue(s, i + DA);
@@ -621,8 +625,8 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
 #pragma unroll
             for (int j = 0; j < RG; ++j)
 #pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    const int rb = g * RG + j, tb = tb0 + wave * 2 + q;
+                for (int q = 0; q < TPW; ++q) {
+                    const int rb = g * RG + j, tb = tb0 + wave * TPW + q;
                     block_epilogue<EPI>(a, s_t[wave], rb, tb, acc[j][q], rb < NB && tb < TB, T, lane);
                 }
         } else {
@@ -630,8 +634,8 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
 #pragma unroll
             for (int j = 0; j < RG; ++j)
 #pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    const int rb = g * RG + j, b = wave * 2 + q;
+                for (int q = 0; q < TPW; ++q) {
+                    const int rb = g * RG + j, b = wave * TPW + q;
                     if (rb < NB && tb0 + b < TB) {
                         float *dst = a.sk_part + (size_t)ks * slab + ((size_t)rb * NT + b) * 256 + lane;
                         st_coherent(dst, acc[j][q][0]); st_coherent(dst + 64, acc[j][q][1]);
@@ -643,11 +647,10 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
     }
 }
 
-// Sum of the K slabs that k_linear_mfma_wt<..., SK = true> left in memory, in slab order, then
-// the epilogue.  One wave per 16 x 16 block; grid = ceil(row blocks * kWideTok / 4) workgroups.
-template <int EPI>
+// Sum of the K slabs that k_linear_mfma_wt<..., SK = true, TPW> left in memory, in slab order, then
+// the epilogue.  One wave per 16 x 16 block; grid = ceil(row blocks * NT / 4) workgroups, NT = 4 TPW.
+template <int EPI, int NT = kWideTok>
 __global__ __launch_bounds__(256) void k_sk_merge(LinArgs<bf16_t> a, int NGR /* row blocks incl. padding */) {
-    constexpr int NT = kWideTok;
     __shared__ __attribute__((aligned(16))) float s_t[4][64][4];
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int NB = a.Np >> 4, T = *a.count, TB = (T + 15) >> 4, KS = a.KS;
