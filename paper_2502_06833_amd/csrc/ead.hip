@@ -419,16 +419,18 @@ void launch_valu(ead_handle *h, int mi, LinArgs<WT> &a, int T, int grid) {
 #undef EAD_LV
 }
 
-// T: the host's count of token rows.  The shape of the matrix alone picks the workgroup:
-//  * many row blocks: four waves, four row blocks each (an activation tile is fetched once
-//    for four weight tiles);
-//  * few row blocks but a large matrix (long K): the same, with K split over KS workgroups
-//    per group so that the chip still gets about two workgroups per compute unit; passes of
-//    more than 64 rows (prefill) are bound by the matrix cores instead and take eight waves
-//    that split K inside one workgroup of two row blocks;
+// T: the host's count of token rows.  The shape of the matrix and ceil(T / 16) pick the kernel:
+//  * large matrices, more than 32 rows (QKV: more than 64): k_linear_mfma_wt, 64 or 128 rows per
+//    sweep, eight row blocks per workgroup; where that gives fewer workgroups than compute units,
+//    K is split over workgroups and k_sk_merge adds the slabs;
+//  * large matrices, up to 32 rows (QKV up to 64), and the LM head: k_linear_mfma with four waves
+//    of four row blocks each (an activation tile is fetched once for four weight tiles) where
+//    there are many row blocks, else with K split over KS workgroups per group of four row blocks
+//    so that the chip still gets about two workgroups per compute unit (the last to arrive adds
+//    the slabs), or eight waves that split K inside a workgroup of two row blocks (QKV);
 //  * small matrices are latency-bound: one row block per four-wave workgroup, as many
 //    workgroups as possible.
-// NT token blocks per pass follow T; the ring depth D follows the register budget.
+// NT token blocks per sweep follow T; the ring depth D follows the register budget.
 constexpr float kSmallLaneMin = 0.3f;                  // grouped schedule, two lanes: see decode_grouped
 constexpr int kSplitKGroups = 4096;                     // arrival counters
 constexpr size_t kSplitKFloats = (size_t)8 << 20;      // partial sums: KS slabs of (padded Np) x 128 floats at most
