@@ -956,6 +956,7 @@ ead_status decode_grouped(ead_handle *h, int n_tokens) {
         // their switch.  The large lane still waits until enough rows have gathered.
         std::vector<char> em[2] = {std::vector<char>(h->batch), std::vector<char>(h->batch)};
         bool busy[2] = {false, false};
+        int small_held = 0;                           // times in a row the small lane was held back while it had rows
         for (;;) {
             int n[2];
             waiting(n);                               // rows of a busy lane count as waiting for it: they are in its pass
@@ -972,7 +973,13 @@ ead_status decode_grouped(ead_handle *h, int n_tokens) {
                 // a small pass costs the same 170 launches for 5 rows as for 50 and slows the
                 // large pass beside it: while the large lane is busy the small lane waits until
                 // kSmallLaneMin of the unfinished rows are ready for it
-                if (m == 0 && busy[1] && (float)n[0] < kSmallLaneMin * (float)N) continue;
+                // (for at most two large passes in a row, so that a few small-model rows are not left
+                // behind while the large lane serves burst after burst)
+                if (m == 0 && busy[1] && (float)n[0] < kSmallLaneMin * (float)N && small_held < 2) {
+                    ++small_held;
+                    continue;
+                }
+                if (m == 0) small_held = 0;
                 use_lane(h, m);
                 std::fill(em[m].begin(), em[m].end(), 0);
                 int T = 0;
