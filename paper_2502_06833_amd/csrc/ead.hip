@@ -448,8 +448,7 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
         // row blocks are split along K over workgroups; a second kernel adds the slabs in order and
         // runs the epilogue.  Longer passes (prefill, teacher-forced scoring) take one launch pair per
         // sweep, or one workgroup per (group, sweep) where K is not split.
-        // (the QKV projection of 33-64 rows stays with the 64-row kernel below: 37 against 42 us)
-        if (big && TB > 2 && !(EPI == EPI_QKV && TB <= 4)) {
+        if (big && TB > 2) {
             const int NG = (NB + 7) / 8, nt = TB > 4 ? kWideTok : 4;
             if (cfg == 4 && EPI != EPI_QKV) {
                 a.sweeps = (TB + nt - 1) / nt;
@@ -458,7 +457,8 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
                 else hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, 2>), dim3(grid_wt), dim3(256), 0, h->stream, a);
                 return;
             }
-            int KS = std::min(kSplitKMax, std::max(1, (h->n_cu + NG / 2) / NG));
+            // one workgroup per compute unit at most: a second round would double the time
+            int KS = std::min(kSplitKMax, std::max(1, h->n_cu / NG));
             while (KS > 1 && (a.K / 32) / KS < 16) --KS;
             if (KS > 1 && (size_t)KS * NG * 8 * nt * 256 <= kSplitKFloats) {
                 a.KS = KS; a.sk_part = h->sk_part;
