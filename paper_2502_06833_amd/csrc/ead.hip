@@ -451,10 +451,15 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
         if (big && TB > 2) {
             const int NG = (NB + 7) / 8, nt = TB > 4 ? kWideTok : 4;
             if (cfg == 4 && EPI != EPI_QKV) {
+                // seven row blocks per workgroup where that still fits one workgroup per compute unit
+                // (1728 row blocks: 247 workgroups instead of 216 on 256 units)
+                const int rg = (NB + 6) / 7 <= h->n_cu ? 7 : 8, ng = (NB + rg - 1) / rg;
                 a.sweeps = (TB + nt - 1) / nt;
-                const int grid_wt = a.sweeps > 1 ? (NG + 7) / 8 * 8 * a.sweeps : NG;
-                if (nt == 4) hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, 1>), dim3(grid_wt), dim3(256), 0, h->stream, a);
-                else hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, 2>), dim3(grid_wt), dim3(256), 0, h->stream, a);
+                const int grid_wt = a.sweeps > 1 ? (ng + 7) / 8 * 8 * a.sweeps : ng;
+#define EAD_WT(TPW_, RG_) hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, TPW_, RG_>), dim3(grid_wt), dim3(256), 0, h->stream, a)
+                if (nt == 4) { if (rg == 7) EAD_WT(1, 7); else EAD_WT(1, 8); }
+                else { if (rg == 7) EAD_WT(2, 7); else EAD_WT(2, 8); }
+#undef EAD_WT
                 return;
             }
             // one workgroup per compute unit at most: a second round would double the time

@@ -531,17 +531,19 @@ __device__ __forceinline__ void block_epilogue(const LinArgs<bf16_t> &a, float (
 
 constexpr int kWideTok = 8;          // token blocks (of 16 rows) per sweep
 
-// Passes of more than 32 rows: a workgroup takes 8 row blocks and 64 TPW token rows per sweep; each of
-// its four waves owns TPW (1 or 2) token blocks and all 8 row blocks.  A wave's activation fragments (hi and lo
+// Passes of more than 32 rows: a workgroup takes RG (8; 7 where that fills the compute units better)
+// row blocks and 64 TPW token rows per sweep; each of its four waves owns TPW (1 or 2) token blocks
+// and all RG row blocks.  A wave's activation fragments (hi and lo
 // of its two blocks) come straight from memory in the matrix cores' operand layout and are never
 // shared; the step's 8 weight tiles, of which each wave fetches two, go through LDS (8 KB read per
 // wave and step; sharing the activation tiles instead, with a row-block pair per wave, reads 16 KB
 // and is no faster).  SK: workgroup (g, ks) takes slab ks of K for group g (one sweep only: TB <= 8)
 // and leaves its sums in memory for k_sk_merge.
-template <int DA, int EPI, bool SK = false, int TPW = 2>
+template <int DA, int EPI, bool SK = false, int TPW = 2, int RG = 8>
 __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
-    constexpr int NT = 4 * TPW, RG = 8;                // token blocks per sweep (TPW per wave), row blocks per workgroup
-    __shared__ __attribute__((aligned(16))) bf16_t s_w[2][RG][512];
+    static_assert(RG >= 5 && RG <= 8, "each wave fetches two of the workgroup's weight tiles");
+    constexpr int NT = 4 * TPW;                        // token blocks per sweep (TPW per wave); RG row blocks per workgroup
+    __shared__ __attribute__((aligned(16))) bf16_t s_w[2][8][512];
     __shared__ __attribute__((aligned(16))) float s_t[4][64][4];
     const int K = a.K, KCfull = K >> 5, NB = a.Np >> 4, NG = (NB + RG - 1) / RG;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -571,7 +573,7 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
             for (int q = 0; q < TPW; ++q) acc[j][q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int q = 0; q < 2; ++q)
-            wp[q] = a.W + tile_offset(min(g * RG + wave * 2 + q, NB - 1), kbase, KCfull) + lane * 8;
+            wp[q] = a.W + tile_offset(min(g * RG + min(wave * 2 + q, RG - 1), NB - 1), kbase, KCfull) + lane * 8;   // RG < 8: the last tile twice
 #pragma unroll
         for (int q = 0; q < TPW; ++q) {
             const int blk = min(tb0 + wave * TPW + q, TB - 1);
