@@ -420,10 +420,10 @@ void launch_valu(ead_handle *h, int mi, LinArgs<WT> &a, int T, int grid) {
 }
 
 // T: the host's count of token rows.  The shape of the matrix and ceil(T / 16) pick the kernel:
-//  * large matrices, more than 32 rows (QKV: more than 64): k_linear_mfma_wt, 64 or 128 rows per
+//  * large matrices, more than 32 rows (QKV and residual projections: more than 16): k_linear_mfma_wt, 64 or 128 rows per
 //    sweep, eight row blocks per workgroup; where that gives fewer workgroups than compute units,
 //    K is split over workgroups and k_sk_merge adds the slabs;
-//  * large matrices, up to 32 rows (QKV up to 64), and the LM head: k_linear_mfma with four waves
+//  * large matrices at fewer rows, and the LM head: k_linear_mfma with four waves
 //    of four row blocks each (an activation tile is fetched once for four weight tiles) where
 //    there are many row blocks, else with K split over KS workgroups per group of four row blocks
 //    so that the chip still gets about two workgroups per compute unit (the last to arrive adds
@@ -448,7 +448,8 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
         // row blocks are split along K over workgroups; a second kernel adds the slabs in order and
         // runs the epilogue.  Longer passes (prefill, teacher-forced scoring) take one launch pair per
         // sweep, or one workgroup per (group, sweep) where K is not split.
-        if (big && TB > 2) {
+        // (17-32 rows: measured better for the split-K matrices, 32 against 34 us, not for gate/up, 72 against 69)
+        if (big && (TB > 2 || (TB == 2 && EPI != EPI_SWIGLU))) {
             const int NG = (NB + 7) / 8, nt = TB > 4 ? kWideTok : 4;
             if (cfg == 4 && EPI != EPI_QKV) {
                 // seven row blocks per workgroup where that still fits one workgroup per compute unit
