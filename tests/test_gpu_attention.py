@@ -74,3 +74,23 @@ def test_catchups_over_several_key_splits_against_oracle(att):
         assert (rp["next_model"][b][safe] == want_next[safe]).all()
     st = e.stats()
     assert st["catchup_rows_large"] >= 16
+
+
+@pytest.mark.parametrize("heads,kv_heads", [(4, 4), (8, 1), (16, 2)])
+def test_head_layouts_at_the_ends_of_the_range(heads, kv_heads):
+    """G = 1 (16 rows of a sequence per pass over its K/V), G = 8 (2 rows), and G = 8
+    with two KV heads at 16 query heads: 300 teacher-forced positions against the oracle."""
+    import paper_2502_06833_amd as ead
+    shape = si.ModelShape(f"att-{heads}-{kv_heads}", 2, 32 * heads, heads, kv_heads, 256, 512, 1e-5, 1e4, bf16=True)
+    W = si.model_weights_torch(shape, 1, "cuda", 0.05)
+    om = oracle.Model(shape, {k: v.float().cpu().numpy() for k, v in W.items()})
+    e = ead.EAD(shape, W, shape, W, window=5, tau=0.0, d_min=4, max_batch=1, max_seq=320)
+    toks = si.prompt_np(5, shape.name, 300, shape.vocab)
+    ref = om.forward_dense(toks)
+    out = e.score(1, toks)
+    err = np.abs(out["logits"] - ref).max(axis=1) / np.abs(ref).max(axis=1)
+    Hr, _ = oracle.entropy_rows(ref)
+    print(f"{shape.name}: logits rel err {err.max():.2e}, H err {np.abs(out['H'] - Hr).max():.2e}", flush=True)
+    assert err.max() < TOL_LOGIT
+    assert np.abs(out["H"] - Hr).max() < TOL_H
+    e.close()
