@@ -26,7 +26,7 @@ import synth_inputs as si
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="llama_1b_8b_b1",
-                    choices=sorted(k for k, v in bench.WORKLOADS.items() if v[0] is not None))
+                    choices=sorted(k for k, v in bench.WORKLOADS.items() if v[0] is not None and not k.startswith("prefill_")))
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--seed", type=int, default=0)
