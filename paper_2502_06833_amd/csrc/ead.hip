@@ -689,6 +689,7 @@ FinArgs make_fin(ead_handle *h, int m, bool score) {
     fa.model_id = m; fa.max_new = h->max_new; fa.eos_id = h->prm.eos_id; fa.replay = h->replay; fa.n_new = h->n_new;
     fa.force_model = h->force_model; fa.step = h->step;
     fa.sampling = (!score && h->samp_temp > 0.f) ? 1 : 0;
+    fa.host_model = h->lanes[0].rb_model; fa.host_done = h->lanes[0].rb_done;      // one array for both lanes: entries are per sequence
     return fa;
 }
 
@@ -871,7 +872,7 @@ ead_status decode_pass(ead_handle *h, int m, int step, std::vector<char> &emitte
 ead_status after_tokens(ead_handle *h, const std::vector<char> &emitted, bool all_lanes) {
     LaneSet &ln = h->lanes[h->cur_lane];
     hipStream_t st = ln.stream;
-    int *rb_model = ln.rb_model, *rb_done = ln.rb_done;
+    int *rb_model = h->lanes[0].rb_model, *rb_done = h->lanes[0].rb_done;
     bool need_sync = h->prm.eos_id >= 0;
     for (int b = 0; b < h->batch; ++b) {
         if (!emitted[b]) continue;
@@ -891,9 +892,7 @@ ead_status after_tokens(ead_handle *h, const std::vector<char> &emitted, bool al
         }
     } else if (need_sync && h->force_model < 0) {
         if (all_lanes && h->two_lanes) HIP_TRY(h, hipStreamSynchronize(h->lanes[1 - h->cur_lane].stream));
-        HIP_TRY(h, hipMemcpyAsync(rb_model, h->s.model, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
-        HIP_TRY(h, hipMemcpyAsync(rb_done, h->s.done, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
-        HIP_TRY(h, hipStreamSynchronize(st));
+        HIP_TRY(h, hipStreamSynchronize(st));      // the pass's last kernel wrote rb_model / rb_done (pinned) itself
         h->stats.host_syncs++;
         for (int b = 0; b < h->batch; ++b) {
             HostSeq &s = h->hs[b];
@@ -903,7 +902,6 @@ ead_status after_tokens(ead_handle *h, const std::vector<char> &emitted, bool al
         }
     } else if (need_sync) {
         if (all_lanes && h->two_lanes) HIP_TRY(h, hipStreamSynchronize(h->lanes[1 - h->cur_lane].stream));
-        HIP_TRY(h, hipMemcpyAsync(rb_done, h->s.done, h->batch * sizeof(int), hipMemcpyDeviceToHost, st));
         HIP_TRY(h, hipStreamSynchronize(st));
         for (int b = 0; b < h->batch; ++b) if (emitted[b] && rb_done[b]) h->hs[b].done = 1;
     }

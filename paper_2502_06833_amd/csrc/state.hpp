@@ -27,6 +27,7 @@ struct FinArgs {
     int score_mode; float *sc_H; int *sc_arg;      // score: indexed by position
     int model_id, max_new, eos_id, replay, n_new, force_model, step;
     int sampling;            // 1: the token is the sampled one (st.gidx), else the arg max
+    int *host_model, *host_done;   // pinned host memory, [max_batch]: next model and done flag of the sequences this pass finalizes
 };
 
 // Algorithm 1's bookkeeping for sequence b once the entropy statistics of its logits are
@@ -51,8 +52,11 @@ __device__ __forceinline__ void lm_finalize_seq(const FinArgs &a, int b, const E
     const int L = a.s.len[b];
     a.s.tokens[(size_t)b * a.s.max_seq + L] = tok;
     a.s.len[b] = L + 1; a.s.ngen[b] = n + 1;
-    a.s.done[b] = (n + 1 >= a.max_new) || (a.eos_id >= 0 && tok == a.eos_id);
+    const int done = (n + 1 >= a.max_new) || (a.eos_id >= 0 && tok == a.eos_id);
+    a.s.done[b] = done;
     a.s.model[b] = next; a.s.c[b] = c; a.s.last_step[b] = a.step;
+    // what the host's mirror needs after the pass, written where it can read it without a copy
+    if (a.host_model) { a.host_model[b] = next; a.host_done[b] = done; }
     if (!isfinite(H)) atomicOr(a.s.err, 1);
 }
 
