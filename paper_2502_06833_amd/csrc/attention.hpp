@@ -51,8 +51,9 @@ __device__ __forceinline__ void attn_store(float *out, bf16_t *out_tiles, bf16_t
 // The waves take the split's keys in chunks of NI * (64 / LPK).  Two register sets
 // alternate: the next chunk's K and V are requested before the current one is worked on.
 // Scores of a chunk are formed, one rescale is applied per chunk and then the values are
-// accumulated.  The waves meet in LDS.  With a single split (the usual case: the host makes
-// a split cover at least 512 keys) the workgroup normalises and writes the output.
+// accumulated.  The waves meet in LDS.  With a single split (short contexts; the host makes a
+// split cover 128 keys for steps of one or two rows, else at least 512) the workgroup normalises
+// and writes the output.
 // Otherwise it leaves an un-normalised partial, written through to memory (st_coherent),
 // and the workgroup that arrives last (ticket counter per (row, head group)) merges the
 // partials with coherent loads, so neither a second launch nor a cache write-back /
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void k_attn(AttnArgs<KT> a) {
     static_assert(GW == G || GW == 1, "a workgroup takes all query heads of a KV head, or one");
     constexpr int LPK = HD / 8;        // lanes per key
     constexpr int KPI = 64 / LPK;      // keys per load instruction
-    constexpr int NI = (GW == 1 && sizeof(KT) == 2) ? 8 : 4;   // load instructions per chunk
+    constexpr int NI = 4;              // load instructions per chunk
     constexpr int CH = NI * KPI;
     __shared__ float s_o[kAttnWaves][GW][HD];
     __shared__ float s_m[kAttnWaves][GW], s_l[kAttnWaves][GW];

@@ -507,7 +507,7 @@ template <typename KT, int HD>
 void launch_attn(ead_handle *h, int mi, AttnArgs<KT> &a, int G, int T, double kv_bytes) {
     // few rows: one workgroup per query head (latency-bound, wants the lanes); many rows:
     // one per KV head, so K and V are streamed once for the heads that share them
-    const bool per_head = (long)T * a.n_kv_heads * a.max_splits <= 64;
+    const bool per_head = T <= 2 || (long)T * a.n_kv_heads * a.max_splits <= 64;
     dim3 grid(a.max_splits, per_head ? a.n_heads : a.n_kv_heads, T);
     if constexpr (std::is_same<KT, bf16_t>::value) {
         // many rows: scores and weighted sums on the matrix cores, rows of one sequence grouped
@@ -547,16 +547,17 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
                            h->plan.row_pos, h->s.max_seq, d, h->x);
     }
     const double attn_bytes = keys_read * 2.0 * NK * sizeof(WT);
-    // attention split: enough waves to fill the chip, bounded scratch
     // attention split: a workgroup (8 waves) takes at least 512 keys; more splits only while
-    // that helps to fill the chip, never more than 16 (the last one merges them all)
-    int chunk = 512;
+    // that helps to fill the chip, never more than 16 (the last one merges them all), bounded scratch
+    // (a decode step of one or two rows is a chain of latencies: splits of 128 keys, one workgroup per
+    // query head and split, spread it over more compute units: +3 % tokens/s at batch 1 against 512)
+    int chunk = T <= 2 ? 128 : 512;
     while ((long)T * m.KV * ((ctx_max + chunk - 1) / chunk) > 1024 && chunk < 65536) chunk <<= 1;
     while ((ctx_max + chunk - 1) / chunk > kAttnMaxSplits) chunk <<= 1;
     while ((long)T * ((ctx_max + chunk - 1) / chunk) > h->items_max) chunk <<= 1;
     // the matrix-core kernel (many rows) is bound by the latency of its short chains of loads, one
     // workgroup per compute unit at a time: fewer, longer workgroups
-    if (is_bf16 && m.layers[0].vtcache && (long)T * m.KV * ((ctx_max + chunk - 1) / chunk) > 64)
+    if (is_bf16 && m.layers[0].vtcache && T > 2 && (long)T * m.KV * ((ctx_max + chunk - 1) / chunk) > 64)
         while ((long)T * m.KV * ((ctx_max + chunk - 1) / chunk) > 2 * h->n_cu && chunk < 65536) chunk <<= 1;
     const int max_splits = (ctx_max + chunk - 1) / chunk;
 
