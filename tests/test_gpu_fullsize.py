@@ -191,3 +191,24 @@ def test_qwen_truncated_batch_with_ragged_prompts_and_catchups():
     lock_large, grouped_large = st["steps_large"], sg["steps_large"]
     print(f"large-model passes: lock step {lock_large}, grouped {grouped_large}", flush=True)
     e.close()
+
+
+def test_qwen_truncated_long_prefill_agrees_with_scoring():
+    """Qwen-shaped widths (2 layers each): a 600-token prompt is prefilled in one pass of 599 rows
+    (five 128-row sweeps per matrix, one launch pair per sweep where K is split, row groups of 2 and
+    3 in the attention); the entropies of the following tokens -- small model, then the large one
+    after a 10-row catch-up -- equal those of scoring the same tokens in passes of 160 rows."""
+    ead = _ead()
+    ss, sl = (s.truncated(2) for s in si.PAIRS["qwen"])
+    Ws = si.model_weights_torch(ss, 0, "cuda")
+    Wl = si.model_weights_torch(sl, 0, "cuda")
+    e = ead.EAD(ss, Ws, sl, Wl, window=5, tau=0.0, d_min=10, max_batch=1, max_seq=640)
+    prompt = si.prompt_np(4, "qlong", 600, ss.vocab)
+    out = e.generate([prompt], 14)
+    assert list(out["model_id"][0]) == [0] * 10 + [1] * 4
+    seq = np.concatenate([prompt, out["tokens"][0]])
+    for which, rng in ((0, range(0, 10)), (1, range(10, 14))):
+        sc = e.score(which, seq[:-1], want_logits=False)
+        for i in rng:
+            assert abs(sc["H"][600 + i - 1] - out["H"][0, i]) < TOL_H, (which, i)
+    e.close()
