@@ -29,20 +29,25 @@ import synth_inputs as si  # noqa: E402
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E peak
 
 WORKLOADS = {
-    # name: (pair, batch, prompt_lo, prompt_hi, default_steps, target_large_share, d_min)
-    "llama_1b_8b_b1": ("llama", 1, 512, 512, 1024, 0.40, 10),
-    "qwen_05b_14b_b32": ("qwen", 32, 256, 256, 256, 0.25, 10),
-    "qwen_05b_14b_b64": ("qwen", 64, 128, 1024, 128, 0.25, 10),
-    "tiny_fp32_b1": ("tiny", 1, 16, 16, 64, 0.40, 10),
+    # name: (pair, batch, prompt_lo, prompt_hi, default_steps, tau rule, d_min)
+    # tau rule ("share", x): bisection on calibration runs until about x of the tokens come from the
+    # large model; ("percentile", q): the q-th percentile of the small model's windowed entropy.
+    "llama_1b_8b_b1": ("llama", 1, 512, 512, 1024, ("share", 0.40), 10),
+    "qwen_05b_14b_b32": ("qwen", 32, 256, 256, 256, ("share", 0.25), 10),
+    "qwen_05b_14b_b64": ("qwen", 64, 128, 1024, 128, ("percentile", 75.0), 10),
+    "tiny_fp32_b1": ("tiny", 1, 16, 16, 64, ("share", 0.40), 10),
     # the paper's other pair shapes, batch 1
-    "llama_1b_3b_b1": ("llama_1b_3b", 1, 512, 512, 1024, 0.40, 10),
-    "qwen_15b_14b_b1": ("qwen_15b_14b", 1, 512, 512, 1024, 0.25, 10),
+    "llama_1b_3b_b1": ("llama_1b_3b", 1, 512, 512, 1024, ("share", 0.40), 10),
+    "qwen_15b_14b_b1": ("qwen_15b_14b", 1, 512, 512, 1024, ("share", 0.25), 10),
     # stand-alone entropy / arg-max / window / switch epilogue on materialised logits
     "entropy_gate_b64": (None, 64, 0, 0, 4096, None, 10),
     # prompt prefill of both models (the step before the decode path): steps = repetitions
     "prefill_qwen_b64": ("qwen", 64, 128, 1024, 4, None, 10),
     "prefill_llama_b8": ("llama", 8, 512, 512, 8, None, 10),
 }
+# The headline workload: the largest configuration that fits one GPU (Qwen-0.5B / Qwen-14B shapes, batch 64,
+# ragged prompts, every row its own instance of Algorithm 1), grouped two-lane schedule.
+DEFAULT_WORKLOAD = "qwen_05b_14b_b64"
 
 MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
@@ -56,19 +61,36 @@ def make_prompts(seed, batch, lo, hi, vocab):
     return [si.prompt_np(seed, f"row{b}", int(lens[b]), vocab) for b in range(batch)]
 
 
-def calibrate_tau(e, prompts, n_tokens, w, d_min, target):
-    """Bisection on free-running calibration runs: tau such that about `target` of the
-    tokens come from the large model (the percentile of the small model's windowed
-    entropy is only the starting bracket, because the window is shared across switches)."""
-    e.set_gate(w, 1e30, d_min)
-    probe = e.generate(prompts, n_tokens)
+def run_lengths(max_prompt, settle, warmup, steps, profile_steps, n_cal):
+    """Tokens every leg of a run generates per row, and the max_seq a handle needs to hold the longest
+    of them.  The profiling leg never runs longer than the timed one."""
+    profile_steps = max(1, min(profile_steps, steps))
+    timed_new = settle + warmup + steps
+    profile_new = settle + warmup + profile_steps
+    return {"timed_new": timed_new, "profile_new": profile_new, "profile_steps": profile_steps, "cal_new": n_cal,
+            "max_seq": max_prompt + max(timed_new, profile_new, n_cal) + 8}
+
+
+def calibrate_tau(e, rule, n_tokens, w, d_min):
+    """Threshold for the workload from free-running calibration runs on the prompts already in the caches.
+    ("percentile", q): q-th percentile of the small model's windowed entropy (one small-only run).
+    ("share", x): bisection until about x of the tokens come from the large model (the percentile is
+    only the starting bracket, because the window is shared across switches)."""
+    def run(tau):
+        e.set_gate(w, tau, d_min)
+        e.rewind(n_tokens)
+        e.decode(n_tokens)
+        return e.fetch()
+    probe = run(1e30)
     hb = probe["Hbar"].ravel()
+    if rule[0] == "percentile":
+        return float(np.percentile(hb, rule[1])), None
+    target = rule[1]
     lo, hi = float(hb.min()) - 1.0, float(hb.max()) + 1e-3
     best = (2.0, hi)
-    for _ in range(12):
+    for _ in range(10):
         tau = 0.5 * (lo + hi)
-        e.set_gate(w, tau, d_min)
-        share = float(e.generate(prompts, n_tokens)["model_id"].mean())
+        share = float(run(tau)["model_id"].mean())
         if abs(share - target) < abs(best[0] - target):
             best = (share, tau)
         if share > target:
@@ -80,40 +102,72 @@ def calibrate_tau(e, prompts, n_tokens, w, d_min, target):
     return best[1], best[0]
 
 
-def cpu_baseline(pair_shapes, Ws, Wl, prompts, w, tau, d_min):
-    """The oracle as it stands, timed on this host: Algorithm 1 on a bounded sample (first
-    row, prompt cut to 16 tokens, 24 generated tokens); prompt handling is subtracted by
-    timing a 1-token run."""
+def host_cpu():
+    """(model name, physical cores) of this host from /proc/cpuinfo; (None, None) where that is not readable."""
+    try:
+        txt = open("/proc/cpuinfo").read()
+    except OSError:
+        return None, None
+    name, cores, phys, core = None, set(), None, None
+    for line in txt.splitlines() + [""]:
+        k, _, v = line.partition(":")
+        k, v = k.strip(), v.strip()
+        if k == "model name" and name is None:
+            name = v
+        elif k == "physical id":
+            phys = v
+        elif k == "core id":
+            core = v
+        elif not line.strip():
+            if core is not None:
+                cores.add((phys, core))
+            phys = core = None
+    return name, (len(cores) or None)
+
+
+def cpu_baseline(pair_shapes, Ws, Wl, prompts, w, tau, d_min, n_prompt, n_new):
+    """The oracle as it stands, timed on this host: Algorithm 1 on a bounded sample (first row, prompt cut
+    to n_prompt tokens, n_new generated tokens after the first, same w / tau / d_min); prompt handling is
+    subtracted by timing a 1-token run first."""
     import oracle
     ss, sl = pair_shapes
     t0 = time.time()
     os_ = oracle.Model(ss, {k: v.float().cpu().numpy() for k, v in Ws.items()})
     ol = oracle.Model(sl, {k: v.float().cpu().numpy() for k, v in Wl.items()})
-    log(f"[cpu_baseline] weights on host in {time.time() - t0:.1f}s")
-    prompt = prompts[0][:16]
-    n = 24
+    log(f"[cpu_baseline] fp32 weights on the host in {time.time() - t0:.1f}s")
+    prompt = prompts[0][:n_prompt]
     t0 = time.time(); oracle.generate(os_, ol, prompt, 1, w, tau, d_min); t1 = time.time()
-    out = oracle.generate(os_, ol, prompt, n + 1, w, tau, d_min); t2 = time.time()
+    out = oracle.generate(os_, ol, prompt, n_new + 1, w, tau, d_min); t2 = time.time()
     dt = max((t2 - t1) - (t1 - t0), 1e-9)
-    return {"value": n / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"row 0, prompt cut to 16 tokens, {n} generated tokens after the first, batch 1, "
-                      f"same w/tau/d_min; large share in sample {float(out['model_id'][1:].mean()):.2f}"}
+    name, phys = host_cpu()
+    return {"value": n_new / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "cpu_model": name, "physical_cores_on_host": phys, "seconds": t2 - t0,
+            "sample": f"row 0, prompt cut to {len(prompt)} tokens, {n_new} generated tokens after the first, batch 1, "
+                      f"same w/tau/d_min; large-model share of the sample's tokens {float(out['model_id'][1:].mean()):.2f} "
+                      f"(a switch makes the large model consume every earlier token first)"}
 
 
 def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 counter runs, or None when
     there is none for this workload/kernel or the kernel sources changed since it was taken."""
-    import hashlib
     path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
     if not os.path.exists(path):
         return None
     rec = json.load(open(path))
-    h = hashlib.sha256()
-    for f in ("common.hpp", "linear.hpp"):
-        h.update(open(os.path.join(ROOT, "paper_2502_06833_amd", "csrc", f), "rb").read())
-    if rec.get("kernel") != kernel or rec.get("kernel_source_sha256_16") != h.hexdigest()[:16]:
+    if rec.get("kernel") != kernel or rec.get("kernel_source_sha256_16") != kernel_source_hash():
         return None
     return rec["traffic_bytes_per_launch"]
+
+
+def kernel_source_hash():
+    """Hash of every source file the library's kernels are compiled from."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_2502_06833_amd", "csrc")
+    h = hashlib.sha256()
+    for f in sorted(os.listdir(csrc)):
+        if f.endswith((".hpp", ".hip")):
+            h.update(open(os.path.join(csrc, f), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def linear_params(shape):
@@ -218,26 +272,49 @@ def bench_entropy_gate(args):
     print(json.dumps(out), flush=True)
 
 
+def build_probe():
+    """Compile roofline_probe.hip (beside this file): a torch-free driver of the library's C ABI for
+    hardware-counter runs (`rocprofv3 --pmc ... -- ./roofline_probe ...`)."""
+    import subprocess
+    from paper_2502_06833_amd import build as lib_build
+    lib_build.build(force=False)
+    libdir = os.path.join(ROOT, "paper_2502_06833_amd")
+    exe = os.path.join(ROOT, "roofline_probe")
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O2", "-std=c++17", "-o", exe, os.path.join(ROOT, "roofline_probe.hip"),
+           "-L" + libdir, "-lead", "-Wl,-rpath," + libdir]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + r.stderr)
+    return exe
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=16)
-    ap.add_argument("--workload", default="llama_1b_8b_b1", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--settle", type=int, default=32,
+                    help="untimed decode steps before the warm-up steps, so that the timed steps see rows on both models, "
+                         "pending catch-ups and contexts past the prompts (as prompt prefill, outside the timed region)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-single-model", action="store_true", help="skip the small-only / large-only runs")
-    ap.add_argument("--profile-steps", type=int, default=64)
+    ap.add_argument("--profile-steps", type=int, default=64, help="steps of the per-kernel timing leg (never more than --steps)")
     ap.add_argument("--fused", type=int, default=None, help="1/0: force the fused single-row decode kernel on/off")
     ap.add_argument("--tau", type=float, default=None, help="skip the calibration runs and use this threshold (nats)")
-    ap.add_argument("--schedule", choices=["lockstep", "grouped"], default="lockstep",
-                    help="grouped: small-model rows run ahead, large-model rows are served together")
+    ap.add_argument("--schedule", choices=["lockstep", "grouped"], default=None,
+                    help="grouped (default for batches): small-model rows run ahead, large-model rows are served together")
     ap.add_argument("--sched-start", type=float, default=0.5, help="grouped: large model starts at this share of waiting rows")
     ap.add_argument("--sched-stop", type=float, default=0.25, help="grouped: ... and stops below this share")
     ap.add_argument("--temperature", type=float, default=0.0, help="sample at this temperature (0 = greedy, the default)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for hardware byte counters)")
+    ap.add_argument("--build-probe", action="store_true", help="compile roofline_probe.hip and exit")
     args = ap.parse_args()
+    if args.build_probe:
+        print(build_probe())
+        return 0
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (sequences are independent, so more GPUs "
                  "would each run this same program on their share of the batch); use --gpus 1")
@@ -250,9 +327,11 @@ def main():
         return bench_entropy_gate(args)
     if args.workload.startswith("prefill_"):
         return bench_prefill(args)
-    pair, batch, plo, phi, dsteps, target, d_min = WORKLOADS[args.workload]
+    pair, batch, plo, phi, dsteps, rule, d_min = WORKLOADS[args.workload]
     steps = args.steps or dsteps
-    warmup = args.warmup
+    warmup, settle = args.warmup, max(args.settle, 0)
+    schedule = args.schedule or ("grouped" if batch > 1 else "lockstep")
+    grouped = schedule == "grouped"
     w = 5
     ss, sl = si.PAIRS[pair]
     t0 = time.time()
@@ -261,8 +340,9 @@ def main():
     torch.cuda.synchronize()
     log(f"[bench] weights generated in {time.time() - t0:.1f}s")
     prompts = make_prompts(args.seed, batch, plo, phi, ss.vocab)
-    max_seq = max(len(p) for p in prompts) + warmup + steps + 8
-    e = ead.EAD(ss, Ws, sl, Wl, window=w, tau=0.0, d_min=d_min, max_batch=batch, max_seq=max_seq)
+    n_cal = 64 if batch > 1 else 96
+    ln = run_lengths(max(len(p) for p in prompts), settle, warmup, steps, args.profile_steps, n_cal)
+    e = ead.EAD(ss, Ws, sl, Wl, window=w, tau=0.0, d_min=d_min, max_batch=batch, max_seq=ln["max_seq"])
     if args.no_cpu_baseline:
         del Ws, Wl
         torch.cuda.empty_cache()
@@ -278,20 +358,41 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    if args.tau is not None:
-        tau = args.tau
-        log(f"[bench] tau={tau:.6f} nats (given)")
-    else:
-        n_cal = min(256, warmup + steps)
-        tau, share_cal = calibrate_tau(e, prompts, n_cal, w, d_min, target)
-        log(f"[bench] tau={tau:.6f} nats -> large share {share_cal:.3f} over {n_cal} calibration tokens "
-            f"at {time.time() - t0:.1f}s")
 
-    def timed(force, grouped=False):
+    # prompt prefill of both models, once; every leg below starts over from this state (ead_rewind)
+    ta = time.perf_counter()
+    e.begin(prompts, ln["timed_new"])
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - ta
+    log(f"[bench] prompts prefilled ({sum(len(p) - 1 for p in prompts)} positions, both models) in {prefill_s:.2f}s")
+
+    out = {
+        "metric": "generated tokens/s at 1 GPU", "value": None, "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": None, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if ss.bf16 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "small": ss.name, "large": sl.name, "batch": batch,
+                   "prompt_len": [int(plo), int(phi)], "window": w, "d_min": d_min, "tau_nats": None, "tau_rule": list(rule),
+                   "vocab": ss.vocab, "schedule": schedule, "temperature": args.temperature, "settle_steps": settle},
+        "prefill_s": prefill_s, "roofline": None, "cpu_baseline": None,
+    }
+    errors = {}
+
+    def leg(name, fn):
+        """Run one leg; a failure is recorded and the other legs still run."""
+        try:
+            return fn()
+        except Exception as ex:  # noqa: BLE001
+            errors[name] = f"{type(ex).__name__}: {ex}"
+            log(f"[bench] leg '{name}' failed: {errors[name]}")
+            return None
+
+    def timed(force, grp):
         e.force_model(force)
-        e.set_schedule(grouped, args.sched_start, args.sched_stop)
+        e.set_schedule(grp, args.sched_start, args.sched_stop)
         e.set_gate(w, tau, d_min)
-        e.begin(prompts, warmup + steps)
+        e.rewind(ln["timed_new"])
+        if settle:
+            e.decode(settle)
         e.decode(warmup)
         e.reset_stats()
         torch.cuda.synchronize()
@@ -304,72 +405,99 @@ def main():
         e.set_schedule(False)
         return dt, st
 
-    grouped = args.schedule == "grouped"
-    dt, st = timed(-1, grouped)
-    n_tok = st["tokens_small"] + st["tokens_large"]
-    tok_s = n_tok / dt
-    algo_gbs = st["algorithmic_bytes"] / dt / 1e9
-    log(f"[bench] EAD: {tok_s:.1f} tok/s, {algo_gbs:.0f} GB/s algorithmic ({algo_gbs / HBM_PEAK_GBS:.1%} of peak), "
-        f"large share {st['large_share']:.3f}, switches {st['switches']}, host syncs {st['host_syncs']}")
-    extra = {}
-    if grouped:
+    tau = args.tau
+
+    def do_calibrate():
+        nonlocal tau
+        tau, share_cal = calibrate_tau(e, rule, n_cal, w, d_min)
+        log(f"[bench] tau={tau:.6f} nats ({rule[0]} {rule[1]}"
+            + (f" -> large share {share_cal:.3f}" if share_cal is not None else "")
+            + f", {n_cal} calibration tokens per row) at {time.time() - t0:.1f}s")
+    if tau is None:
+        leg("calibration", do_calibrate)
+    else:
+        log(f"[bench] tau={tau:.6f} nats (given)")
+    out["config"]["tau_nats"] = tau
+
+    def do_headline():
+        dt, st = timed(-1, grouped)
+        n_tok = st["tokens_small"] + st["tokens_large"]
+        algo_gbs = st["algorithmic_bytes"] / dt / 1e9
+        out.update({"value": n_tok / dt, "ms_per_step": 1e3 * dt / steps,
+                    "decode_hbm_gbs": algo_gbs, "decode_hbm_frac_of_peak": algo_gbs / HBM_PEAK_GBS,
+                    "large_token_share": st["large_share"], "param_ratio": st["param_ratio"], "switches": st["switches"],
+                    "host_syncs": st["host_syncs"]})
+        if grouped:
+            out["grouped"] = {"start": args.sched_start, "stop": args.sched_stop, "large_passes": st["steps_large"],
+                              "small_passes": st["steps_small"], "catchup_rows_large": st["catchup_rows_large"]}
+        log(f"[bench] EAD ({schedule}): {n_tok / dt:.1f} tok/s, {algo_gbs:.0f} GB/s algorithmic ({algo_gbs / HBM_PEAK_GBS:.1%} of peak), "
+            f"large share {st['large_share']:.3f}, switches {st['switches']}, host syncs {st['host_syncs']}, "
+            f"passes large/small {st['steps_large']}/{st['steps_small']}")
+
+    def do_lockstep():
         d1, s1 = timed(-1, False)
         n1 = s1["tokens_small"] + s1["tokens_large"]
-        extra["lockstep"] = {"tokens_per_s": n1 / d1, "large_passes": s1["steps_large"], "small_passes": s1["steps_small"]}
-        extra["grouped"] = {"start": args.sched_start, "stop": args.sched_stop, "large_passes": st["steps_large"],
-                            "small_passes": st["steps_small"]}
-        log(f"[bench] lock step: {n1 / d1:.1f} tok/s with {s1['steps_large']} large / {s1['steps_small']} small passes; "
-            f"grouped: {st['steps_large']} / {st['steps_small']}")
-    if not args.no_single_model:
-        for name, which in (("small_only", 0), ("large_only", 1)):
-            d2, s2 = timed(which)
-            n2 = s2["tokens_small"] + s2["tokens_large"]
-            extra[name] = {"tokens_per_s": n2 / d2, "hbm_frac": s2["algorithmic_bytes"] / d2 / 1e9 / HBM_PEAK_GBS}
-            log(f"[bench] {name}: {n2 / d2:.1f} tok/s, {extra[name]['hbm_frac']:.1%} of HBM peak")
+        out["lockstep"] = {"tokens_per_s": n1 / d1, "large_passes": s1["steps_large"], "small_passes": s1["steps_small"],
+                           "large_token_share": s1["large_share"]}
+        log(f"[bench] lock step: {n1 / d1:.1f} tok/s with {s1['steps_large']} large / {s1['steps_small']} small passes")
 
-    # ---- per-kernel HIP-event timing on a separate, untimed run ----
-    e.set_gate(w, tau, d_min)
-    e.begin(prompts, warmup + args.profile_steps)
-    e.decode(warmup)
-    e.profile(True)
-    e.decode(args.profile_steps)
-    prof = e.profile_read()
-    e.profile(False)
-    by_kind = {}
-    for r in prof:
-        k = r["name"].split("/")[0]
-        a = by_kind.setdefault(k, {"launches": 0, "total_ms": 0.0, "bytes": 0.0})
-        a["launches"] += r["launches"]; a["total_ms"] += r["total_ms"]; a["bytes"] += r["bytes"]
-    for r in sorted(prof, key=lambda r: -r["total_ms"]):
-        gbs = r["bytes"] / max(r["total_ms"], 1e-9) / 1e6
-        log(f"[prof] {r['name']:<28s} n={r['launches']:<6d} avg {1e3 * r['total_ms'] / r['launches']:8.2f} us  "
-            f"{gbs:8.0f} GB/s")
-    # the dominant kernel is reported per model (one kernel, one shape): the one that moves the most
-    # bytes over the pass, which does not flip with timing noise the way a ranking by time can
-    dom = max(prof, key=lambda r: r["bytes"])["name"]
-    d = next(r for r in prof if r["name"] == dom)
-    achieved = d["bytes"] / d["total_ms"] / 1e6
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload, dom),
-                "avg_launch_us": 1e3 * d["total_ms"] / d["launches"],
-                "bytes_per_launch": d["bytes"] / d["launches"], "launches": d["launches"]}
+    def do_single(name, which):
+        d2, s2 = timed(which, False)
+        n2 = s2["tokens_small"] + s2["tokens_large"]
+        out[name] = {"tokens_per_s": n2 / d2, "hbm_frac": s2["algorithmic_bytes"] / d2 / 1e9 / HBM_PEAK_GBS}
+        log(f"[bench] {name}: {n2 / d2:.1f} tok/s, {out[name]['hbm_frac']:.1%} of HBM peak")
 
-    out = {
-        "metric": "generated tokens/s at 1 GPU", "value": tok_s, "unit": "tokens/s", "n_gpus": 1,
-        "steps": steps, "warmup": warmup, "ms_per_step": 1e3 * dt / steps, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if ss.bf16 else "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "small": ss.name, "large": sl.name, "batch": batch,
-                   "prompt_len": [int(plo), int(phi)], "window": w, "d_min": d_min, "tau_nats": tau,
-                   "vocab": ss.vocab, "schedule": args.schedule, "temperature": args.temperature},
-        "decode_hbm_gbs": algo_gbs, "decode_hbm_frac_of_peak": algo_gbs / HBM_PEAK_GBS,
-        "large_token_share": st["large_share"], "param_ratio": st["param_ratio"], "switches": st["switches"],
-        "host_syncs": st["host_syncs"], **extra, "roofline": roofline,
-    }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline((ss, sl), Ws, Wl, prompts, w, tau, d_min)
-    e.close()
+    def do_profile():
+        # per-kernel HIP-event timing on a separate, untimed run of the same schedule
+        e.force_model(-1)
+        e.set_schedule(grouped, args.sched_start, args.sched_stop)
+        e.set_gate(w, tau, d_min)
+        e.rewind(ln["profile_new"])
+        if settle:
+            e.decode(settle)
+        e.decode(warmup)
+        e.profile(True)
+        e.decode(ln["profile_steps"])
+        prof = e.profile_read()
+        e.profile(False)
+        e.set_schedule(False)
+        for r in sorted(prof, key=lambda r: -r["total_ms"]):
+            gbs = r["bytes"] / max(r["total_ms"], 1e-9) / 1e6
+            log(f"[prof] {r['name']:<28s} n={r['launches']:<6d} avg {1e3 * r['total_ms'] / r['launches']:8.2f} us  "
+                f"{gbs:8.0f} GB/s")
+        # the dominant kernel is reported per model (one kernel, one shape): the one that moves the most
+        # bytes over the pass, which does not flip with timing noise the way a ranking by time can
+        d = max(prof, key=lambda r: r["bytes"])
+        achieved = d["bytes"] / d["total_ms"] / 1e6
+        out["roofline"] = {"bound": "hbm", "kernel": d["name"], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload, d["name"]),
+                           "avg_launch_us": 1e3 * d["total_ms"] / d["launches"],
+                           "bytes_per_launch": d["bytes"] / d["launches"], "launches": d["launches"],
+                           "profiled_steps": ln["profile_steps"], "schedule": schedule}
+
+    def do_cpu():
+        big = sl.n_params() > 2e9
+        out["cpu_baseline"] = cpu_baseline((ss, sl), Ws, Wl, prompts, w, tau, d_min,
+                                           n_prompt=8 if big else 16, n_new=14 if big else 24)
+
+    if tau is not None:
+        leg("headline", do_headline)
+        if grouped:
+            leg("lockstep", do_lockstep)
+        if not args.no_single_model:
+            leg("small_only", lambda: do_single("small_only", 0))
+            leg("large_only", lambda: do_single("large_only", 1))
+        if out.get("large_only") and out["value"]:
+            out["ead_over_large_only"] = out["value"] / out["large_only"]["tokens_per_s"]
+        leg("profile", do_profile)
+        if not args.no_cpu_baseline:
+            leg("cpu_baseline", do_cpu)
+    if errors:
+        out["errors"] = errors
+    leg("close", e.close)
     print(json.dumps(out), flush=True)
+    return 1 if errors or out["value"] is None else 0
 
 
 if __name__ == "__main__":
-    main()
+    sys.exit(main() or 0)

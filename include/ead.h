@@ -15,20 +15,25 @@
  *    memory on the GPU that was current when the handle was created.
  *  - Weights are BORROWED only for the duration of ead_create(): the library
  *    copies them into its own streaming layout, after which the caller may free
- *    them.  Everything else the library needs (KV caches, gate state, scratch)
- *    it allocates in ead_create() and frees in ead_destroy().
+ *    them.  Until the caller does, device memory holds every matrix twice (the
+ *    caller's tensors and the library's tiles): about 58 GB for a 0.5 B + 14 B
+ *    parameter pair in bf16, half of that afterwards.  Everything else the
+ *    library needs (KV caches, gate state, scratch) it allocates in ead_create()
+ *    and frees in ead_destroy().
  *  - Outputs are caller-owned host buffers unless the name ends in _dev.
  *  - A handle serves one call at a time (calls are not re-entrant).  Work is
  *    queued on ead_params.hip_stream and every call returns after its results
  *    have reached the host buffers.
- *  - Decoding is greedy (token = arg max of the raw logits, lowest index on a
- *    tie); Algorithm 1's temperature-sampling step is not implemented.
+ *  - Decoding is greedy by default (token = arg max of the raw logits, lowest
+ *    index on a tie); ead_set_sampling() turns on Algorithm 1's sampling step
+ *    y ~ softmax(l / T).
  *  - Models: pre-norm decoders with RMSNorm, rotary position embedding
  *    ("rotate-half" pairing, angle pos * theta^(-2i/head_dim)), grouped-query
  *    attention (query head h reads KV head h / (n_heads / n_kv_heads)) and a
  *    SwiGLU feed-forward block; no biases.
- *  - Shape limits: d_model, d_ffn multiples of 32; vocab and n_heads*head_dim
- *    multiples of 16; head_dim one of 32, 64, 128.
+ *  - Shape limits: d_model, d_ffn and n_heads*head_dim multiples of 32, at most
+ *    15360 (float32 weights: at most 4096); vocab a multiple of 16; head_dim one
+ *    of 32, 64, 128; n_heads / n_kv_heads an integer between 1 and 8.
  */
 #ifndef EAD_H
 #define EAD_H
@@ -146,6 +151,13 @@ ead_status ead_generate(ead_handle *h, const int32_t *prompt_tokens, const int32
  * first decode step produces the first token).  max_new_tokens bounds the run. */
 ead_status ead_begin(ead_handle *h, const int32_t *prompt_tokens, const int32_t *prompt_lens,
                      int32_t batch, int32_t max_new_tokens);
+/* Start the run over from the state ead_begin() left: Algorithm 1's initialisation (empty
+ * window, M = M_S, c = 0, nothing generated) with both models still holding the prompts of the
+ * last ead_begin() in their caches, so no prompt pass is repeated.  Takes the gate, forced-model,
+ * schedule and sampling settings in force now; max_new_tokens bounds the new run.
+ * Errors: STATE when the caches no longer hold those prompts (no ead_begin yet, or an
+ * ead_score / ead_replay since), SEQ_OVERFLOW, INVALID_ARG. */
+ead_status ead_rewind(ead_handle *h, int32_t max_new_tokens);
 /* Run n_steps iterations of Algorithm 1's loop for every unfinished row
  * (one token per row per step, including any catch-up the active model needs).
  * Returns after the last step's work has finished on the GPU. */
@@ -183,11 +195,16 @@ ead_status ead_replay(ead_handle *h, const int32_t *prompt_tokens, const int32_t
 /* Row-wise entropy (Eq. 1-2) and arg max of a logits matrix already in device memory.
  *   logits_dev [rows, vocab] of `dtype`, row-major; H_dev [rows] float32 in `unit`;
  *   argmax_dev [rows] int32 (nullable).  Asynchronous on `hip_stream`.
- * Uses an internal scratch buffer that the first call on a device allocates. */
+ * Limits: 1 <= rows <= 4096, vocab a multiple of 8 and at most 1048576.
+ * The per-chunk statistics go through a 6 MB buffer per device that the first call on that
+ * device allocates and the process keeps; all calls on a device share it, so calls whose
+ * work overlaps on the GPU (different streams) race: issue them on one stream or wait in between. */
 ead_status ead_entropy_argmax(const void *logits_dev, int32_t dtype, int32_t rows, int32_t vocab,
                               int32_t unit, float *H_dev, int32_t *argmax_dev, void *hip_stream);
 
-/* Rolling window + switch rule (Eq. 3-4) for `rows` independent sequences, state on device. */
+/* Rolling window + switch rule (Eq. 3-4) for `rows` independent sequences, state on device
+ * (1 <= rows <= 4096).  A gate owns the scratch of its own entropy passes, so gates on
+ * different streams do not interfere; one gate serves one call at a time. */
 typedef struct ead_gate ead_gate;
 ead_status ead_gate_create(int32_t rows, int32_t window, float tau, int32_t d_min, void *hip_stream,
                            ead_gate **out);

@@ -65,6 +65,7 @@ _SIGNATURES = {
     "ead_set_gate": (C.c_int, [C.c_void_p, C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_int32]),
     "ead_generate": (C.c_int, [C.c_void_p, _I32P, _I32P, C.c_int32, C.c_int32, _I32P, _U8P, _F32P, _F32P, _I32P]),
     "ead_begin": (C.c_int, [C.c_void_p, _I32P, _I32P, C.c_int32, C.c_int32]),
+    "ead_rewind": (C.c_int, [C.c_void_p, C.c_int32]),
     "ead_decode": (C.c_int, [C.c_void_p, C.c_int32]),
     "ead_fetch": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _U8P, _F32P, _F32P, _I32P]),
     "ead_score": (C.c_int, [C.c_void_p, C.c_int32, _I32P, C.c_int32, _F32P, _F32P, _I32P]),
@@ -218,6 +219,10 @@ class EAD:
         self._B, self._max_new = len(lens), max_new
         self._check(lib().ead_begin(self._h, _ptr(flat, _I32P), _ptr(lens, _I32P), len(lens), max_new))
 
+    def rewind(self, max_new: int):
+        self._max_new = max_new
+        self._check(lib().ead_rewind(self._h, max_new))
+
     def decode(self, n_steps: int):
         self._check(lib().ead_decode(self._h, n_steps))
 
@@ -279,15 +284,18 @@ class EAD:
         self._check(lib().ead_reset_stats(self._h))
 
 
-def entropy_argmax(logits, unit=NATS):
-    """Row-wise (H, argmax) of a CUDA logits tensor [rows, vocab] (bf16 or fp32)."""
+def entropy_argmax(logits, unit=NATS, out=None):
+    """Row-wise (H, argmax) of a CUDA logits tensor [rows, vocab] (bf16 or fp32).
+    out: (H, argmax) tensors to write into."""
     import torch
     assert logits.is_cuda and logits.is_contiguous() and logits.dim() == 2
     rows, V = logits.shape
-    H = torch.empty(rows, dtype=torch.float32, device=logits.device)
-    am = torch.empty(rows, dtype=torch.int32, device=logits.device)
-    rc = lib().ead_entropy_argmax(logits.data_ptr(), _dtype_code(logits), rows, V, unit, H.data_ptr(),
-                                  am.data_ptr(), _stream_ptr())
+    if out is None:
+        out = (torch.empty(rows, dtype=torch.float32, device=logits.device),
+               torch.empty(rows, dtype=torch.int32, device=logits.device))
+    H, am = out
+    fn = lib().ead_entropy_argmax
+    rc = fn(logits.data_ptr(), _dtype_code(logits), rows, V, unit, H.data_ptr(), am.data_ptr(), _stream_ptr())
     if rc:
         raise EadError(rc, (lib().ead_last_error(None) or b"").decode())
     return H, am

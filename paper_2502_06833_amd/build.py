@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libead.so")
 SOURCES = ["ead.hip"]
-HEADERS = ["common.hpp", "linear.hpp", "attention.hpp", "entropy.hpp"]
+HEADERS = ["common.hpp", "linear.hpp", "attention.hpp", "entropy.hpp", "state.hpp", "fused.hpp"]
 
 
 def _newest_source() -> float:
@@ -37,18 +37,5 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
-def build_probe() -> str:
-    """Torch-free C++ driver used for hardware-counter (rocprofv3 --pmc) runs."""
-    build(force=False)
-    exe = os.path.join(HERE, "roofline_probe")
-    cmd = ["hipcc", "--offload-arch=gfx950", "-O2", "-std=c++17", "-o", exe, os.path.join(CSRC, "roofline_probe.hip"),
-           "-L" + HERE, "-lead", "-Wl,-rpath," + HERE]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + r.stderr)
-    return exe
-
-
 if __name__ == "__main__":
     print(build(verbose=True))
-    print(build_probe())

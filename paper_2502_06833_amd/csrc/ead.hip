@@ -11,6 +11,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <string>
 #include <type_traits>
@@ -184,11 +185,12 @@ struct ead_handle {
     int *h_model, *h_done;   // pinned
     LaneSet lanes[2]; int cur_lane = 0, two_lanes = 0; hipStream_t lane1_stream = nullptr;
     // fused single-row decode
-    long long *trace = nullptr;
     float *att_o; float2 *att_ml; unsigned *bar_mem; int *abort_flag; unsigned bar_epoch = 0; int fused_on = 0, fused_grid = 0;
     std::vector<void *> allocs;
     std::vector<HostSeq> hs;
     int batch, max_new, began, replay, n_new, force_model, step;
+    int prefilled = 0;                   // both caches hold the prompts of the last ead_begin and nothing has clobbered them
+    std::vector<int> prompt_len;
     int sched_grouped = 0, sched_phase = 0; float sched_hi = 0.5f, sched_lo = 0.25f;
     float samp_temp = 0.f; uint64_t samp_seed = 0;        // temperature 0: greedy
     int scoring = 0;                                       // inside ead_score: logits of given tokens, nothing is sampled
@@ -705,9 +707,6 @@ ead_status fused_step(ead_handle *h, int mi, double keys) {
     a.bar = GridBar{h->bar_mem, h->bar_mem + kBarGroups * 32, h->abort_flag, h->bar_epoch};
     a.fin = make_fin(h, mi, false);
     a.batch = h->batch;
-#ifdef EAD_FUSED_TRACE
-    a.trace = h->trace;
-#endif
     void *args[] = {&a};
     ProfScope ps(h, PK_FUSED, mi, m.weight_bytes_nolm + m.lm_bytes + keys * m.kv_bytes_per_pos);
     HIP_TRY(h, hipLaunchCooperativeKernel(fused_kernel_for(m), dim3(h->fused_grid), dim3(kFusedThreads), args,
@@ -782,37 +781,52 @@ ead_status validate_prompts(ead_handle *h, const int32_t *toks, const int32_t *l
     return EAD_OK;
 }
 
-ead_status begin_impl(ead_handle *h, const int32_t *toks, const int32_t *lens, int batch, int max_new) {
-    use_lane(h, 0);
-    if (h->two_lanes) HIP_TRY(h, hipStreamSynchronize(h->lanes[1].stream));
-    TRY(validate_prompts(h, toks, lens, batch, max_new));
+// Algorithm 1's initialisation for every sequence of the run (W empty, M = M_S, c = 0, nothing generated),
+// on the host mirror and on the device.  kv_fill = 0: no model has consumed anything yet (ead_begin, before
+// the prompt passes); 1: both models hold every prompt position but the last (ead_rewind).
+ead_status reset_run_state(ead_handle *h, int max_new, int kv_fill) {
     hipStream_t st = h->stream;
-    const int MB = h->s.max_batch, MS = h->s.max_seq;
-    h->batch = batch; h->max_new = max_new; h->began = 0; h->step = 0;
+    const int MB = h->s.max_batch, batch = h->batch;
+    h->max_new = max_new; h->began = 0; h->step = 0; h->sched_phase = 0;
     h->hs.assign(batch, HostSeq{});
-    std::vector<int> tok((size_t)batch * MS, 0), len(MB, 0), zeros(MB * 2, 0), model(MB, 0), neg(MB, -1);
-    size_t off = 0;
+    std::vector<int> len(MB, 0), zeros(MB * 2, 0), kv(MB * 2, 0), model(MB, 0), neg(MB, -1), goal(MB, max_new);
     for (int b = 0; b < batch; ++b) {
-        memcpy(&tok[(size_t)b * MS], toks + off, sizeof(int) * lens[b]);
-        off += lens[b];
-        len[b] = lens[b];
         HostSeq &s = h->hs[b];
-        s.len = lens[b]; s.kvlen[0] = s.kvlen[1] = 0; s.c = 0; s.ngen = 0; s.done = 0; s.last_step = -1; s.goal = max_new;
+        s.len = len[b] = h->prompt_len[b];
+        s.kvlen[0] = s.kvlen[1] = kv[b] = kv[MB + b] = kv_fill ? h->prompt_len[b] - 1 : 0;
+        s.c = 0; s.ngen = 0; s.done = 0; s.last_step = -1; s.goal = max_new;
         s.model = h->force_model >= 0 ? h->force_model : (h->replay ? -1 : 0);
         model[b] = std::max(s.model, 0);
     }
-    HIP_TRY(h, hipMemcpyAsync(h->s.tokens, tok.data(), tok.size() * sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.len, len.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
-    HIP_TRY(h, hipMemcpyAsync(h->s.kvlen, zeros.data(), 2 * MB * sizeof(int), hipMemcpyHostToDevice, st));
+    HIP_TRY(h, hipMemcpyAsync(h->s.kvlen, kv.data(), 2 * MB * sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.model, model.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.c, zeros.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.ngen, zeros.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.done, zeros.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.last_step, neg.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
-    std::vector<int> goal(MB, max_new);
     HIP_TRY(h, hipMemcpyAsync(h->s.goal, goal.data(), MB * sizeof(int), hipMemcpyHostToDevice, st));
     HIP_TRY(h, hipMemcpyAsync(h->s.err, zeros.data(), sizeof(int), hipMemcpyHostToDevice, st));
-    HIP_TRY(h, hipStreamSynchronize(st));
+    HIP_TRY(h, hipStreamSynchronize(st));          // the staging vectors leave scope
+    return EAD_OK;
+}
+
+ead_status begin_impl(ead_handle *h, const int32_t *toks, const int32_t *lens, int batch, int max_new) {
+    use_lane(h, 0);
+    if (h->two_lanes) HIP_TRY(h, hipStreamSynchronize(h->lanes[1].stream));
+    TRY(validate_prompts(h, toks, lens, batch, max_new));
+    hipStream_t st = h->stream;
+    const int MS = h->s.max_seq;
+    h->batch = batch; h->prefilled = 0;
+    h->prompt_len.assign(lens, lens + batch);
+    std::vector<int> tok((size_t)batch * MS, 0);
+    size_t off = 0;
+    for (int b = 0; b < batch; ++b) {
+        memcpy(&tok[(size_t)b * MS], toks + off, sizeof(int) * lens[b]);
+        off += lens[b];
+    }
+    HIP_TRY(h, hipMemcpyAsync(h->s.tokens, tok.data(), tok.size() * sizeof(int), hipMemcpyHostToDevice, st));
+    TRY(reset_run_state(h, max_new, 0));           // waits for the stream: tok may leave scope
     // both models consume every prompt token but the last
     std::vector<int> rows; std::vector<char> complete;
     for (int m = 0; m < 2; ++m) {
@@ -828,6 +842,7 @@ ead_status begin_impl(ead_handle *h, const int32_t *toks, const int32_t *lens, i
     HIP_TRY(h, hipStreamSynchronize(st));
     memset(&h->stats, 0, sizeof h->stats);
     h->began = 1;
+    h->prefilled = h->replay ? 0 : 1;
     return EAD_OK;
 }
 
@@ -1102,58 +1117,77 @@ ead_status fetch_impl(ead_handle *h, int stride, int32_t *tok, uint8_t *mid, flo
     return EAD_OK;
 }
 
-// ---- stand-alone entropy: per-device scratch for the partials -------------------------
+// ---- stand-alone entropy: where the partials of a pass go ----------------------------------
+// ead_entropy_argmax: a per-device buffer that the first call on a device allocates (kept until the
+// process ends).  A gate owns a buffer of its own.
 constexpr int kEntMaxRows = 4096, kEntMaxChunks = 64;
-EntPartial *g_ent_scratch[16] = {nullptr};
+constexpr int kEntMaxDevices = 16;
 
-template <typename T>
-void launch_entropy_partial(const void *const *step_logits, int steps, int rows, int V, EntPartial *part, int *n_chunks,
-                            hipStream_t st) {
+struct EntDevice {                // per device, set up once by the first call on it
+    bool ready = false;
+    int resident = 1024;          // workgroups of k_entropy_partial the chip holds at once
+    EntPartial *heap_part = nullptr;       // ead_entropy_argmax's buffer, allocated on first use
+};
+EntDevice g_ent_dev[kEntMaxDevices];
+std::mutex g_ent_mutex;
+
+// Device record of the current device.
+ead_status entropy_device(EntDevice **out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return fail(nullptr, EAD_ERR_NO_DEVICE, "no HIP device");
+    if (dev < 0 || dev >= kEntMaxDevices) return fail(nullptr, EAD_ERR_DEVICE, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_ent_mutex);
+    EntDevice &d = g_ent_dev[dev];
+    if (!d.ready) {
+        int per_cu = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_entropy_partial<bf16_t>, 256, 0) == hipSuccess && per_cu > 0)
+            d.resident = per_cu * prop.multiProcessorCount;
+        d.ready = true;
+    }
+    *out = &d;
+    return EAD_OK;
+}
+
+ead_status entropy_heap_scratch(EntDevice *d, EntPartial **out) {
+    std::lock_guard<std::mutex> lock(g_ent_mutex);
+    if (!d->heap_part) {
+        void *p = nullptr;
+        if (hipMalloc(&p, sizeof(EntPartial) * (size_t)kEntMaxRows * kEntMaxChunks) != hipSuccess)
+            return fail(nullptr, EAD_ERR_OOM, "scratch allocation failed");
+        d->heap_part = (EntPartial *)p;
+    }
+    *out = d->heap_part;
+    return EAD_OK;
+}
+
+// The split of a row into work items depends on (rows, V) alone, so a step's result does not depend on
+// how many steps share a launch, nor on which entry point asked for it.  Long chunks (up to 8 vectors
+// per thread) amortise the per-workgroup merge; shorter ones only when the rows of one step would
+// otherwise give too few workgroups to fill the chip.
+void entropy_split(int rows, int V, int *chunks_out, int *per_out) {
     const int nvec = V / 8;
-    // long chunks (up to 8 vectors per thread) amortise the per-workgroup merge; shorter ones
-    // only when the rows of one step would otherwise give too few workgroups to fill the chip.
-    // The split depends on (rows, V) alone, so a step's result does not depend on how many
-    // steps share a launch.
     int chunks = std::max(1, (nvec + 2047) / 2048);
     while ((long)chunks * rows < 512 && chunks < kEntMaxChunks && nvec / (chunks * 2) >= 256) chunks *= 2;
     int per = (std::max(nvec, 1) + chunks - 1) / chunks;
     while (per > 8 * 256) { ++chunks; per = (nvec + chunks - 1) / chunks; }
-    *n_chunks = chunks;
+    *chunks_out = chunks; *per_out = per;
+}
+
+template <typename T>
+void launch_entropy_partial(const void *const *step_logits, int steps, int rows, int V, EntPartial *part, int resident,
+                            hipStream_t st) {
+    int chunks, per;
+    entropy_split(rows, V, &chunks, &per);
     EntArgs<T> a{};
     for (int z = 0; z < steps; ++z) a.step_logits[z] = (const T *)step_logits[z];
     a.V = V; a.rows = rows; a.chunks = chunks; a.vec_per_item = per; a.items = steps * rows * chunks; a.partials = part;
     // persistent grid: as many workgroups as the chip holds at once
-    static int resident = 0;
-    if (!resident) {
-        int per_cu = 0, dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_entropy_partial<T>, 256, 0) == hipSuccess && per_cu > 0)
-            resident = per_cu * prop.multiProcessorCount;
-        else
-            resident = 1024;
-    }
     hipLaunchKernelGGL((k_entropy_partial<T>), dim3(std::min(a.items, resident)), dim3(256), 0, st, a);
 }
 
-ead_status entropy_scratch(EntPartial **out) {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return fail(nullptr, EAD_ERR_NO_DEVICE, "no HIP device");
-    if (dev < 0 || dev >= 16) return fail(nullptr, EAD_ERR_DEVICE, "device index %d out of range", dev);
-    if (!g_ent_scratch[dev]) {
-        void *p = nullptr;
-        // chunks can exceed kEntMaxChunks only for rows longer than 64*2048*8 elements
-        if (hipMalloc(&p, sizeof(EntPartial) * (size_t)kEntMaxRows * kEntMaxChunks * 4) != hipSuccess)
-            return fail(nullptr, EAD_ERR_OOM, "scratch allocation failed");
-        g_ent_scratch[dev] = (EntPartial *)p;
-    }
-    *out = g_ent_scratch[dev];
-    return EAD_OK;
-}
-
-// step_logits: host array of `steps` device pointers (<= kGateMaxSteps), one [rows, vocab] matrix each
-ead_status entropy_partials(const void *const *step_logits, int steps, int dtype, int rows, int vocab, hipStream_t st,
-                            EntPartial **part, int *chunks) {
+ead_status entropy_check(const void *const *step_logits, int steps, int dtype, int rows, int vocab) {
     if (steps < 1 || steps > kGateMaxSteps || (long)steps * rows > kEntMaxRows)
         return fail(nullptr, EAD_ERR_INVALID_ARG, "too many steps for one launch");
     for (int z = 0; z < steps; ++z)
@@ -1162,17 +1196,24 @@ ead_status entropy_partials(const void *const *step_logits, int steps, int dtype
     if (vocab < 1) return fail(nullptr, EAD_ERR_INVALID_ARG, "vocab must be >= 1");
     if (dtype != EAD_F32 && dtype != EAD_BF16) return fail(nullptr, EAD_ERR_INVALID_ARG, "unknown dtype");
     if (vocab % 8) return fail(nullptr, EAD_ERR_SHAPE, "vocab must be a multiple of 8");
-    if ((long)vocab > 64L * 2048 * 8 * 4) return fail(nullptr, EAD_ERR_SHAPE, "vocab too large");
-    TRY(entropy_scratch(part));
-    if (dtype == EAD_BF16) launch_entropy_partial<bf16_t>(step_logits, steps, rows, vocab, *part, chunks, st);
-    else launch_entropy_partial<float>(step_logits, steps, rows, vocab, *part, chunks, st);
+    if ((long)vocab > 64L * 2048 * 8) return fail(nullptr, EAD_ERR_SHAPE, "vocab above %ld", 64L * 2048 * 8);
     return EAD_OK;
+}
+
+// step_logits: host array of `steps` device pointers (<= kGateMaxSteps), one [rows, vocab] matrix each;
+// part: room for steps * rows * chunks partials (chunks as entropy_split gives it)
+void entropy_launch(const void *const *step_logits, int steps, int dtype, int rows, int vocab, hipStream_t st,
+                    EntPartial *part, int resident) {
+    if (dtype == EAD_BF16) launch_entropy_partial<bf16_t>(step_logits, steps, rows, vocab, part, resident, st);
+    else launch_entropy_partial<float>(step_logits, steps, rows, vocab, part, resident, st);
 }
 
 }  // namespace
 
 struct ead_gate {
     GateState st; GateCfg cfg; int rows; hipStream_t stream;
+    EntPartial *part = nullptr;   // partials of this gate's entropy passes: (steps per launch) x rows x kEntMaxChunks
+    int resident = 1024;
     std::vector<void *> allocs;
 };
 
@@ -1297,9 +1338,6 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
         {
             const size_t hmax = std::max(a.H, b.H), qm = qmax;
             TRY(dmalloc(h, &h->att_o, qm * kFusedMaxSplits)); TRY(dmalloc(h, &h->att_ml, hmax * kFusedMaxSplits));
-#ifdef EAD_FUSED_TRACE
-            TRY(dmalloc(h, &h->trace, (size_t)8192));
-#endif
             TRY(dmalloc(h, &h->bar_mem, (size_t)kBarGroups * 32 + 32)); TRY(dmalloc(h, &h->abort_flag, (size_t)1));
             HIP_TRY(h, hipMemsetAsync(h->bar_mem, 0, (kBarGroups * 32 + 32) * sizeof(unsigned), h->stream));
             HIP_TRY(h, hipMemsetAsync(h->abort_flag, 0, sizeof(int), h->stream));
@@ -1351,6 +1389,23 @@ ead_status ead_begin(ead_handle *h, const int32_t *prompt_tokens, const int32_t 
     if (!h) return EAD_ERR_INVALID_ARG;
     h->replay = 0; h->n_new = 0;
     return begin_impl(h, prompt_tokens, prompt_lens, batch, max_new_tokens);
+}
+
+ead_status ead_rewind(ead_handle *h, int32_t max_new_tokens) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    if (!h->prefilled) return fail(h, EAD_ERR_STATE, "ead_rewind needs the prompts of a previous ead_begin in the caches");
+    if (max_new_tokens < 1) return fail(h, EAD_ERR_INVALID_ARG, "max_new_tokens must be >= 1");
+    for (int b = 0; b < h->batch; ++b)
+        if ((long)h->prompt_len[b] + max_new_tokens > h->prm.max_seq)
+            return fail(h, EAD_ERR_SEQ_OVERFLOW, "prompt %d: %d + %d tokens exceed max_seq %d", b, h->prompt_len[b], max_new_tokens, h->prm.max_seq);
+    use_lane(h, 0);
+    if (h->two_lanes) HIP_TRY(h, hipStreamSynchronize(h->lanes[1].stream));
+    HIP_TRY(h, hipStreamSynchronize(h->stream));
+    h->replay = 0; h->n_new = 0;
+    TRY(reset_run_state(h, max_new_tokens, 1));
+    memset(&h->stats, 0, sizeof h->stats);
+    h->began = 1;
+    return EAD_OK;
 }
 
 ead_status ead_decode(ead_handle *h, int32_t n_steps) {
@@ -1409,7 +1464,7 @@ ead_status ead_replay(ead_handle *h, const int32_t *prompt_tokens, const int32_t
     }
     if (rc == EAD_OK) rc = decode_impl(h, n_new);
     if (rc == EAD_OK) rc = fetch_impl(h, n_new, out_argmax, nullptr, out_entropy, out_window_mean, out_decision, nullptr);
-    h->replay = 0; h->force_model = saved_force; h->began = 0;
+    h->replay = 0; h->force_model = saved_force; h->began = 0; h->prefilled = 0;
     return rc;
 }
 
@@ -1424,7 +1479,7 @@ ead_status ead_score(ead_handle *h, int32_t which, const int32_t *tokens, int32_
         if (tokens[i] < 0 || tokens[i] >= m.V) return fail(h, EAD_ERR_INVALID_ARG, "token %d out of range", i);
     use_lane(h, 0);
     hipStream_t st = h->stream;
-    h->began = 0; h->batch = 1; h->replay = 0;
+    h->began = 0; h->batch = 1; h->replay = 0; h->prefilled = 0;
     struct Scoring { ead_handle *h; Scoring(ead_handle *h_) : h(h_) { h->scoring = 1; } ~Scoring() { h->scoring = 0; } } scoring_guard(h);
     h->hs.assign(1, HostSeq{});
     HostSeq &s = h->hs[0];
@@ -1476,15 +1531,6 @@ ead_status ead_reset_stats(ead_handle *h) {
     return EAD_OK;
 }
 
-#ifdef EAD_FUSED_TRACE
-ead_status ead_trace_read(ead_handle *h, long long *out) {
-    if (!h || !out) return EAD_ERR_INVALID_ARG;
-    HIP_TRY(h, hipStreamSynchronize(h->stream));
-    HIP_TRY(h, hipMemcpy(out, h->trace, 8192 * sizeof(long long), hipMemcpyDeviceToHost));
-    return EAD_OK;
-}
-#endif
-
 ead_status ead_set_schedule(ead_handle *h, int32_t grouped, float start_fraction, float stop_fraction) {
     if (!h) return EAD_ERR_INVALID_ARG;
     if (grouped && !(start_fraction > 0.f && start_fraction <= 1.f && stop_fraction >= 0.f && stop_fraction <= start_fraction))
@@ -1534,16 +1580,28 @@ ead_status ead_profile_read(ead_handle *h, ead_kernel_profile *out, int32_t capa
 }
 
 // ---- entropy / gate on their own ---------------------------------------------------------
-ead_status ead_entropy_argmax(const void *logits_dev, int32_t dtype, int32_t rows, int32_t vocab, int32_t unit,
-                              float *H_dev, int32_t *argmax_dev, void *hip_stream) {
+namespace {
+ead_status entropy_argmax_impl(const void *logits_dev, int32_t dtype, int32_t rows, int32_t vocab, int32_t unit,
+                               float *H_dev, int32_t *argmax_dev, hipStream_t st) {
     if (!H_dev) return fail(nullptr, EAD_ERR_INVALID_ARG, "H_dev is null");
     if (unit != EAD_NATS && unit != EAD_BITS) return fail(nullptr, EAD_ERR_INVALID_ARG, "unit must be 0 or 1");
-    EntPartial *part = nullptr; int chunks = 0;
-    TRY(entropy_partials(&logits_dev, 1, dtype, rows, vocab, (hipStream_t)hip_stream, &part, &chunks));
-    hipLaunchKernelGGL(k_entropy_finalize, dim3(rows), dim3(64), 0, (hipStream_t)hip_stream, part, chunks, rows, unit,
-                       H_dev, argmax_dev);
+    TRY(entropy_check(&logits_dev, 1, dtype, rows, vocab));
+    int chunks = 0, per = 0;
+    entropy_split(rows, vocab, &chunks, &per);
+    EntDevice *d = nullptr;
+    TRY(entropy_device(&d));
+    EntPartial *part = nullptr;
+    TRY(entropy_heap_scratch(d, &part));
+    entropy_launch(&logits_dev, 1, dtype, rows, vocab, st, part, d->resident);
+    hipLaunchKernelGGL(k_entropy_finalize, dim3(rows), dim3(64), 0, st, part, chunks, rows, unit, H_dev, argmax_dev);
     if (hipGetLastError() != hipSuccess) return fail(nullptr, EAD_ERR_DEVICE, "kernel launch failed");
     return EAD_OK;
+}
+}  // namespace
+
+ead_status ead_entropy_argmax(const void *logits_dev, int32_t dtype, int32_t rows, int32_t vocab, int32_t unit,
+                              float *H_dev, int32_t *argmax_dev, void *hip_stream) {
+    return entropy_argmax_impl(logits_dev, dtype, rows, vocab, unit, H_dev, argmax_dev, (hipStream_t)hip_stream);
 }
 
 ead_status ead_gate_create(int32_t rows, int32_t window, float tau, int32_t d_min, void *hip_stream, ead_gate **out) {
@@ -1554,13 +1612,19 @@ ead_status ead_gate_create(int32_t rows, int32_t window, float tau, int32_t d_mi
     ead_gate *g = new (std::nothrow) ead_gate();
     if (!g) return fail(nullptr, EAD_ERR_OOM, "host allocation failed");
     g->rows = rows; g->cfg = GateCfg{window, tau, d_min}; g->stream = (hipStream_t)hip_stream;
-    void *p[4] = {nullptr, nullptr, nullptr, nullptr};
-    const size_t sz[4] = {(size_t)rows * window * 4, (size_t)rows * 4, (size_t)rows * 4, (size_t)rows * 4};
-    for (int i = 0; i < 4; ++i) {
+    EntDevice *d = nullptr;
+    { const ead_status rc = entropy_device(&d); if (rc != EAD_OK) { delete g; return rc; } }
+    g->resident = d->resident;
+    const size_t steps_per_launch = std::max(1, std::min(kGateMaxSteps, kEntMaxRows / rows));
+    void *p[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    const size_t sz[5] = {(size_t)rows * window * 4, (size_t)rows * 4, (size_t)rows * 4, (size_t)rows * 4,
+                          steps_per_launch * rows * kEntMaxChunks * sizeof(EntPartial)};
+    for (int i = 0; i < 5; ++i) {
         if (hipMalloc(&p[i], sz[i]) != hipSuccess) { for (int j = 0; j < i; ++j) (void)hipFree(p[j]); delete g; return fail(nullptr, EAD_ERR_OOM, "hipMalloc failed"); }
         g->allocs.push_back(p[i]);
     }
     g->st.ring = (float *)p[0]; g->st.n = (int *)p[1]; g->st.c = (int *)p[2]; g->st.model = (int *)p[3];
+    g->part = (EntPartial *)p[4];
     *out = g;
     return ead_gate_reset(g);
 }
@@ -1596,8 +1660,10 @@ ead_status ead_gate_step_logits(ead_gate *g, const void *logits_dev, int32_t dty
                                 uint8_t *next_model_dev) {
     if (!g) return EAD_ERR_INVALID_ARG;
     if (unit != EAD_NATS && unit != EAD_BITS) return fail(nullptr, EAD_ERR_INVALID_ARG, "unit must be 0 or 1");
-    EntPartial *part = nullptr; int chunks = 0;
-    TRY(entropy_partials(&logits_dev, 1, dtype, g->rows, vocab, g->stream, &part, &chunks));
+    TRY(entropy_check(&logits_dev, 1, dtype, g->rows, vocab));
+    EntPartial *part = g->part; int chunks = 0, per = 0;
+    entropy_split(g->rows, vocab, &chunks, &per);
+    entropy_launch(&logits_dev, 1, dtype, g->rows, vocab, g->stream, part, g->resident);
     GateStepArgs a{};
     a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.steps = 1; a.partials = part; a.n_part = chunks; a.unit = unit;
     a.H_out = H_dev; a.argmax_out = argmax_dev;
@@ -1617,10 +1683,12 @@ ead_status ead_gate_run_logits(ead_gate *g, const void *const *logits_dev_list, 
     const int S = std::max(1, std::min(kGateMaxSteps, kEntMaxRows / g->rows));
     for (int s0 = 0; s0 < n_steps; s0 += S) {
         const int ns = std::min(S, n_steps - s0);
-        EntPartial *part = nullptr; int chunks = 0;
+        EntPartial *part = g->part; int chunks = 0, per = 0;
         const void *ptrs[kGateMaxSteps];
         for (int z = 0; z < ns; ++z) ptrs[z] = logits_dev_list[(s0 + z) % n_tensors];
-        TRY(entropy_partials(ptrs, ns, dtype, g->rows, vocab, g->stream, &part, &chunks));
+        TRY(entropy_check(ptrs, ns, dtype, g->rows, vocab));
+        entropy_split(g->rows, vocab, &chunks, &per);
+        entropy_launch(ptrs, ns, dtype, g->rows, vocab, g->stream, part, g->resident);
         GateStepArgs a{};
         a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.steps = ns; a.partials = part; a.n_part = chunks; a.unit = unit;
         const size_t o = (size_t)s0 * g->rows;

@@ -21,12 +21,6 @@
 
 namespace ead {
 
-#ifdef EAD_FUSED_TRACE
-#define EAD_TS(slot) do { if (threadIdx.x == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x - 1) && a.trace) a.trace[(blockIdx.x ? 4096 : 0) + (ts_n++)] = wall_clock64(); } while (0)
-#else
-#define EAD_TS(slot) do {} while (0)
-#endif
-
 constexpr int kFusedWaves = 8;
 constexpr int kFusedThreads = kFusedWaves * 64;
 constexpr long kFusedSpinLimit = 1L << 21;
@@ -104,7 +98,6 @@ struct FusedArgs {
     GridBar bar;
     FinArgs fin;
     int batch, n_mats;
-    long long *trace;                // optional timestamps (tracing builds only)
 };
 
 // ---- staging the activation vector of a phase into LDS ----------------------------------------
@@ -506,8 +499,6 @@ __global__ __launch_bounds__(kFusedThreads) void k_decode_fused(FusedArgs<WT> a)
     const int NQ = a.H * HD, NK = a.KV * HD;
     const int S = min(kFusedMaxSplits, max(1, (pos + 1 + 255) / 256));
     GridBar bar = a.bar;
-    int ts_n = 0; (void)ts_n;
-    EAD_TS(0);
     EntStat st; st.init();
 
     // phases: per layer QKV, attention, output projection, gate/up, down; then the LM head
@@ -516,14 +507,11 @@ __global__ __launch_bounds__(kFusedThreads) void k_decode_fused(FusedArgs<WT> a)
         const int kind = ph < 5 * a.L ? ph % 5 : 5, l = ph / 5;
         if (ph > 0) {
             bar_arrive(bar);
-            EAD_TS(2);
             if (!bar_wait(bar, &s_ok)) return;
-            EAD_TS(3);
         }
         if (kind == 1) {
             const FusedLayer<WT> ly = a.layers[l];
             fused_attention<WT, HD, G>(a, ly.kcache, ly.vcache, seq, pos, S, smem);
-            EAD_TS(1);
             continue;
         }
         LinArgs<WT> p{};
@@ -553,13 +541,11 @@ __global__ __launch_bounds__(kFusedThreads) void k_decode_fused(FusedArgs<WT> a)
             epi = EPI_LOGITS;
             p.Np = a.V; p.K = a.d; p.partials = a.lm_part;
         }
-        EAD_TS(1);
         const int mat = ph < 5 * a.L ? 4 * l + (kind == 0 ? 0 : kind - 1) : 4 * a.L;
         if ((int)blockIdx.x < __builtin_amdgcn_readfirstlane(s_mats[mat].NB)) {     // this workgroup has row blocks here
             cs.set(s_mats[mat], wave);
             fused_linear<WT>(p, epi, xs, xzero, red, cs, ic, A, B, par, st);
         }
-        EAD_TS(1);
         if (kind == 5 && tid < 16 * kFusedRbChunk) {      // one partial per (workgroup, chunk slot)
             p.partials = a.lm_part + (size_t)(tid >> 4) * gridDim.x;
             logits_flush<WT, true>(p, 0, true, st);

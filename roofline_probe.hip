@@ -1,16 +1,18 @@
-// Torch-free driver for hardware-counter runs: builds the Llama-1B / Llama-8B shaped pair
-// with constant weights straight through the C ABI, decodes a few single-row steps with
-// each model, and runs one plain copy kernel of known size as the reference point for
-// byte counters.  Values do not matter for traffic, only shapes do.
-//   rocprofv3 --pmc FETCH_SIZE --output-format csv -d out -- ./roofline_probe [steps] [batch] [prompt_len]
-// batch > 1 decodes that many identical rows together (the matrix-core path of the linear
-// layers), for counters of the batched kernels.
+// Torch-free driver for hardware-counter runs (built by `python bench.py --build-probe`): builds the
+// Llama-1B / Llama-8B or the Qwen-0.5B / Qwen-14B shaped pair with constant weights straight through
+// the C ABI, decodes a few steps with each model, and runs one plain copy kernel of known size as the
+// reference point for byte counters.  Values do not matter for traffic, only shapes do.
+//   rocprofv3 --pmc FETCH_SIZE --output-format csv -d out -- ./roofline_probe [pair] [steps] [batch] [prompt_len]
+// pair: llama (default) or qwen.  batch > 1 decodes that many identical rows together (the
+// matrix-core path of the linear layers), for counters of the batched kernels.
 #include <hip/hip_runtime.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <vector>
 
-#include "../../include/ead.h"
+#include <string.h>
+
+#include "include/ead.h"
 
 #define CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { fprintf(stderr, "%s: %s\n", #x, hipGetErrorString(e_)); exit(1); } } while (0)
 
@@ -62,13 +64,23 @@ static void build(const Shape &s, Built &b) {
 }
 
 int main(int argc, char **argv) {
-    const int steps = argc > 1 ? atoi(argv[1]) : 4;
-    const int batch = argc > 2 ? atoi(argv[2]) : 1;
-    const int prompt_len = argc > 3 ? atoi(argv[3]) : 512;
-    if (steps < 1 || batch < 1 || batch > 256 || prompt_len < 1 || prompt_len > 4096) { fprintf(stderr, "usage: roofline_probe [steps] [batch<=256] [prompt_len<=4096]\n"); return 2; }
+    const char *pair = argc > 1 ? argv[1] : "llama";
+    const int steps = argc > 2 ? atoi(argv[2]) : 4;
+    const int batch = argc > 3 ? atoi(argv[3]) : 1;
+    const int prompt_len = argc > 4 ? atoi(argv[4]) : 512;
+    const bool qwen = strcmp(pair, "qwen") == 0;
+    if ((!qwen && strcmp(pair, "llama") != 0) || steps < 1 || batch < 1 || batch > 256 || prompt_len < 1 || prompt_len > 4096) {
+        fprintf(stderr, "usage: roofline_probe [llama|qwen] [steps] [batch<=256] [prompt_len<=4096]\n"); return 2;
+    }
     Built S, L;
-    build(Shape{16, 2048, 32, 8, 8192, 128256, 1e-5f, 5e5f}, S);
-    build(Shape{32, 4096, 32, 8, 14336, 128256, 1e-5f, 5e5f}, L);
+    const int vocab = qwen ? 151936 : 128256;
+    if (qwen) {
+        build(Shape{24, 896, 14, 2, 4864, vocab, 1e-6f, 1e6f}, S);
+        build(Shape{48, 5120, 40, 8, 13824, vocab, 1e-6f, 1e6f}, L);
+    } else {
+        build(Shape{16, 2048, 32, 8, 8192, vocab, 1e-5f, 5e5f}, S);
+        build(Shape{32, 4096, 32, 8, 14336, vocab, 1e-5f, 5e5f}, L);
+    }
     CK(hipDeviceSynchronize());
     ead_params p{5, 1e30f, 10, EAD_NATS, batch, prompt_len + 2 * steps + 8, -1, nullptr};
     ead_handle *h = nullptr;
@@ -83,7 +95,7 @@ int main(int argc, char **argv) {
         CK(hipFree(a)); CK(hipFree(b));
     }
     std::vector<int32_t> prompt((size_t)prompt_len * batch);
-    for (size_t i = 0; i < prompt.size(); ++i) prompt[i] = (int32_t)((i * 7919) % 128256);
+    for (size_t i = 0; i < prompt.size(); ++i) prompt[i] = (int32_t)((i * 7919) % vocab);
     std::vector<int32_t> lens(batch, prompt_len);
     for (int which = 0; which < 2; ++which) {
         if (ead_force_model(h, which) != EAD_OK || ead_begin(h, prompt.data(), lens.data(), batch, steps) != EAD_OK ||

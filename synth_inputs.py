@@ -252,28 +252,39 @@ def weight_names(shape: ModelShape):
     yield "lm_head", (shape.vocab, d), "normal"
 
 
-def model_weights_np(shape: ModelShape, seed: int, std: float = 0.02) -> dict:
+def model_weights_np(shape: ModelShape, seed: int, std: float = 0.02, gain_std: float = 0.0,
+                     lm_std: float | None = None) -> dict:
     """All weights as float32 numpy arrays (bf16-rounded values for bf16 models).
 
-    Matrices are N(0, std^2); norm gains are 1 (float32, never rounded).
+    Matrices are N(0, std^2) (the LM head N(0, lm_std^2) if given); norm gains are 1, or
+    1 + N(0, gain_std^2) when gain_std > 0 (float32, never rounded).
     """
     out = {}
     for name, shp, kind in weight_names(shape):
         if kind == "ones":
             out[name] = np.ones(shp, dtype=np.float32)
+            if gain_std > 0:
+                out[name] = out[name] + normal_np(seed, f"{shape.name}/{name}", shp, gain_std)
+        elif name == "lm_head" and lm_std is not None:
+            out[name] = normal_np(seed, f"{shape.name}/{name}", shp, lm_std, bf16=shape.bf16)
         else:
             out[name] = normal_np(seed, f"{shape.name}/{name}", shp, std, bf16=shape.bf16)
     return out
 
 
-def model_weights_torch(shape: ModelShape, seed: int, device, std: float = 0.02) -> dict:
-    """All weights on `device`: matrices in the model dtype, gains in float32."""
+def model_weights_torch(shape: ModelShape, seed: int, device, std: float = 0.02, gain_std: float = 0.0,
+                        lm_std: float | None = None) -> dict:
+    """All weights on `device`: matrices in the model dtype, gains in float32 (same values as model_weights_np)."""
     import torch
     dt = torch.bfloat16 if shape.bf16 else torch.float32
     out = {}
     for name, shp, kind in weight_names(shape):
         if kind == "ones":
             out[name] = torch.ones(shp, dtype=torch.float32, device=device)
+            if gain_std > 0:
+                out[name] = out[name] + normal_torch(seed, f"{shape.name}/{name}", shp, gain_std, torch.float32, device)
+        elif name == "lm_head" and lm_std is not None:
+            out[name] = normal_torch(seed, f"{shape.name}/{name}", shp, lm_std, dt, device)
         else:
             out[name] = normal_torch(seed, f"{shape.name}/{name}", shp, std, dt, device)
     return out
