@@ -201,6 +201,18 @@ ead_status ead_replay(ead_handle *h, const int32_t *prompt_tokens, const int32_t
  * work overlaps on the GPU (different streams) race: issue them on one stream or wait in between. */
 ead_status ead_entropy_argmax(const void *logits_dev, int32_t dtype, int32_t rows, int32_t vocab,
                               int32_t unit, float *H_dev, int32_t *argmax_dev, void *hip_stream);
+/* The same computation for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid it): this entry point calls no
+ * allocation routine at all.  Its per-chunk statistics go to a 384 KB array that is part of
+ * the library's device image (one copy per GPU, held until the process ends), which bounds
+ * the input: rows * chunks <= 16384, where chunks = the number of pieces a row is cut into
+ * (10 at vocab 151936 and 64 rows; at most 64).  Larger inputs are rejected with
+ * EAD_ERR_INVALID_ARG and a message that names the limit.  Results are bit-identical to
+ * ead_entropy_argmax on the same input.  Every call on a GPU uses that GPU's one array:
+ * calls whose work overlaps on the GPU race, as above.  Nothing in it needs clearing
+ * between calls (every statistic a call reads it has written itself). */
+ead_status ead_entropy_argmax_static(const void *logits_dev, int32_t dtype, int32_t rows, int32_t vocab,
+                                     int32_t unit, float *H_dev, int32_t *argmax_dev, void *hip_stream);
 
 /* Rolling window + switch rule (Eq. 3-4) for `rows` independent sequences, state on device
  * (1 <= rows <= 4096).  A gate owns the scratch of its own entropy passes, so gates on

@@ -71,6 +71,7 @@ _SIGNATURES = {
     "ead_score": (C.c_int, [C.c_void_p, C.c_int32, _I32P, C.c_int32, _F32P, _F32P, _I32P]),
     "ead_replay": (C.c_int, [C.c_void_p, _I32P, _I32P, C.c_int32, C.c_int32, _I32P, _U8P, _I32P, _F32P, _F32P, _U8P]),
     "ead_entropy_argmax": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "ead_entropy_argmax_static": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "ead_gate_create": (C.c_int, [C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p, C.POINTER(C.c_void_p)]),
     "ead_gate_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "ead_gate_step_logits": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
@@ -284,9 +285,9 @@ class EAD:
         self._check(lib().ead_reset_stats(self._h))
 
 
-def entropy_argmax(logits, unit=NATS, out=None):
+def entropy_argmax(logits, unit=NATS, out=None, static=False):
     """Row-wise (H, argmax) of a CUDA logits tensor [rows, vocab] (bf16 or fp32).
-    out: (H, argmax) tensors to write into."""
+    out: (H, argmax) tensors to write into; static: the entry point that allocates nothing."""
     import torch
     assert logits.is_cuda and logits.is_contiguous() and logits.dim() == 2
     rows, V = logits.shape
@@ -294,7 +295,7 @@ def entropy_argmax(logits, unit=NATS, out=None):
         out = (torch.empty(rows, dtype=torch.float32, device=logits.device),
                torch.empty(rows, dtype=torch.int32, device=logits.device))
     H, am = out
-    fn = lib().ead_entropy_argmax
+    fn = lib().ead_entropy_argmax_static if static else lib().ead_entropy_argmax
     rc = fn(logits.data_ptr(), _dtype_code(logits), rows, V, unit, H.data_ptr(), am.data_ptr(), _stream_ptr())
     if rc:
         raise EadError(rc, (lib().ead_last_error(None) or b"").decode())

@@ -1119,19 +1119,24 @@ ead_status fetch_impl(ead_handle *h, int stride, int32_t *tok, uint8_t *mid, flo
 
 // ---- stand-alone entropy: where the partials of a pass go ----------------------------------
 // ead_entropy_argmax: a per-device buffer that the first call on a device allocates (kept until the
-// process ends).  A gate owns a buffer of its own.
+// process ends).  A gate owns a buffer of its own.  ead_entropy_argmax_static: the file-scope device
+// array below, for callers that must not allocate.
 constexpr int kEntMaxRows = 4096, kEntMaxChunks = 64;
+constexpr int kEntStaticPartials = 16384;              // rows * chunks a call of ead_entropy_argmax_static may need
 constexpr int kEntMaxDevices = 16;
+
+static __device__ __align__(256) unsigned char scratch[(size_t)kEntStaticPartials * sizeof(EntPartial)];
 
 struct EntDevice {                // per device, set up once by the first call on it
     bool ready = false;
     int resident = 1024;          // workgroups of k_entropy_partial the chip holds at once
+    EntPartial *static_part = nullptr;     // device address of `scratch` on this device
     EntPartial *heap_part = nullptr;       // ead_entropy_argmax's buffer, allocated on first use
 };
 EntDevice g_ent_dev[kEntMaxDevices];
 std::mutex g_ent_mutex;
 
-// Device record of the current device.
+// Device record of the current device; allocates nothing.
 ead_status entropy_device(EntDevice **out) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return fail(nullptr, EAD_ERR_NO_DEVICE, "no HIP device");
@@ -1139,6 +1144,11 @@ ead_status entropy_device(EntDevice **out) {
     std::lock_guard<std::mutex> lock(g_ent_mutex);
     EntDevice &d = g_ent_dev[dev];
     if (!d.ready) {
+        // every GPU holds its own copy of the array at its own address: ask with this device current
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(nullptr, EAD_ERR_DEVICE, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        d.static_part = (EntPartial *)p;
         int per_cu = 0;
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, dev) == hipSuccess &&
@@ -1582,7 +1592,7 @@ ead_status ead_profile_read(ead_handle *h, ead_kernel_profile *out, int32_t capa
 // ---- entropy / gate on their own ---------------------------------------------------------
 namespace {
 ead_status entropy_argmax_impl(const void *logits_dev, int32_t dtype, int32_t rows, int32_t vocab, int32_t unit,
-                               float *H_dev, int32_t *argmax_dev, hipStream_t st) {
+                               float *H_dev, int32_t *argmax_dev, hipStream_t st, bool use_static) {
     if (!H_dev) return fail(nullptr, EAD_ERR_INVALID_ARG, "H_dev is null");
     if (unit != EAD_NATS && unit != EAD_BITS) return fail(nullptr, EAD_ERR_INVALID_ARG, "unit must be 0 or 1");
     TRY(entropy_check(&logits_dev, 1, dtype, rows, vocab));
@@ -1591,7 +1601,14 @@ ead_status entropy_argmax_impl(const void *logits_dev, int32_t dtype, int32_t ro
     EntDevice *d = nullptr;
     TRY(entropy_device(&d));
     EntPartial *part = nullptr;
-    TRY(entropy_heap_scratch(d, &part));
+    if (use_static) {
+        if ((long)rows * chunks > kEntStaticPartials)
+            return fail(nullptr, EAD_ERR_INVALID_ARG, "rows * chunks = %d * %d exceeds the %d partials of the static scratch array",
+                        rows, chunks, kEntStaticPartials);
+        part = d->static_part;
+    } else {
+        TRY(entropy_heap_scratch(d, &part));
+    }
     entropy_launch(&logits_dev, 1, dtype, rows, vocab, st, part, d->resident);
     hipLaunchKernelGGL(k_entropy_finalize, dim3(rows), dim3(64), 0, st, part, chunks, rows, unit, H_dev, argmax_dev);
     if (hipGetLastError() != hipSuccess) return fail(nullptr, EAD_ERR_DEVICE, "kernel launch failed");
@@ -1601,7 +1618,12 @@ ead_status entropy_argmax_impl(const void *logits_dev, int32_t dtype, int32_t ro
 
 ead_status ead_entropy_argmax(const void *logits_dev, int32_t dtype, int32_t rows, int32_t vocab, int32_t unit,
                               float *H_dev, int32_t *argmax_dev, void *hip_stream) {
-    return entropy_argmax_impl(logits_dev, dtype, rows, vocab, unit, H_dev, argmax_dev, (hipStream_t)hip_stream);
+    return entropy_argmax_impl(logits_dev, dtype, rows, vocab, unit, H_dev, argmax_dev, (hipStream_t)hip_stream, false);
+}
+
+ead_status ead_entropy_argmax_static(const void *logits_dev, int32_t dtype, int32_t rows, int32_t vocab, int32_t unit,
+                                     float *H_dev, int32_t *argmax_dev, void *hip_stream) {
+    return entropy_argmax_impl(logits_dev, dtype, rows, vocab, unit, H_dev, argmax_dev, (hipStream_t)hip_stream, true);
 }
 
 ead_status ead_gate_create(int32_t rows, int32_t window, float tau, int32_t d_min, void *hip_stream, ead_gate **out) {
