@@ -61,12 +61,15 @@ def make_prompts(seed, batch, lo, hi, vocab):
     return [si.prompt_np(seed, f"row{b}", int(lens[b]), vocab) for b in range(batch)]
 
 
-def run_lengths(max_prompt, settle, warmup, steps, profile_steps, n_cal):
-    """Tokens every leg of a run generates per row, and the max_seq a handle needs to hold the longest
-    of them.  The profiling leg never runs longer than the timed one."""
+def run_lengths(max_prompt, settle, warmup, steps, profile_steps, n_cal, lead=0):
+    """Tokens every leg of a run may generate per row, and the max_seq a handle needs to hold the longest
+    of them.  The profiling leg never runs longer than the timed one.  lead: how far a row of a free-running
+    batch may get ahead of the slowest one (0: rows move in steps); such a row must still not reach the end
+    of its run inside the timed region, so its bound lies a lead (and a few passes' overshoot) further."""
     profile_steps = max(1, min(profile_steps, steps))
-    timed_new = settle + warmup + steps
-    profile_new = settle + warmup + profile_steps
+    margin = lead + 8 if lead else 0
+    timed_new = settle + warmup + steps + margin
+    profile_new = settle + warmup + profile_steps + margin
     return {"timed_new": timed_new, "profile_new": profile_new, "profile_steps": profile_steps, "cal_new": n_cal,
             "max_seq": max_prompt + max(timed_new, profile_new, n_cal) + 8}
 
@@ -125,26 +128,34 @@ def host_cpu():
     return name, (len(cores) or None)
 
 
-def cpu_baseline(pair_shapes, Ws, Wl, prompts, w, tau, d_min, n_prompt, n_new):
-    """The oracle as it stands, timed on this host: Algorithm 1 on a bounded sample (first row, prompt cut
-    to n_prompt tokens, n_new generated tokens after the first, same w / tau / d_min); prompt handling is
-    subtracted by timing a 1-token run first."""
+def cpu_baseline(pair_shapes, Ws, Wl, prompts, w, tau, d_min, n_prompt, n_new, budget_s=20.0, max_rows=8):
+    """The oracle as it stands, timed on this host: Algorithm 1 on a bounded sample of the workload -- the
+    first rows of the batch one after the other (the oracle has no batching), each with its prompt cut to
+    n_prompt tokens and n_new generated tokens after the first, same w / tau / d_min, until budget_s
+    seconds of oracle time are spent or max_rows rows are done.  A row's prompt handling is subtracted by
+    timing a 1-token run of it first.  Rows that switch make the large model consume every earlier token,
+    so the sample's rate depends on how many of its rows switch: the share is reported with it."""
     import oracle
     ss, sl = pair_shapes
     t0 = time.time()
     os_ = oracle.Model(ss, {k: v.float().cpu().numpy() for k, v in Ws.items()})
     ol = oracle.Model(sl, {k: v.float().cpu().numpy() for k, v in Wl.items()})
     log(f"[cpu_baseline] fp32 weights on the host in {time.time() - t0:.1f}s")
-    prompt = prompts[0][:n_prompt]
-    t0 = time.time(); oracle.generate(os_, ol, prompt, 1, w, tau, d_min); t1 = time.time()
-    out = oracle.generate(os_, ol, prompt, n_new + 1, w, tau, d_min); t2 = time.time()
-    dt = max((t2 - t1) - (t1 - t0), 1e-9)
+    spent, n_tok, n_large, rows = 0.0, 0, 0, 0
+    for prompt in prompts[:max_rows]:
+        prompt = prompt[:n_prompt]
+        ta = time.time(); oracle.generate(os_, ol, prompt, 1, w, tau, d_min); tb = time.time()
+        out = oracle.generate(os_, ol, prompt, n_new + 1, w, tau, d_min); tc = time.time()
+        spent += max((tc - tb) - (tb - ta), 1e-9)
+        n_tok += n_new; n_large += int(out["model_id"][1:].sum()); rows += 1
+        if spent >= budget_s:
+            break
     name, phys = host_cpu()
-    return {"value": n_new / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "cpu_model": name, "physical_cores_on_host": phys, "seconds": t2 - t0,
-            "sample": f"row 0, prompt cut to {len(prompt)} tokens, {n_new} generated tokens after the first, batch 1, "
-                      f"same w/tau/d_min; large-model share of the sample's tokens {float(out['model_id'][1:].mean()):.2f} "
-                      f"(a switch makes the large model consume every earlier token first)"}
+    return {"value": n_tok / spent, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "cpu_model": name, "physical_cores_on_host": phys, "oracle_seconds": spent,
+            "sample": f"rows 0-{rows - 1} one after the other, prompts cut to {n_prompt} tokens, {n_new} generated tokens "
+                      f"after the first per row, same w/tau/d_min; large-model share of the sample's tokens "
+                      f"{n_large / max(n_tok, 1):.2f}"}
 
 
 def measured_traffic(workload, kernel):
@@ -307,6 +318,9 @@ def main():
                     help="grouped (default for batches): small-model rows run ahead, large-model rows are served together")
     ap.add_argument("--sched-start", type=float, default=0.5, help="grouped: large model starts at this share of waiting rows")
     ap.add_argument("--sched-stop", type=float, default=0.25, help="grouped: ... and stops below this share")
+    ap.add_argument("--lead", type=int, default=64,
+                    help="grouped: rows run freely, none more than this many tokens ahead of the slowest (a step is then "
+                         "one token per row of batch progress: batch tokens in total); 0: every row exactly one token per step")
     ap.add_argument("--temperature", type=float, default=0.0, help="sample at this temperature (0 = greedy, the default)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for hardware byte counters)")
@@ -341,7 +355,8 @@ def main():
     log(f"[bench] weights generated in {time.time() - t0:.1f}s")
     prompts = make_prompts(args.seed, batch, plo, phi, ss.vocab)
     n_cal = 64 if batch > 1 else 96
-    ln = run_lengths(max(len(p) for p in prompts), settle, warmup, steps, args.profile_steps, n_cal)
+    lead = args.lead if grouped else 0
+    ln = run_lengths(max(len(p) for p in prompts), settle, warmup, steps, args.profile_steps, n_cal, lead)
     e = ead.EAD(ss, Ws, sl, Wl, window=w, tau=0.0, d_min=d_min, max_batch=batch, max_seq=ln["max_seq"])
     if args.no_cpu_baseline:
         del Ws, Wl
@@ -372,7 +387,9 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if ss.bf16 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "small": ss.name, "large": sl.name, "batch": batch,
                    "prompt_len": [int(plo), int(phi)], "window": w, "d_min": d_min, "tau_nats": None, "tau_rule": list(rule),
-                   "vocab": ss.vocab, "schedule": schedule, "temperature": args.temperature, "settle_steps": settle},
+                   "vocab": ss.vocab, "schedule": schedule, "temperature": args.temperature, "settle_steps": settle,
+                   "step": ("free-running rows: a step is one token per row of batch progress (batch tokens), no row more than "
+                            f"{lead} tokens ahead of the slowest") if lead else "one token for every row"},
         "prefill_s": prefill_s, "roofline": None, "cpu_baseline": None,
     }
     errors = {}
@@ -386,18 +403,26 @@ def main():
             log(f"[bench] leg '{name}' failed: {errors[name]}")
             return None
 
+    def advance(n_steps, free):
+        """n_steps steps of the batch: one token per row and step, or (free-running rows) batch tokens per step."""
+        if free:
+            e.decode_tokens(n_steps * batch, lead)
+        else:
+            e.decode(n_steps)
+
     def timed(force, grp):
+        free = grp and lead > 0
         e.force_model(force)
         e.set_schedule(grp, args.sched_start, args.sched_stop)
         e.set_gate(w, tau, d_min)
         e.rewind(ln["timed_new"])
         if settle:
-            e.decode(settle)
-        e.decode(warmup)
+            advance(settle, free)
+        advance(warmup, free)
         e.reset_stats()
         torch.cuda.synchronize()
         a = time.perf_counter()
-        e.decode(steps)
+        advance(steps, free)
         torch.cuda.synchronize()
         dt = time.perf_counter() - a
         st = e.stats()
@@ -423,12 +448,12 @@ def main():
         dt, st = timed(-1, grouped)
         n_tok = st["tokens_small"] + st["tokens_large"]
         algo_gbs = st["algorithmic_bytes"] / dt / 1e9
-        out.update({"value": n_tok / dt, "ms_per_step": 1e3 * dt / steps,
+        out.update({"value": n_tok / dt, "ms_per_step": 1e3 * dt / (n_tok / batch), "tokens_timed": n_tok,
                     "decode_hbm_gbs": algo_gbs, "decode_hbm_frac_of_peak": algo_gbs / HBM_PEAK_GBS,
                     "large_token_share": st["large_share"], "param_ratio": st["param_ratio"], "switches": st["switches"],
                     "host_syncs": st["host_syncs"]})
         if grouped:
-            out["grouped"] = {"start": args.sched_start, "stop": args.sched_stop, "large_passes": st["steps_large"],
+            out["grouped"] = {"start": args.sched_start, "stop": args.sched_stop, "max_lead": lead, "large_passes": st["steps_large"],
                               "small_passes": st["steps_small"], "catchup_rows_large": st["catchup_rows_large"]}
         log(f"[bench] EAD ({schedule}): {n_tok / dt:.1f} tok/s, {algo_gbs:.0f} GB/s algorithmic ({algo_gbs / HBM_PEAK_GBS:.1%} of peak), "
             f"large share {st['large_share']:.3f}, switches {st['switches']}, host syncs {st['host_syncs']}, "
@@ -453,11 +478,12 @@ def main():
         e.set_schedule(grouped, args.sched_start, args.sched_stop)
         e.set_gate(w, tau, d_min)
         e.rewind(ln["profile_new"])
+        free = grouped and lead > 0
         if settle:
-            e.decode(settle)
-        e.decode(warmup)
+            advance(settle, free)
+        advance(warmup, free)
         e.profile(True)
-        e.decode(ln["profile_steps"])
+        advance(ln["profile_steps"], free)
         prof = e.profile_read()
         e.profile(False)
         e.set_schedule(False)

@@ -162,6 +162,14 @@ ead_status ead_rewind(ead_handle *h, int32_t max_new_tokens);
  * (one token per row per step, including any catch-up the active model needs).
  * Returns after the last step's work has finished on the GPU. */
 ead_status ead_decode(ead_handle *h, int32_t n_steps);
+/* Free-running batch: rows are independent instances of Algorithm 1, so nothing forces them to move in
+ * steps.  Runs the grouped schedule (see ead_set_schedule; its start / stop fractions apply) until the batch
+ * as a whole has produced at least n_tokens more tokens, every row free to go on as far as max_lead tokens
+ * ahead of the unfinished row that has produced the fewest (and never past the run's max_new_tokens).  No new
+ * forward pass is started once the count is reached; passes in flight finish, so a few more tokens than
+ * asked for may come out (ead_get_stats counts them).  Per row the tokens are those ead_decode would have
+ * produced (up to the rounding differences between passes of different width).  Batches of up to 512. */
+ead_status ead_decode_tokens(ead_handle *h, int64_t n_tokens, int32_t max_lead);
 /* Copy what has been generated so far to host buffers laid out as in
  * ead_generate with row stride `stride` (>= tokens generated). Any pointer may be NULL. */
 ead_status ead_fetch(ead_handle *h, int32_t stride, int32_t *out_tokens, uint8_t *out_model_id,

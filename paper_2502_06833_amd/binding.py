@@ -67,6 +67,7 @@ _SIGNATURES = {
     "ead_begin": (C.c_int, [C.c_void_p, _I32P, _I32P, C.c_int32, C.c_int32]),
     "ead_rewind": (C.c_int, [C.c_void_p, C.c_int32]),
     "ead_decode": (C.c_int, [C.c_void_p, C.c_int32]),
+    "ead_decode_tokens": (C.c_int, [C.c_void_p, C.c_int64, C.c_int32]),
     "ead_fetch": (C.c_int, [C.c_void_p, C.c_int32, _I32P, _U8P, _F32P, _F32P, _I32P]),
     "ead_score": (C.c_int, [C.c_void_p, C.c_int32, _I32P, C.c_int32, _F32P, _F32P, _I32P]),
     "ead_replay": (C.c_int, [C.c_void_p, _I32P, _I32P, C.c_int32, C.c_int32, _I32P, _U8P, _I32P, _F32P, _F32P, _U8P]),
@@ -226,6 +227,9 @@ class EAD:
 
     def decode(self, n_steps: int):
         self._check(lib().ead_decode(self._h, n_steps))
+
+    def decode_tokens(self, n_tokens: int, max_lead: int = 64):
+        self._check(lib().ead_decode_tokens(self._h, n_tokens, max_lead))
 
     def fetch(self):
         B, max_new = self._B, self._max_new

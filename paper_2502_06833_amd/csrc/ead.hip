@@ -452,16 +452,21 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
         // sweep, or one workgroup per (group, sweep) where K is not split.
         // (17-32 rows: measured better for the split-K matrices, 32 against 34 us, not for gate/up, 72 against 69)
         if (big && (TB > 2 || (TB == 2 && EPI != EPI_SWIGLU))) {
-            const int NG = (NB + 7) / 8, nt = TB > 4 ? kWideTok : 4;
-            if (cfg == 4 && EPI != EPI_QKV) {
+            // token blocks per sweep: four up to 64 rows; the pass's own five to eight for 65-128 rows, one
+            // wave per block; eight (two per wave) for the sweeps of longer passes
+            const bool multi = TB > kWideTok;
+            const int NG = (NB + 7) / 8, nt = TB <= 4 ? 4 : (multi ? kWideTok : TB);
+            if constexpr (EPI != EPI_QKV) if (cfg == 4) {
                 // seven row blocks per workgroup where that still fits one workgroup per compute unit
                 // (1728 row blocks: 247 workgroups instead of 216 on 256 units)
                 const int rg = (NB + 6) / 7 <= h->n_cu ? 7 : 8, ng = (NB + rg - 1) / rg;
                 a.sweeps = (TB + nt - 1) / nt;
                 const int grid_wt = a.sweeps > 1 ? (ng + 7) / 8 * 8 * a.sweeps : ng;
-#define EAD_WT(TPW_, RG_) hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, TPW_, RG_>), dim3(grid_wt), dim3(256), 0, h->stream, a)
-                if (nt == 4) { if (rg == 7) EAD_WT(1, 7); else EAD_WT(1, 8); }
-                else { if (rg == 7) EAD_WT(2, 7); else EAD_WT(2, 8); }
+#define EAD_WT(TPW_, NW_) do { if (rg == 7) hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, TPW_, 7, NW_>), dim3(grid_wt), dim3(NW_ * 64), 0, h->stream, a); \
+                               else hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, TPW_, 8, NW_>), dim3(grid_wt), dim3(NW_ * 64), 0, h->stream, a); } while (0)
+                if (multi) EAD_WT(2, 4);
+                else switch (nt) { case 4: EAD_WT(1, 4); break; case 5: EAD_WT(1, 5); break; case 6: EAD_WT(1, 6); break;
+                                   case 7: EAD_WT(1, 7); break; default: EAD_WT(1, 8); break; }
 #undef EAD_WT
                 return;
             }
@@ -470,15 +475,14 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
             while (KS > 1 && (a.K / 32) / KS < 16) --KS;
             if (KS > 1 && (size_t)KS * NG * 8 * nt * 256 <= kSplitKFloats) {
                 a.KS = KS; a.sk_part = h->sk_part;
+#define EAD_SK(TPW_, NW_) do { hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, true, TPW_, 8, NW_>), dim3(NG * KS), dim3(NW_ * 64), 0, h->stream, a); \
+                               hipLaunchKernelGGL((k_sk_merge<EPI, TPW_ * NW_>), dim3((NB * TPW_ * NW_ + 3) / 4), dim3(256), 0, h->stream, a, NG * 8); } while (0)
                 for (a.tb_base = 0; a.tb_base < TB; a.tb_base += nt) {
-                    if (nt == 4) {
-                        hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, true, 1>), dim3(NG * KS), dim3(256), 0, h->stream, a);
-                        hipLaunchKernelGGL((k_sk_merge<EPI, 4>), dim3((NB * 4 + 3) / 4), dim3(256), 0, h->stream, a, NG * 8);
-                    } else {
-                        hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, true, 2>), dim3(NG * KS), dim3(256), 0, h->stream, a);
-                        hipLaunchKernelGGL((k_sk_merge<EPI, kWideTok>), dim3((NB * kWideTok + 3) / 4), dim3(256), 0, h->stream, a, NG * 8);
-                    }
+                    if (multi) EAD_SK(2, 4);
+                    else switch (nt) { case 4: EAD_SK(1, 4); break; case 5: EAD_SK(1, 5); break; case 6: EAD_SK(1, 6); break;
+                                       case 7: EAD_SK(1, 7); break; default: EAD_SK(1, 8); break; }
                 }
+#undef EAD_SK
                 return;
             }
         }
@@ -931,19 +935,37 @@ ead_status after_tokens(ead_handle *h, const std::vector<char> &emitted, bool al
 // token position.  The large model starts running when at least `hi` of the unfinished rows
 // wait for it and keeps running until fewer than `lo` do (rows stay on it for at least d_min
 // tokens, so its passes come in bursts).  No row's arithmetic depends on the schedule.
-ead_status decode_grouped(ead_handle *h, int n_tokens) {
+// budget < 0: every row produces up to n_tokens more tokens (per-sequence goals).  budget >= 0: the batch as a
+// whole produces at least `budget` more tokens; rows run freely, none more than `lead` tokens ahead of the
+// unfinished row that has produced the fewest, and no pass is started once the budget is met.
+ead_status decode_grouped(ead_handle *h, int n_tokens, long budget = -1, int lead = 0) {
     use_lane(h, 0);
     hipStream_t st = h->stream;
     std::vector<int> goal(h->s.max_batch, 0);
-    for (int b = 0; b < h->batch; ++b) {
-        HostSeq &s = h->hs[b];
-        s.goal = (int)std::min<long>(h->max_new, (long)s.ngen + n_tokens);
-        goal[b] = s.goal;
+    const bool by_budget = budget >= 0;
+    const long produced0 = h->stats.tokens_small + h->stats.tokens_large;
+    auto exhausted = [&]() { return by_budget && h->stats.tokens_small + h->stats.tokens_large - produced0 >= budget; };
+    // budget mode: the host's copy of the goals follows the slowest row; the device's stay at the bound of the
+    // run, and every pass names its sequences to the plan kernel
+    auto update_goals = [&]() {
+        if (!by_budget) return;
+        int lo = h->max_new;
+        for (int b = 0; b < h->batch; ++b) if (!h->hs[b].done) lo = std::min(lo, h->hs[b].ngen);
+        for (int b = 0; b < h->batch; ++b) h->hs[b].goal = (int)std::min<long>(h->max_new, (long)lo + lead);
+    };
+    if (!by_budget) {
+        for (int b = 0; b < h->batch; ++b) {
+            HostSeq &s = h->hs[b];
+            s.goal = (int)std::min<long>(h->max_new, (long)s.ngen + n_tokens);
+            goal[b] = s.goal;
+        }
+        HIP_TRY(h, hipMemcpyAsync(h->s.goal, goal.data(), h->s.max_batch * sizeof(int), hipMemcpyHostToDevice, st));
+        HIP_TRY(h, hipStreamSynchronize(st));      // `goal` leaves scope; the other lane starts after this too
     }
-    HIP_TRY(h, hipMemcpyAsync(h->s.goal, goal.data(), h->s.max_batch * sizeof(int), hipMemcpyHostToDevice, st));
-    HIP_TRY(h, hipStreamSynchronize(st));      // `goal` leaves scope; the other lane starts after this too
     auto waiting = [&](int n[2]) {
+        update_goals();
         n[0] = n[1] = 0;
+        if (exhausted()) return;
         for (int b = 0; b < h->batch; ++b) {
             const HostSeq &s = h->hs[b];
             if (!s.done && s.ngen < s.goal) n[s.model ? 1 : 0]++;
@@ -1033,18 +1055,20 @@ ead_status decode_grouped(ead_handle *h, int n_tokens) {
     }
     // pauses end here: rows may run to the bound of the run again
     for (int b = 0; b < h->batch; ++b) { h->hs[b].goal = h->max_new; goal[b] = h->max_new; }
-    HIP_TRY(h, hipMemcpyAsync(h->s.goal, goal.data(), h->s.max_batch * sizeof(int), hipMemcpyHostToDevice, st));
-    HIP_TRY(h, hipStreamSynchronize(st));
+    if (!by_budget) {
+        HIP_TRY(h, hipMemcpyAsync(h->s.goal, goal.data(), h->s.max_batch * sizeof(int), hipMemcpyHostToDevice, st));
+        HIP_TRY(h, hipStreamSynchronize(st));
+    }
     return EAD_OK;
 }
 
-ead_status decode_impl(ead_handle *h, int n_steps) {
+ead_status decode_impl(ead_handle *h, int n_steps, long budget = -1, int lead = 0) {
     if (!h->began) return fail(h, EAD_ERR_STATE, "ead_decode before ead_begin");
     use_lane(h, 0);
     hipStream_t st = h->stream;
     std::vector<char> emitted(h->batch);
-    if (h->sched_grouped) {
-        TRY(decode_grouped(h, n_steps));
+    if (h->sched_grouped || budget >= 0) {
+        TRY(decode_grouped(h, n_steps, budget, lead));
         n_steps = 0;
     }
     bool used_prev[2] = {false, false};
@@ -1422,6 +1446,14 @@ ead_status ead_decode(ead_handle *h, int32_t n_steps) {
     if (!h) return EAD_ERR_INVALID_ARG;
     if (n_steps < 0) return fail(h, EAD_ERR_INVALID_ARG, "n_steps < 0");
     return decode_impl(h, n_steps);
+}
+
+ead_status ead_decode_tokens(ead_handle *h, int64_t n_tokens, int32_t max_lead) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    if (n_tokens < 0 || max_lead < 1) return fail(h, EAD_ERR_INVALID_ARG, "need n_tokens >= 0 and max_lead >= 1");
+    if (h->prm.max_batch > 64 * kAllowWords) return fail(h, EAD_ERR_INVALID_ARG, "ead_decode_tokens serves batches of up to %d sequences", 64 * kAllowWords);
+    if (h->replay) return fail(h, EAD_ERR_STATE, "ead_decode_tokens inside a replay");
+    return decode_impl(h, 0, (long)n_tokens, max_lead);
 }
 
 ead_status ead_fetch(ead_handle *h, int32_t stride, int32_t *out_tokens, uint8_t *out_model_id, float *out_entropy,

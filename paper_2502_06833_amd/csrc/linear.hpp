@@ -532,19 +532,22 @@ __device__ __forceinline__ void block_epilogue(const LinArgs<bf16_t> &a, float (
 constexpr int kWideTok = 8;          // token blocks (of 16 rows) per sweep
 
 // Passes of more than 32 rows: a workgroup takes RG (8; 7 where that fills the compute units better)
-// row blocks and 64 TPW token rows per sweep; each of its four waves owns TPW (1 or 2) token blocks
-// and all RG row blocks.  A wave's activation fragments (hi and lo
-// of its two blocks) come straight from memory in the matrix cores' operand layout and are never
-// shared; the step's 8 weight tiles, of which each wave fetches two, go through LDS (8 KB read per
+// row blocks and 16 NW TPW token rows per sweep; each of its NW waves owns TPW (1 or 2) token blocks
+// and all RG row blocks.  NW follows the pass: four waves for up to 64 rows (TPW = 1) and for sweeps of
+// 128 (TPW = 2), five to eight waves with one block each for 65-128 rows, so that a pass of 72 rows
+// multiplies and fetches five blocks' worth, not eight.  A wave's activation fragments (hi and lo
+// of its blocks) come straight from memory in the matrix cores' operand layout and are never
+// shared; the step's RG weight tiles, of which each wave fetches at most two, go through LDS (8 KB read per
 // wave and step; sharing the activation tiles instead, with a row-block pair per wave, reads 16 KB
-// and is no faster).  SK: workgroup (g, ks) takes slab ks of K for group g (one sweep only: TB <= 8)
+// and is no faster).  SK: workgroup (g, ks) takes slab ks of K for group g (one sweep only: TB <= NW TPW)
 // and leaves its sums in memory for k_sk_merge.
-template <int DA, int EPI, bool SK = false, int TPW = 2, int RG = 8>
-__global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
-    static_assert(RG >= 5 && RG <= 8, "each wave fetches two of the workgroup's weight tiles");
-    constexpr int NT = 4 * TPW;                        // token blocks per sweep (TPW per wave); RG row blocks per workgroup
+template <int DA, int EPI, bool SK = false, int TPW = 2, int RG = 8, int NW = 4>
+__global__ __launch_bounds__(NW * 64) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
+    static_assert(RG >= 5 && RG <= 8 && NW >= 4 && NW <= 8, "each wave fetches at most two of the workgroup's weight tiles");
+    constexpr int NT = NW * TPW;                       // token blocks per sweep (TPW per wave); RG row blocks per workgroup
+    constexpr int WPT = (RG + NW - 1) / NW;            // weight tiles a wave fetches per step: tiles wave, wave + NW
     __shared__ __attribute__((aligned(16))) bf16_t s_w[2][8][512];
-    __shared__ __attribute__((aligned(16))) float s_t[4][64][4];
+    __shared__ __attribute__((aligned(16))) float s_t[NW][64][4];
     const int K = a.K, KCfull = K >> 5, NB = a.Np >> 4, NG = (NB + RG - 1) / RG;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -566,25 +569,25 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
 
     for (int tb0 = tb_first; tb0 < TB; tb0 += one_sweep ? TB : NT) {
         f32x4_t acc[RG][TPW];
-        const bf16_t *wp[2], *bp[2 * TPW];
+        const bf16_t *wp[WPT], *bp[2 * TPW];
 #pragma unroll
         for (int j = 0; j < RG; ++j)
 #pragma unroll
             for (int q = 0; q < TPW; ++q) acc[j][q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
-            wp[q] = a.W + tile_offset(min(g * RG + min(wave * 2 + q, RG - 1), NB - 1), kbase, KCfull) + lane * 8;   // RG < 8: the last tile twice
+        for (int q = 0; q < WPT; ++q)      // a wave whose second tile would lie past RG fetches the last tile again and drops it
+            wp[q] = a.W + tile_offset(min(g * RG + min(wave + q * NW, RG - 1), NB - 1), kbase, KCfull) + lane * 8;
 #pragma unroll
         for (int q = 0; q < TPW; ++q) {
             const int blk = min(tb0 + wave * TPW + q, TB - 1);
             bp[q] = a.xp_lo + act_tile_offset(blk, kbase, TB) + lane * 8;          // lo of block q, then hi
             bp[TPW + q] = a.xp + act_tile_offset(blk, kbase, TB) + lane * 8;
         }
-        Vec8<bf16_t> wa[DA][2], ba[DA][2 * TPW];
+        Vec8<bf16_t> wa[DA][WPT], ba[DA][2 * TPW];
         auto issue = [&](int s, int i) __attribute__((always_inline)) {
             const size_t off = (size_t)min(i, KC - 1) * 512;
 #pragma unroll
-            for (int q = 0; q < 2; ++q) wa[s][q].load_stream(wp[q] + off);
+            for (int q = 0; q < WPT; ++q) wa[s][q].load_stream(wp[q] + off);
 #pragma unroll
             for (int q = 0; q < 2 * TPW; ++q) ba[s][q].load(bp[q] + off * TB);
         };
@@ -600,14 +603,15 @@ __global__ __launch_bounds__(256) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
                 if (i < KC) {                                  // uniform over the workgroup
                     bf16_t (*buf)[512] = s_w[i & 1];
 #pragma unroll
-                    for (int q = 0; q < 2; ++q)
-                        *reinterpret_cast<u32x4_t *>(&buf[wave * 2 + q][lane * 8]) = wa[s][q].raw;
+                    for (int q = 0; q < WPT; ++q)
+                        if (wave + q * NW < RG)                // uniform over the wave
+                            *reinterpret_cast<u32x4_t *>(&buf[wave + q * NW][lane * 8]) = wa[s][q].raw;
                     __syncthreads();
                     u32x4_t fw[RG];
 #pragma unroll
                     for (int j = 0; j < RG; ++j) fw[j] = *reinterpret_cast<const u32x4_t *>(&buf[j][lane * 8]);
                     __builtin_amdgcn_sched_barrier(0);
-                    // lo products of all 16 accumulators, then the hi products: neighbouring
+                    // lo products of all accumulators, then the hi products: neighbouring
                     // products never wait for each other's result
 #pragma unroll
                     for (int h = 0; h < 2; ++h)

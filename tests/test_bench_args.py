@@ -7,6 +7,11 @@ import bench
 def test_run_lengths_cover_every_leg():
     for max_prompt, settle, warmup, steps, prof, n_cal in itertools.product(
             (1, 16, 512, 1024), (0, 32), (0, 5, 16), (1, 20, 64, 1024), (1, 64, 200), (64, 96)):
+        for lead in (0, 64):
+            free = bench.run_lengths(max_prompt, settle, warmup, steps, prof, n_cal, lead)
+            # a free-running row may be `lead` tokens ahead of the slowest when the timed region ends
+            assert free["timed_new"] >= settle + warmup + steps + lead
+            assert max_prompt + free["timed_new"] <= free["max_seq"] and max_prompt + free["profile_new"] <= free["max_seq"]
         ln = bench.run_lengths(max_prompt, settle, warmup, steps, prof, n_cal)
         # no leg (timed run, per-kernel timing run, calibration runs) may ask for more tokens than the handle holds
         for leg_new in (ln["timed_new"], ln["profile_new"], ln["cal_new"]):

@@ -199,6 +199,25 @@ def test_grouped_schedule_gives_the_same_rows(tiny):
         got = e.fetch()
         assert (got["tokens"] == lock["tokens"]).all() and (got["model_id"] == lock["model_id"]).all()
         assert (got["lens"] == 48).all()
+        # free-running rows (ead_decode_tokens): token budgets for the batch as a whole, no row more than
+        # `lead` tokens ahead of the slowest; the rows still come out the same
+        for lead, budget in ((5, 23), (64, 50), (1, 4)):
+            e.begin(prompts, 48)
+            total = 0
+            for _ in range(400):
+                e.decode_tokens(budget, lead)
+                part = e.fetch()
+                assert part["lens"].sum() >= min(total + budget, 4 * 48), (lead, budget)
+                total = int(part["lens"].sum())
+                unfinished = part["lens"][part["lens"] < 48]
+                if len(unfinished):
+                    assert part["lens"].max() - unfinished.min() <= lead + 1, (lead, part["lens"])   # + 1: a pass in flight
+                if (part["lens"] == 48).all():
+                    break
+            assert (part["lens"] == 48).all(), (lead, budget)
+            assert (part["tokens"] == lock["tokens"]).all() and (part["model_id"] == lock["model_id"]).all(), (lead, budget)
+            st = e.stats()
+            assert st["tokens_small"] + st["tokens_large"] == 4 * 48
     finally:
         e.set_schedule(False)
 
