@@ -177,6 +177,7 @@ struct ead_handle {
     ead_params prm;
     hipStream_t stream;
     int Tmax, items_max, lm_grid, score_rows, n_cu = 256;
+    size_t lds_per_block = 65536;        // most LDS one workgroup may ask for on this device
     SeqState s; Plan plan; GateCfg cfg;
     // scratch
     float *x, *q, *o, *hbuf; bf16_t *xp_a, *xp_o, *xp_h, *xl_a, *xl_o, *xl_h;
@@ -437,6 +438,26 @@ constexpr float kSmallLaneMin = 0.3f;                  // grouped schedule, two 
 constexpr int kSplitKGroups = 4096;                     // arrival counters
 constexpr size_t kSplitKFloats = (size_t)8 << 20;      // partial sums: KS slabs of (padded Np) x 128 floats at most
 
+// Kernels that ask for more than 64 KB of dynamic LDS have to say so once.
+std::mutex g_lds_attr_mutex;
+bool allow_big_lds(const void *kernel, size_t bytes) {
+    static std::vector<const void *> done;
+    std::lock_guard<std::mutex> lock(g_lds_attr_mutex);
+    if (std::find(done.begin(), done.end(), kernel) != done.end()) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) { (void)hipGetLastError(); return false; }
+    done.push_back(kernel);
+    return true;
+}
+
+template <int EPI, bool SK, int NW, int RG>
+bool launch_ls(ead_handle *h, const LinArgs<bf16_t> &a, int grid) {
+    const void *kern = (const void *)k_linear_mfma_ls<EPI, SK, NW, RG>;
+    const size_t lds = kLsLdsBytes(NW);
+    if (lds > h->lds_per_block || !allow_big_lds(kern, lds)) return false;
+    hipLaunchKernelGGL((k_linear_mfma_ls<EPI, SK, NW, RG>), dim3(grid), dim3((NW + kLsProducers) * 64), lds, h->stream, a);
+    return true;
+}
+
 template <int EPI>
 void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap = 0) {
     ProfScope ps(h, PK_MFMA_QKV + EPI, mi, (double)a.Np * a.K * 2.0);
@@ -464,9 +485,13 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
                 const int grid_wt = a.sweeps > 1 ? (ng + 7) / 8 * 8 * a.sweeps : ng;
 #define EAD_WT(TPW_, NW_) do { if (rg == 7) hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, TPW_, 7, NW_>), dim3(grid_wt), dim3(NW_ * 64), 0, h->stream, a); \
                                else hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, TPW_, 8, NW_>), dim3(grid_wt), dim3(NW_ * 64), 0, h->stream, a); } while (0)
+#define EAD_LS(NW_) (rg == 7 ? launch_ls<EPI, false, NW_, 7>(h, a, grid_wt) : launch_ls<EPI, false, NW_, 8>(h, a, grid_wt))
                 if (multi) EAD_WT(2, 4);
-                else switch (nt) { case 4: EAD_WT(1, 4); break; case 5: EAD_WT(1, 5); break; case 6: EAD_WT(1, 6); break;
-                                   case 7: EAD_WT(1, 7); break; default: EAD_WT(1, 8); break; }
+                else switch (nt) {      // weight tiles straight into LDS by fetching waves; the register-ring kernel where LDS does not allow it
+                    case 4: if (!EAD_LS(4)) EAD_WT(1, 4); break; case 5: if (!EAD_LS(5)) EAD_WT(1, 5); break;
+                    case 6: if (!EAD_LS(6)) EAD_WT(1, 6); break; case 7: if (!EAD_LS(7)) EAD_WT(1, 7); break;
+                    default: if (!EAD_LS(8)) EAD_WT(1, 8); break; }
+#undef EAD_LS
 #undef EAD_WT
                 return;
             }
@@ -475,7 +500,8 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
             while (KS > 1 && (a.K / 32) / KS < 16) --KS;
             if (KS > 1 && (size_t)KS * NG * 8 * nt * 256 <= kSplitKFloats) {
                 a.KS = KS; a.sk_part = h->sk_part;
-#define EAD_SK(TPW_, NW_) do { hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, true, TPW_, 8, NW_>), dim3(NG * KS), dim3(NW_ * 64), 0, h->stream, a); \
+#define EAD_SK(TPW_, NW_) do { if (TPW_ != 1 || !launch_ls<EPI, true, NW_, 8>(h, a, NG * KS)) \
+                                   hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, true, TPW_, 8, NW_>), dim3(NG * KS), dim3(NW_ * 64), 0, h->stream, a); \
                                hipLaunchKernelGGL((k_sk_merge<EPI, TPW_ * NW_>), dim3((NB * TPW_ * NW_ + 3) / 4), dim3(256), 0, h->stream, a, NG * 8); } while (0)
                 for (a.tb_base = 0; a.tb_base < TB; a.tb_base += nt) {
                     if (multi) EAD_SK(2, 4);
@@ -1379,6 +1405,7 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
             HIP_TRY(h, hipGetDevice(&dev)); HIP_TRY(h, hipGetDeviceProperties(&prop, dev));
             h->fused_grid = std::min(256, prop.multiProcessorCount);
             h->n_cu = prop.multiProcessorCount;
+            h->lds_per_block = std::max<size_t>(prop.sharedMemPerBlock, prop.sharedMemPerBlockOptin);
             for (int mi = 0; mi < 2; ++mi) {
                 Model &md = h->mdl[mi];
                 void *fn = fused_kernel_for(md);

@@ -653,6 +653,139 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
     }
 }
 
+// ------------------------------------------------------------------------------------
+// Single-sweep passes of 33-128 rows with the weight stream decoupled from the arithmetic.
+// In k_linear_mfma_wt every wave fetches weights (from HBM), fetches activations (from L2) and
+// multiplies; a wave's loads complete in order, so its slow weight fetches and its fast
+// activation fetches wait for each other, and what a wave can keep in flight is bounded by its
+// registers (about 40 KB of weights per compute unit, which at 2-3 us of loaded memory latency
+// is 3.5-5 TB/s over the chip).  Here a workgroup has two extra waves that do nothing but fetch
+// weight tiles, straight into LDS (the load writes LDS itself: no registers, no ds_write), kDepth - 1
+// k steps ahead: up to 104 KB of weights in flight per compute unit.  The NW multiplying waves
+// (one token block each, all RG row blocks, as in k_linear_mfma_wt with TPW = 1) fetch only
+// their activation fragments, and read a step's weight fragments from LDS while they multiply the step
+// before (all waves read all RG tiles: the LDS reads of a step take as long as its products).
+// One workgroup barrier per k step hands a step's tiles over; the slot a step leaves is refilled
+// right after the next barrier, when every wave has read it.
+// The order of the sums of an output element is that of k_linear_mfma_wt.
+// ------------------------------------------------------------------------------------
+constexpr int kLsDepth = 14;                 // k steps of weight tiles LDS holds (8 KB each)
+constexpr int kLsProducers = 2;              // fetching waves; each has 4 (kLsDepth - 1) loads of 1 KB in flight (the counter holds 63)
+constexpr size_t kLsLdsBytes(int nw) { return (size_t)kLsDepth * 8 * 1024 + (size_t)nw * 64 * 4 * sizeof(float); }
+
+template <int EPI, bool SK, int NW, int RG>
+__global__ __launch_bounds__((NW + kLsProducers) * 64) void k_linear_mfma_ls(LinArgs<bf16_t> a) {
+    static_assert(RG >= 5 && RG <= 8 && NW >= 4 && NW <= 8, "a producer wave fetches four of the step's eight tile slots");
+    constexpr int DA = 6;                              // ring of activation fragments per multiplying wave
+    extern __shared__ __attribute__((aligned(16))) unsigned char ls_smem[];
+    bf16_t (*s_w)[8][512] = reinterpret_cast<bf16_t (*)[8][512]>(ls_smem);                       // [kLsDepth][8][512]
+    float (*s_t)[64][4] = reinterpret_cast<float (*)[64][4]>(ls_smem + (size_t)kLsDepth * 8 * 1024);   // [NW][64][4]
+    const int K = a.K, KCfull = K >> 5, NB = a.Np >> 4, NG = (NB + RG - 1) / RG;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int T = *a.count;
+    const int TB = (T + 15) >> 4;
+    if (TB == 0) return;
+    const int KS = SK ? a.KS : 1;
+    const int g = SK ? (int)blockIdx.x / KS : (int)blockIdx.x, ks = SK ? (int)blockIdx.x % KS : 0;
+    const int tb0 = SK ? a.tb_base : 0;
+    const int kbase = (ks * KCfull) / KS, KC = ((ks + 1) * KCfull) / KS - kbase;     // this workgroup's k tiles
+    auto kstep = [&](int j) __attribute__((always_inline)) { return min(j, KC - 1); };      // past the end: the last step again
+
+    if (wave >= NW) {
+        // ---- fetching wave p: tile slots p, p + 2, p + 4, p + 6 of every step (slots past RG repeat the last row block) ----
+        const int p = wave - NW;
+        const bf16_t *wp[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            wp[q] = a.W + tile_offset(min(g * RG + min(p + 2 * q, RG - 1), NB - 1), kbase, KCfull) + lane * 8;
+        auto issue = [&](int j) __attribute__((always_inline)) {      // step j (past the end: the last step again, never read)
+            const size_t off = (size_t)kstep(j) * 512;
+            bf16_t (*slot)[512] = s_w[j % kLsDepth];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wp[q] + off),
+                                                 (__attribute__((address_space(3))) void *)&slot[p + 2 * q][0], 16, 0, 0);
+        };
+        for (int j = 0; j < kLsDepth - 1; ++j) issue(j);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (kLsDepth - 2)) : "memory");      // step 0 has landed
+        __builtin_amdgcn_s_barrier();                 // the bare barrier: this wave has nothing else to wait for
+        for (int i = 0; i < KC; ++i) {
+            // the multiplying waves read a step's tiles one step ahead of using them: step i + 1 has to
+            // have landed; steps i + 2 .. i + kLsDepth - 2 may still be on their way
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(4 * (kLsDepth - 3)) : "memory");
+            __builtin_amdgcn_s_barrier();
+            issue(i + kLsDepth - 1);                  // into the slot of step i - 1, which every wave has read by now
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // nothing may land in LDS after the workgroup has gone
+        return;
+    }
+
+    // ---- multiplying wave: token block tb0 + wave, all RG row blocks ----
+    f32x4_t acc[RG];
+#pragma unroll
+    for (int j = 0; j < RG; ++j) acc[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const int blk = min(tb0 + wave, TB - 1);
+    const bf16_t *bp[2] = {a.xp_lo + act_tile_offset(blk, kbase, TB) + lane * 8,          // lo, then hi
+                           a.xp + act_tile_offset(blk, kbase, TB) + lane * 8};
+    Vec8<bf16_t> ba[DA][2];
+    auto issue = [&](int s, int i) __attribute__((always_inline)) {
+        const size_t off = (size_t)kstep(i) * 512 * TB;
+        ba[s][0].load(bp[0] + off); ba[s][1].load(bp[1] + off);
+    };
+#pragma unroll
+    for (int s = 0; s < DA; ++s) {
+        issue(s, s);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // weight fragments of step i + 1 are read from LDS while step i is multiplied (two register sets)
+    static_assert(DA % 2 == 0, "the two fragment sets alternate with the unrolled ring slots");
+    u32x4_t fw[2][RG];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < RG; ++j) fw[0][j] = *reinterpret_cast<const u32x4_t *>(&s_w[0][j][lane * 8]);
+    for (int i0 = 0; i0 < KC; i0 += DA) {
+#pragma unroll
+        for (int s = 0; s < DA; ++s) {
+            const int i = i0 + s;
+            if (i < KC) {                                  // uniform over the workgroup
+                __syncthreads();
+                bf16_t (*nxt)[512] = s_w[(i + 1) % kLsDepth];      // past the last step: a slot nobody uses
+#pragma unroll
+                for (int j = 0; j < RG; ++j) fw[(s + 1) & 1][j] = *reinterpret_cast<const u32x4_t *>(&nxt[j][lane * 8]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int j = 0; j < RG; ++j)
+                        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            __builtin_bit_cast(bf16x8_t, fw[s & 1][j]), __builtin_bit_cast(bf16x8_t, ba[s][h].raw), acc[j], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            issue(s, i + DA);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    if constexpr (!SK) {
+#pragma unroll
+        for (int j = 0; j < RG; ++j) {
+            const int rb = g * RG + j, tb = tb0 + wave;
+            block_epilogue<EPI>(a, s_t[wave], rb, tb, acc[j], rb < NB && tb < TB, T, lane);
+        }
+    } else {
+        const size_t slab = (size_t)NG * RG * NW * 256;                // floats per slab
+#pragma unroll
+        for (int j = 0; j < RG; ++j) {
+            const int rb = g * RG + j, b = wave;
+            if (rb < NB && tb0 + b < TB) {
+                float *dst = a.sk_part + (size_t)ks * slab + ((size_t)rb * NW + b) * 256 + lane;
+                st_coherent(dst, acc[j][0]); st_coherent(dst + 64, acc[j][1]);
+                st_coherent(dst + 128, acc[j][2]); st_coherent(dst + 192, acc[j][3]);
+            }
+        }
+    }
+}
+
 // Sum of the K slabs that k_linear_mfma_wt<..., SK = true, TPW> left in memory, in slab order, then
 // the epilogue.  One wave per 16 x 16 block; grid = ceil(row blocks * NT / 4) workgroups, NT = 4 TPW.
 template <int EPI, int NT = kWideTok>
