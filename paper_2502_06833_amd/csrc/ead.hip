@@ -465,7 +465,12 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
     const bool big = (double)a.Np * a.K * 2.0 >= 24e6;
     const int NT = TB <= 1 ? 1 : (TB == 2 ? 2 : 4);
     int cfg = !big ? 1 : (NB >= 4 * 256 ? 4 : 2);       // 1: (4 waves, R=1)  4: (4, R=4)  2: (8 waves, R=2)  5: (4, R=4, split K)
-    int grid = (NB + cfg - 1) / cfg;
+    // 3: (4 waves, R=2) for matrices below that size with many row blocks, from 33 rows up: with one row block per
+    // workgroup every workgroup fetches all activation tiles for 16 output rows (gate/up of a narrow model:
+    // 139 MB of activation reads beside 17 MB of weights)
+    if constexpr (EPI == EPI_SWIGLU) { if (!big && NB >= 2 * h->n_cu && TB >= 3) cfg = 3; }
+    const int rpw = cfg == 3 ? 2 : cfg;                  // row blocks per workgroup
+    int grid = (NB + rpw - 1) / rpw;
     if constexpr (EPI != EPI_LOGITS) {
         // more than 32 rows: 64 or 128 rows per sweep, weight tiles shared through LDS.  Matrices with few
         // row blocks are split along K over workgroups; a second kernel adds the slabs in order and
@@ -522,15 +527,31 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
             cfg = 5; a.KS = KS; a.sk_part = h->sk_part; a.sk_tickets = h->sk_tickets; grid = NG * KS;
         }
     }
+    // small matrices with few row blocks and a long K (the down projection of a narrow model: 56 row blocks,
+    // 152 k tiles) leave most of the chip idle with one workgroup per row block: K is split over workgroups here
+    // too, the last to arrive adds the slabs
+    if constexpr (EPI == EPI_RES) {
+        if (cfg == 1 && TB <= 4 && NB <= h->n_cu) {
+            int KS = std::min(kSplitKMax, std::max(1, 2 * h->n_cu / NB));
+            while (KS > 1 && (a.K / 32) / KS < 16) --KS;
+            if (KS > 1 && (size_t)KS * NB * NT * 256 <= kSplitKFloats && NB <= kSplitKGroups) {
+                cfg = 6; a.KS = KS; a.sk_part = h->sk_part; a.sk_tickets = h->sk_tickets; grid = NB * KS;
+            }
+        }
+    }
     if (grid_cap > 0) grid = grid_cap;      // LM head: the number of partials per row is fixed
 #define EAD_LM(NW_, R_, NT_, D_, SK_) hipLaunchKernelGGL((k_linear_mfma<NW_, R_, NT_, D_, EPI, SK_>), dim3(grid), dim3(NW_ * 64), 0, h->stream, a)
     switch (cfg * 10 + NT) {
         case 11: EAD_LM(4, 1, 1, 8, false); break; case 12: EAD_LM(4, 1, 2, 6, false); break; case 14: EAD_LM(4, 1, 4, 4, false); break;
         case 21: EAD_LM(8, 2, 1, 8, false); break; case 22: EAD_LM(8, 2, 2, 6, false); break; case 24: EAD_LM(8, 2, 4, 3, false); break;
+        case 34: if constexpr (EPI == EPI_SWIGLU) EAD_LM(4, 2, 4, 4, false); break;
         case 41: EAD_LM(4, 4, 1, 6, false); break; case 42: EAD_LM(4, 4, 2, 4, false); break; case 44: EAD_LM(4, 4, 4, 3, false); break;
         case 51: if constexpr (EPI != EPI_LOGITS && EPI != EPI_QKV) EAD_LM(4, 4, 1, 6, true); break;
         case 52: if constexpr (EPI != EPI_LOGITS && EPI != EPI_QKV) EAD_LM(4, 4, 2, 4, true); break;
-        default: if constexpr (EPI != EPI_LOGITS && EPI != EPI_QKV) EAD_LM(4, 4, 4, 3, true); break;
+        case 54: if constexpr (EPI != EPI_LOGITS && EPI != EPI_QKV) EAD_LM(4, 4, 4, 3, true); break;
+        case 61: if constexpr (EPI == EPI_RES) EAD_LM(4, 1, 1, 8, true); break;
+        case 62: if constexpr (EPI == EPI_RES) EAD_LM(4, 1, 2, 6, true); break;
+        default: if constexpr (EPI == EPI_RES) EAD_LM(4, 1, 4, 4, true); break;
     }
 #undef EAD_LM
 }
