@@ -264,7 +264,7 @@ def bench_entropy_gate(args):
         "config": {"workload": "entropy_gate_b64", "rows": rows, "vocab": V, "window": w, "tau_nats": tau,
                    "d_min": d_min, "pool_tensors": pool_n},
         "large_token_share": float(share.item()), "event_ms_total": ev_ms,
-        "roofline": {"bound": "hbm", "kernel": "entropy_partial (+ gate_step), 16 steps per launch pair",
+        "roofline": {"bound": "hbm", "kernel": "entropy_rows (entropy, arg max, window and switch rule; 16 steps per launch)",
                      "achieved": bytes_step / per_step_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": bytes_step / per_step_us / 1e3 / HBM_PEAK_GBS, "traffic": None,
                      "avg_launch_us": per_step_us, "bytes_per_launch": bytes_step, "launches": steps},
@@ -277,8 +277,11 @@ def bench_entropy_gate(args):
         while time.time() - t0 < 10.0:
             oracle.entropy_rows(ref)
             n += rows
+        name, phys = host_cpu()
         out["cpu_baseline"] = {"value": n / (time.time() - t0), "unit": "tokens/s", "cores": 1, "kind": "oracle",
-                               "sample": "entropy + arg max of the 64 rows of one tensor, repeated for 10 s (single thread)"}
+                               "cpu_model": name, "physical_cores_on_host": phys,
+                               "sample": "entropy + arg max of the 64 rows of one tensor, repeated for 10 s (the oracle's "
+                                         "entropy routine is single-threaded: one thread used)"}
     g.close()
     print(json.dumps(out), flush=True)
 

@@ -1289,11 +1289,26 @@ void entropy_launch(const void *const *step_logits, int steps, int dtype, int ro
     else launch_entropy_partial<float>(step_logits, steps, rows, vocab, part, resident, st);
 }
 
+template <typename T>
+void launch_entropy_rows(const void *const *step_logits, int steps, int rows, int V, int resident, hipStream_t st,
+                         const GateStepArgs &gate, float *pair_H, int *row_tickets) {
+    const int nvec = V / 8;
+    EntRowArgs<T> a{};
+    for (int z = 0; z < steps; ++z) a.step_logits[z] = (const T *)step_logits[z];
+    a.V = V; a.rows = rows; a.steps = steps;
+    a.chunks = std::max(1, (nvec + 2047) / 2048);                 // pieces of at most 8 vectors per thread
+    a.vec_per_item = (std::max(nvec, 1) + a.chunks - 1) / a.chunks;
+    a.pair_H = pair_H; a.row_tickets = row_tickets; a.gate = gate;
+    hipLaunchKernelGGL((k_entropy_rows<T>), dim3(std::min(steps * rows, resident)), dim3(256), 0, st, a);
+}
+
 }  // namespace
 
 struct ead_gate {
     GateState st; GateCfg cfg; int rows; hipStream_t stream;
     EntPartial *part = nullptr;   // partials of this gate's entropy passes: (steps per launch) x rows x kEntMaxChunks
+    float *pair_H = nullptr;      // small windows (one launch per group of steps): entropies handed between workgroups
+    int *row_tickets = nullptr;   //   and the arrival counters per row, zero between launches
     int resident = 1024;
     std::vector<void *> allocs;
 };
@@ -1718,15 +1733,15 @@ ead_status ead_gate_create(int32_t rows, int32_t window, float tau, int32_t d_mi
     { const ead_status rc = entropy_device(&d); if (rc != EAD_OK) { delete g; return rc; } }
     g->resident = d->resident;
     const size_t steps_per_launch = std::max(1, std::min(kGateMaxSteps, kEntMaxRows / rows));
-    void *p[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
-    const size_t sz[5] = {(size_t)rows * window * 4, (size_t)rows * 4, (size_t)rows * 4, (size_t)rows * 4,
-                          steps_per_launch * rows * kEntMaxChunks * sizeof(EntPartial)};
-    for (int i = 0; i < 5; ++i) {
+    void *p[7] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+    const size_t sz[7] = {(size_t)rows * window * 4, (size_t)rows * 4, (size_t)rows * 4, (size_t)rows * 4,
+                          steps_per_launch * rows * kEntMaxChunks * sizeof(EntPartial), steps_per_launch * rows * 4, (size_t)rows * 4};
+    for (int i = 0; i < 7; ++i) {
         if (hipMalloc(&p[i], sz[i]) != hipSuccess) { for (int j = 0; j < i; ++j) (void)hipFree(p[j]); delete g; return fail(nullptr, EAD_ERR_OOM, "hipMalloc failed"); }
         g->allocs.push_back(p[i]);
     }
     g->st.ring = (float *)p[0]; g->st.n = (int *)p[1]; g->st.c = (int *)p[2]; g->st.model = (int *)p[3];
-    g->part = (EntPartial *)p[4];
+    g->part = (EntPartial *)p[4]; g->pair_H = (float *)p[5]; g->row_tickets = (int *)p[6];
     *out = g;
     return ead_gate_reset(g);
 }
@@ -1737,6 +1752,7 @@ ead_status ead_gate_reset(ead_gate *g) {
     (void)hipMemsetAsync(g->st.n, 0, (size_t)g->rows * 4, g->stream);
     (void)hipMemsetAsync(g->st.c, 0, (size_t)g->rows * 4, g->stream);
     (void)hipMemsetAsync(g->st.model, 0, (size_t)g->rows * 4, g->stream);
+    (void)hipMemsetAsync(g->row_tickets, 0, (size_t)g->rows * 4, g->stream);
     return hipGetLastError() == hipSuccess ? EAD_OK : EAD_ERR_DEVICE;
 }
 
@@ -1757,20 +1773,36 @@ ead_status ead_gate_step(ead_gate *g, const float *H_dev, uint8_t *model_id_dev,
     return hipGetLastError() == hipSuccess ? EAD_OK : EAD_ERR_DEVICE;
 }
 
+namespace {
+// Entropy + arg max of `ns` logits matrices and the gate through those steps.  Windows up to kGateFoldWindow: one
+// launch (k_entropy_rows); longer windows: the partials pass, then k_gate_step.
+ead_status gate_steps(ead_gate *g, const void *const *ptrs, int ns, int dtype, int vocab, int unit, float *H_dev,
+                      int32_t *argmax_dev, uint8_t *model_id_dev, float *window_mean_dev, uint8_t *next_model_dev) {
+    TRY(entropy_check(ptrs, ns, dtype, g->rows, vocab));
+    GateStepArgs a{};
+    a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.steps = ns; a.unit = unit;
+    a.H_out = H_dev; a.argmax_out = argmax_dev;
+    a.model_id_out = model_id_dev; a.Hbar_out = window_mean_dev; a.next_out = next_model_dev;
+    if (g->cfg.w <= kGateFoldWindow) {
+        if (dtype == EAD_BF16) launch_entropy_rows<bf16_t>(ptrs, ns, g->rows, vocab, g->resident, g->stream, a, g->pair_H, g->row_tickets);
+        else launch_entropy_rows<float>(ptrs, ns, g->rows, vocab, g->resident, g->stream, a, g->pair_H, g->row_tickets);
+    } else {
+        int chunks = 0, per = 0;
+        entropy_split(g->rows, vocab, &chunks, &per);
+        a.partials = g->part; a.n_part = chunks;
+        entropy_launch(ptrs, ns, dtype, g->rows, vocab, g->stream, g->part, g->resident);
+        hipLaunchKernelGGL(k_gate_step, dim3(g->rows), dim3(ns * 64), 0, g->stream, a);
+    }
+    return EAD_OK;
+}
+}  // namespace
+
 ead_status ead_gate_step_logits(ead_gate *g, const void *logits_dev, int32_t dtype, int32_t vocab, int32_t unit,
                                 float *H_dev, int32_t *argmax_dev, uint8_t *model_id_dev, float *window_mean_dev,
                                 uint8_t *next_model_dev) {
     if (!g) return EAD_ERR_INVALID_ARG;
     if (unit != EAD_NATS && unit != EAD_BITS) return fail(nullptr, EAD_ERR_INVALID_ARG, "unit must be 0 or 1");
-    TRY(entropy_check(&logits_dev, 1, dtype, g->rows, vocab));
-    EntPartial *part = g->part; int chunks = 0, per = 0;
-    entropy_split(g->rows, vocab, &chunks, &per);
-    entropy_launch(&logits_dev, 1, dtype, g->rows, vocab, g->stream, part, g->resident);
-    GateStepArgs a{};
-    a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.steps = 1; a.partials = part; a.n_part = chunks; a.unit = unit;
-    a.H_out = H_dev; a.argmax_out = argmax_dev;
-    a.model_id_out = model_id_dev; a.Hbar_out = window_mean_dev; a.next_out = next_model_dev;
-    hipLaunchKernelGGL(k_gate_step, dim3(g->rows), dim3(64), 0, g->stream, a);
+    TRY(gate_steps(g, &logits_dev, 1, dtype, vocab, unit, H_dev, argmax_dev, model_id_dev, window_mean_dev, next_model_dev));
     return hipGetLastError() == hipSuccess ? EAD_OK : EAD_ERR_DEVICE;
 }
 
@@ -1781,22 +1813,15 @@ ead_status ead_gate_run_logits(ead_gate *g, const void *const *logits_dev_list, 
     if (n_tensors < 1 || n_tensors > 4096 || n_steps < 0) return fail(nullptr, EAD_ERR_INVALID_ARG, "need 1 <= n_tensors <= 4096, n_steps >= 0");
     if (unit != EAD_NATS && unit != EAD_BITS) return fail(nullptr, EAD_ERR_INVALID_ARG, "unit must be 0 or 1");
     for (int i = 0; i < n_tensors; ++i) if (!logits_dev_list[i]) return fail(nullptr, EAD_ERR_INVALID_ARG, "null logits pointer");
-    // steps per launch pair, bounded by the scratch for the partials
+    // steps per launch, bounded by the gate's hand-over buffers
     const int S = std::max(1, std::min(kGateMaxSteps, kEntMaxRows / g->rows));
     for (int s0 = 0; s0 < n_steps; s0 += S) {
         const int ns = std::min(S, n_steps - s0);
-        EntPartial *part = g->part; int chunks = 0, per = 0;
         const void *ptrs[kGateMaxSteps];
         for (int z = 0; z < ns; ++z) ptrs[z] = logits_dev_list[(s0 + z) % n_tensors];
-        TRY(entropy_check(ptrs, ns, dtype, g->rows, vocab));
-        entropy_split(g->rows, vocab, &chunks, &per);
-        entropy_launch(ptrs, ns, dtype, g->rows, vocab, g->stream, part, g->resident);
-        GateStepArgs a{};
-        a.st = g->st; a.cfg = g->cfg; a.rows = g->rows; a.steps = ns; a.partials = part; a.n_part = chunks; a.unit = unit;
         const size_t o = (size_t)s0 * g->rows;
-        a.H_out = H_dev ? H_dev + o : nullptr; a.argmax_out = argmax_dev ? argmax_dev + o : nullptr;
-        a.model_id_out = model_id_dev ? model_id_dev + o : nullptr; a.Hbar_out = window_mean_dev ? window_mean_dev + o : nullptr;
-        hipLaunchKernelGGL(k_gate_step, dim3(g->rows), dim3(ns * 64), 0, g->stream, a);
+        TRY(gate_steps(g, ptrs, ns, dtype, vocab, unit, H_dev ? H_dev + o : nullptr, argmax_dev ? argmax_dev + o : nullptr,
+                       model_id_dev ? model_id_dev + o : nullptr, window_mean_dev ? window_mean_dev + o : nullptr, nullptr));
     }
     return hipGetLastError() == hipSuccess ? EAD_OK : EAD_ERR_DEVICE;
 }
