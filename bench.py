@@ -321,7 +321,7 @@ def main():
                     help="grouped (default for batches): small-model rows run ahead, large-model rows are served together")
     ap.add_argument("--sched-start", type=float, default=0.5, help="grouped: large model starts at this share of waiting rows")
     ap.add_argument("--sched-stop", type=float, default=0.25, help="grouped: ... and stops below this share")
-    ap.add_argument("--lead", type=int, default=64,
+    ap.add_argument("--lead", type=int, default=32,
                     help="grouped: rows run freely, none more than this many tokens ahead of the slowest (a step is then "
                          "one token per row of batch progress: batch tokens in total); 0: every row exactly one token per step")
     ap.add_argument("--temperature", type=float, default=0.0, help="sample at this temperature (0 = greedy, the default)")
@@ -462,6 +462,20 @@ def main():
             f"large share {st['large_share']:.3f}, switches {st['switches']}, host syncs {st['host_syncs']}, "
             f"passes large/small {st['steps_large']}/{st['steps_small']}")
 
+    def do_exact():
+        # the grouped schedule with every row held to exactly `steps` tokens (rows that are ahead wait at the end)
+        nonlocal lead
+        keep, lead = lead, 0
+        try:
+            d1, s1 = timed(-1, True)
+        finally:
+            lead = keep
+        n1 = s1["tokens_small"] + s1["tokens_large"]
+        out["grouped_exact_steps"] = {"tokens_per_s": n1 / d1, "large_passes": s1["steps_large"], "small_passes": s1["steps_small"],
+                                      "large_token_share": s1["large_share"]}
+        log(f"[bench] grouped, exactly {steps} tokens per row: {n1 / d1:.1f} tok/s, large share {s1['large_share']:.3f}, "
+            f"passes large/small {s1['steps_large']}/{s1['steps_small']}")
+
     def do_lockstep():
         d1, s1 = timed(-1, False)
         n1 = s1["tokens_small"] + s1["tokens_large"]
@@ -475,34 +489,52 @@ def main():
         out[name] = {"tokens_per_s": n2 / d2, "hbm_frac": s2["algorithmic_bytes"] / d2 / 1e9 / HBM_PEAK_GBS}
         log(f"[bench] {name}: {n2 / d2:.1f} tok/s, {out[name]['hbm_frac']:.1%} of HBM peak")
 
-    def do_profile():
-        # per-kernel HIP-event timing on a separate, untimed run of the same schedule
-        e.force_model(-1)
-        e.set_schedule(grouped, args.sched_start, args.sched_stop)
+    def profiled_run(select, force=-1, grp=None):
+        # per-kernel HIP-event timing on a separate, untimed run (events on the lanes' own streams)
+        grp = grouped if grp is None else grp
+        e.force_model(force)
+        e.set_schedule(grp, args.sched_start, args.sched_stop)
         e.set_gate(w, tau, d_min)
         e.rewind(ln["profile_new"])
-        free = grouped and lead > 0
+        free = grp and lead > 0
         if settle:
             advance(settle, free)
         advance(warmup, free)
+        e.profile_select(select)
         e.profile(True)
         advance(ln["profile_steps"], free)
         prof = e.profile_read()
         e.profile(False)
+        e.profile_select(None)
         e.set_schedule(False)
+        e.force_model(-1)
+        return prof
+
+    def do_profile():
+        prof = profiled_run(None)
         for r in sorted(prof, key=lambda r: -r["total_ms"]):
             gbs = r["bytes"] / max(r["total_ms"], 1e-9) / 1e6
             log(f"[prof] {r['name']:<28s} n={r['launches']:<6d} avg {1e3 * r['total_ms'] / r['launches']:8.2f} us  "
                 f"{gbs:8.0f} GB/s")
-        # the dominant kernel is reported per model (one kernel, one shape): the one that moves the most
-        # bytes over the pass, which does not flip with timing noise the way a ranking by time can
-        d = max(prof, key=lambda r: r["bytes"])
+        # The dominant kernel is reported per model (one kernel, one shape): the one that moves the most bytes
+        # over the pass, which does not flip with timing noise the way a ranking by time can.  Its roofline
+        # entry is timed on its model's own passes (the other model idle, only this kernel's launches bracketed):
+        # while both lanes' queues are busy, event brackets read about 25 us more than the kernel's begin and
+        # end stamps in a rocprofv3 trace of the same launches, with one lane they agree to a few microseconds.
+        dom = max(prof, key=lambda r: r["bytes"])["name"]
+        which = 1 if dom.endswith("/large") else 0
+        d = next(r for r in profiled_run(dom, force=which, grp=False) if r["name"] == dom)
         achieved = d["bytes"] / d["total_ms"] / 1e6
-        out["roofline"] = {"bound": "hbm", "kernel": d["name"], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload, d["name"]),
+        both = next(r for r in prof if r["name"] == dom)
+        log(f"[prof] {dom} on its model's own passes ({batch} rows): n={d['launches']} avg {1e3 * d['total_ms'] / d['launches']:.2f} us "
+            f"= {achieved:.0f} GB/s")
+        out["roofline"] = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload, dom),
                            "avg_launch_us": 1e3 * d["total_ms"] / d["launches"],
                            "bytes_per_launch": d["bytes"] / d["launches"], "launches": d["launches"],
-                           "profiled_steps": ln["profile_steps"], "schedule": schedule}
+                           "profiled_steps": ln["profile_steps"], "rows_per_pass": batch,
+                           "timed_on": ("large" if which else "small") + "-model-only passes, one lane, this kernel's launches bracketed",
+                           "avg_launch_us_both_lanes_bracketed": 1e3 * both["total_ms"] / both["launches"]}
 
     def do_cpu():
         big = sl.n_params() > 2e9
@@ -512,6 +544,8 @@ def main():
     if tau is not None:
         leg("headline", do_headline)
         if grouped:
+            if lead > 0:
+                leg("grouped_exact_steps", do_exact)
             leg("lockstep", do_lockstep)
         if not args.no_single_model:
             leg("small_only", lambda: do_single("small_only", 0))

@@ -297,6 +297,10 @@ typedef struct {
 } ead_kernel_profile;
 ead_status ead_profile_enable(ead_handle *h, int32_t on);   /* also clears what was collected */
 ead_status ead_profile_read(ead_handle *h, ead_kernel_profile *out, int32_t capacity, int32_t *n_out);
+/* Bracket only the launches of one kernel class (a name as ead_profile_read reports it, e.g.
+ * "linear_mfma_swiglu/large"), so that timing the kernel a roofline entry is about disturbs the
+ * rest of the run as little as possible; NULL or "" = every class again (the default). */
+ead_status ead_profile_select(ead_handle *h, const char *name);
 /* Library version as major*10000 + minor*100 + patch. */
 int32_t ead_version(void);
 

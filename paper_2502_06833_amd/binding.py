@@ -88,6 +88,7 @@ _SIGNATURES = {
     "ead_set_schedule": (C.c_int, [C.c_void_p, C.c_int32, C.c_float, C.c_float]),
     "ead_set_sampling": (C.c_int, [C.c_void_p, C.c_float, C.c_uint64]),
     "ead_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),
+    "ead_profile_select": (C.c_int, [C.c_void_p, C.c_char_p]),
     "ead_profile_read": (C.c_int, [C.c_void_p, C.POINTER(KernelProfile), C.c_int32, _I32P]),
 }
 
@@ -277,6 +278,9 @@ class EAD:
 
     def profile(self, on: bool):
         self._check(lib().ead_profile_enable(self._h, 1 if on else 0))
+
+    def profile_select(self, name=None):
+        self._check(lib().ead_profile_select(self._h, name.encode() if name else None))
 
     def profile_read(self) -> list:
         arr = (KernelProfile * 64)()

@@ -199,6 +199,7 @@ struct ead_handle {
     std::string err;
     // optional per-kernel event timing
     int prof_on = 0;
+    unsigned long long prof_mask = ~0ull;    // kernel classes (kind * 2 + model) that are bracketed while prof_on
     struct ProfRec { int cls; hipEvent_t a, b; double bytes; };
     std::vector<ProfRec> prof_recs;
     std::vector<hipEvent_t> ev_pool;
@@ -247,7 +248,8 @@ const char *const kProfNames[PK_COUNT] = {"embed", "pack_act", "linear_fma_qkv",
 // Brackets the launches made during its lifetime with two events (profiling mode only).
 struct ProfScope {
     ead_handle *h; bool on;
-    ProfScope(ead_handle *h_, int kind, int model, double bytes) : h(h_), on(h_->prof_on != 0) {
+    ProfScope(ead_handle *h_, int kind, int model, double bytes)
+        : h(h_), on(h_->prof_on != 0 && ((h_->prof_mask >> (kind * 2 + model)) & 1ull)) {
         if (!on) return;
         hipEvent_t ev[2];
         for (auto &e : ev) {
@@ -1665,6 +1667,20 @@ ead_status ead_profile_enable(ead_handle *h, int32_t on) {
     prof_collect(h);
     memset(h->prof_ms, 0, sizeof h->prof_ms); memset(h->prof_bytes, 0, sizeof h->prof_bytes); memset(h->prof_n, 0, sizeof h->prof_n);
     h->prof_on = on ? 1 : 0;
+    return EAD_OK;
+}
+
+ead_status ead_profile_select(ead_handle *h, const char *name) {
+    if (!h) return EAD_ERR_INVALID_ARG;
+    if (!name || !*name) { h->prof_mask = ~0ull; return EAD_OK; }
+    unsigned long long mask = 0;
+    for (int c = 0; c < PK_COUNT * 2; ++c) {
+        char buf[64];
+        snprintf(buf, sizeof buf, "%s/%s", kProfNames[c / 2], (c & 1) ? "large" : "small");
+        if (strcmp(buf, name) == 0) mask |= 1ull << c;
+    }
+    if (!mask) return fail(h, EAD_ERR_INVALID_ARG, "no kernel class is called '%s'", name);
+    h->prof_mask = mask;
     return EAD_OK;
 }
 
