@@ -48,6 +48,7 @@ WORKLOADS = {
 # The headline workload: the largest configuration that fits one GPU (Qwen-0.5B / Qwen-14B shapes, batch 64,
 # ragged prompts, every row its own instance of Algorithm 1), grouped two-lane schedule.
 DEFAULT_WORKLOAD = "qwen_05b_14b_b64"
+SECONDARY_WORKLOAD = "llama_1b_8b_b1"     # the batch-1 pair, reported beside the default workload
 
 MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
@@ -286,6 +287,25 @@ def bench_entropy_gate(args):
     print(json.dumps(out), flush=True)
 
 
+def run_secondary(workload, args):
+    """Another workload through this same script in a child process (its own handle and weights); returns the
+    fields of its JSON line that describe the decode path."""
+    import subprocess
+    cmd = [sys.executable, os.path.abspath(__file__), "--workload", workload, "--secondary", "none", "--no-cpu-baseline",
+           "--warmup", str(args.warmup), "--seed", str(args.seed)]
+    r = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+    for line in r.stderr.splitlines():
+        if line.startswith("[bench]"):
+            log("  (secondary) " + line)
+    lines = [l for l in r.stdout.splitlines() if l.startswith("{")]
+    if not lines:
+        raise RuntimeError(f"secondary workload {workload} printed no result (exit {r.returncode}): {r.stderr[-400:]}")
+    d = json.loads(lines[-1])
+    keep = ("metric", "value", "unit", "steps", "warmup", "ms_per_step", "dtype", "config", "decode_hbm_gbs", "decode_hbm_frac_of_peak",
+            "large_token_share", "param_ratio", "switches", "small_only", "large_only", "ead_over_large_only", "roofline", "errors")
+    return {k: d[k] for k in keep if k in d}
+
+
 def build_probe():
     """Compile roofline_probe.hip (beside this file): a torch-free driver of the library's C ABI for
     hardware-counter runs (`rocprofv3 --pmc ... -- ./roofline_probe ...`)."""
@@ -315,7 +335,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-single-model", action="store_true", help="skip the small-only / large-only runs")
     ap.add_argument("--profile-steps", type=int, default=64, help="steps of the per-kernel timing leg (never more than --steps)")
-    ap.add_argument("--fused", type=int, default=None, help="1/0: force the fused single-row decode kernel on/off")
+    ap.add_argument("--fused", type=int, default=None, help="1/0: the fused single-row decode kernel on/off (2: its register-buffered variant)")
     ap.add_argument("--tau", type=float, default=None, help="skip the calibration runs and use this threshold (nats)")
     ap.add_argument("--schedule", choices=["lockstep", "grouped"], default=None,
                     help="grouped (default for batches): small-model rows run ahead, large-model rows are served together")
@@ -328,6 +348,9 @@ def main():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for hardware byte counters)")
     ap.add_argument("--build-probe", action="store_true", help="compile roofline_probe.hip and exit")
+    ap.add_argument("--secondary", default=None,
+                    help="a second workload measured by a child process after this one and reported under 'secondary' in the same "
+                         "JSON line ('none' to skip; default: the batch-1 workload when the default workload runs)")
     args = ap.parse_args()
     if args.build_probe:
         print(build_probe())
@@ -366,7 +389,7 @@ def main():
         torch.cuda.empty_cache()
     log(f"[bench] handle created at {time.time() - t0:.1f}s")
     if args.fused is not None:
-        e.set_fused(bool(args.fused))
+        e.set_fused(int(args.fused))
     if args.temperature > 0:
         e.set_sampling(args.temperature, args.seed)
 
@@ -555,9 +578,15 @@ def main():
         leg("profile", do_profile)
         if not args.no_cpu_baseline:
             leg("cpu_baseline", do_cpu)
+    leg("close", e.close)
+    secondary = args.secondary or (SECONDARY_WORKLOAD if args.workload == DEFAULT_WORKLOAD else "none")
+    if secondary != "none" and tau is not None:
+        del e
+        Ws = Wl = None
+        torch.cuda.empty_cache()
+        leg("secondary", lambda: out.update({"secondary": run_secondary(secondary, args)}))
     if errors:
         out["errors"] = errors
-    leg("close", e.close)
     print(json.dumps(out), flush=True)
     return 1 if errors or out["value"] is None else 0
 

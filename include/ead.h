@@ -278,9 +278,12 @@ ead_status ead_set_sampling(ead_handle *h, float temperature, uint64_t seed);
 ead_status ead_set_schedule(ead_handle *h, int32_t grouped, float start_fraction, float stop_fraction);
 /* Single-row decode steps can run as ONE persistent kernel per step (grid barriers
  * instead of kernel boundaries, weight prefetch across them) instead of the per-layer
- * kernels that wider batches use.  Off by default; on = 1 selects it for the shapes it
- * is built for (the per-layer kernels are used regardless for any other shape).  Both
- * paths compute the same thing; tests compare them. */
+ * kernels that wider batches use.  Off by default (on this hardware the per-layer kernels
+ * are the faster of the two); on = 1 selects it for the shapes it is built for (the
+ * per-layer kernels are used regardless for any other shape): for bf16 models the variant
+ * whose fetching waves stream the weights through a ring in LDS, for float32 models the
+ * one that buffers them in registers; on = 2 selects the register-buffered variant for
+ * bf16 models as well.  All paths compute the same thing; tests compare them. */
 ead_status ead_set_fused(ead_handle *h, int32_t on);
 
 /* Per-kernel timing for roofline reports.  While enabled, every kernel launch of the

@@ -273,8 +273,10 @@ class EAD:
     def set_sampling(self, temperature: float, seed: int = 0):
         self._check(lib().ead_set_sampling(self._h, temperature, seed))
 
-    def set_fused(self, on: bool):
-        self._check(lib().ead_set_fused(self._h, 1 if on else 0))
+    def set_fused(self, on):
+        """False/0: per-layer kernels; True/1: one persistent kernel per single-row step (the streamed
+        variant where the model has one); 2: the register-buffered persistent kernel even then."""
+        self._check(lib().ead_set_fused(self._h, 2 if on == 2 and on is not True else (1 if on else 0)))
 
     def profile(self, on: bool):
         self._check(lib().ead_profile_enable(self._h, 1 if on else 0))

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libead.so")
 SOURCES = ["ead.hip"]
-HEADERS = ["common.hpp", "linear.hpp", "attention.hpp", "entropy.hpp", "state.hpp", "fused.hpp"]
+HEADERS = ["common.hpp", "linear.hpp", "attention.hpp", "entropy.hpp", "state.hpp", "fused.hpp", "stream.hpp"]
 
 
 def _newest_source() -> float:

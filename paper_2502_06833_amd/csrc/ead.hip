@@ -23,6 +23,7 @@
 #include "linear.hpp"
 #include "state.hpp"
 #include "fused.hpp"
+#include "stream.hpp"
 
 using namespace ead;
 
@@ -151,6 +152,8 @@ struct Model {
     std::vector<Layer> layers;
     double weight_bytes_nolm, lm_bytes, kv_bytes_per_pos, n_params;
     void *fused_mats = nullptr, *fused_layers = nullptr; int n_mats = 0; bool fused_ok = false;
+    void *arena = nullptr; size_t layer_elems = 0, mat_off[4] = {0, 0, 0, 0};      // packed layer matrices: layer l's j-th at arena + l * layer_elems + mat_off[j]
+    bool stream_ok = false;                                                     // k_decode_stream serves this model
     size_t esz() const { return dtype == EAD_BF16 ? 2 : 4; }
 };
 
@@ -314,11 +317,12 @@ ead_status check_model(const ead_model_desc *m, const char *name) {
     return EAD_OK;
 }
 
+// `place`: where the packed matrix goes; null = memory of its own
 template <typename WT>
 ead_status pack_matrix(ead_handle *h, const void *s0, const void *s1, const void *s2, void **dst, int Np, int K,
-                       int mode, int hd, int NQ, int NK) {
-    WT *d = nullptr;
-    TRY(dmalloc(h, &d, (size_t)Np * K));
+                       int mode, int hd, int NQ, int NK, WT *place = nullptr) {
+    WT *d = place;
+    if (!d) TRY(dmalloc(h, &d, (size_t)Np * K));
     const size_t chunks = (size_t)Np * K / 8;
     hipLaunchKernelGGL(k_pack_weights<WT>, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, h->stream,
                        (const WT *)s0, (const WT *)s1, (const WT *)s2, d, Np, K, mode, hd, NQ, NK);
@@ -340,12 +344,21 @@ ead_status build_model(ead_handle *h, const ead_model_desc *src, Model *m, int m
     HIP_TRY(h, hipMemcpyAsync(m->g_final, src->norm_final, d * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
     m->layers.resize(m->L);
     const size_t cache_elems = (size_t)max_batch * m->KV * max_seq * hd;
+    // The four matrices of all layers share one allocation with a constant layer stride, so that a
+    // kernel that walks the whole model (k_decode_stream) finds every matrix by arithmetic alone.
+    const size_t n_qkv = (size_t)(NQ + 2 * NK) * d, n_o = (size_t)d * NQ, n_gu = 2 * (size_t)m->F * d, n_dn = (size_t)d * m->F;
+    const size_t layer_elems = n_qkv + n_o + n_gu + n_dn;        // every part a multiple of 512 elements
+    WT *arena = nullptr;
+    TRY(dmalloc(h, &arena, layer_elems * (size_t)m->L));
+    m->arena = arena; m->layer_elems = layer_elems;
+    m->mat_off[0] = 0; m->mat_off[1] = n_qkv; m->mat_off[2] = n_qkv + n_o; m->mat_off[3] = n_qkv + n_o + n_gu;
     for (int l = 0; l < m->L; ++l) {
         Layer &ly = m->layers[l];
-        TRY(pack_matrix<WT>(h, src->wq[l], src->wk[l], src->wv[l], &ly.wqkv, NQ + 2 * NK, d, PACK_QKV, hd, NQ, NK));
-        TRY(pack_matrix<WT>(h, src->wo[l], nullptr, nullptr, &ly.wo, d, NQ, PACK_PLAIN, 0, 0, 0));
-        TRY(pack_matrix<WT>(h, src->w_gate[l], src->w_up[l], nullptr, &ly.wgu, 2 * m->F, d, PACK_GATEUP, 0, 0, 0));
-        TRY(pack_matrix<WT>(h, src->w_down[l], nullptr, nullptr, &ly.wdown, d, m->F, PACK_PLAIN, 0, 0, 0));
+        WT *lb = arena + (size_t)l * layer_elems;
+        TRY(pack_matrix<WT>(h, src->wq[l], src->wk[l], src->wv[l], &ly.wqkv, NQ + 2 * NK, d, PACK_QKV, hd, NQ, NK, lb + m->mat_off[0]));
+        TRY(pack_matrix<WT>(h, src->wo[l], nullptr, nullptr, &ly.wo, d, NQ, PACK_PLAIN, 0, 0, 0, lb + m->mat_off[1]));
+        TRY(pack_matrix<WT>(h, src->w_gate[l], src->w_up[l], nullptr, &ly.wgu, 2 * m->F, d, PACK_GATEUP, 0, 0, 0, lb + m->mat_off[2]));
+        TRY(pack_matrix<WT>(h, src->w_down[l], nullptr, nullptr, &ly.wdown, d, m->F, PACK_PLAIN, 0, 0, 0, lb + m->mat_off[3]));
         TRY(dmalloc(h, &ly.g_attn, (size_t)d)); TRY(dmalloc(h, &ly.g_ffn, (size_t)d));
         HIP_TRY(h, hipMemcpyAsync(ly.g_attn, src->norm_attn[l], d * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
         HIP_TRY(h, hipMemcpyAsync(ly.g_ffn, src->norm_ffn[l], d * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
@@ -730,6 +743,24 @@ void *fused_kernel_for(const Model &m) {
     return nullptr;
 }
 
+// the streamed variant: bf16 only
+template <int HD, int G>
+void *stream_kernel_ptr() { return (void *)k_decode_stream<HD, G>; }
+void *stream_kernel_for(const Model &m) {
+    const int G = m.H / m.KV;
+    if (m.dtype != EAD_BF16) return nullptr;
+    if (m.hd == 64 && G == 4) return stream_kernel_ptr<64, 4>();
+    if (m.hd == 128 && G == 4) return stream_kernel_ptr<128, 4>();
+    if (m.hd == 64 && G == 7) return stream_kernel_ptr<64, 7>();
+    if (m.hd == 128 && G == 5) return stream_kernel_ptr<128, 5>();
+    return nullptr;
+}
+size_t stream_lds_bytes(const Model &m) {
+    const size_t kmax = std::max(std::max(m.d, m.F), m.H * m.hd);
+    const size_t attn = (size_t)kFusedWaves * m.hd + 2 * kFusedWaves;
+    return (size_t)kStreamDepth * kStreamSlotBytes + std::max(kmax + 2 * kFusedWaves * 16 + 64, attn) * sizeof(float);
+}
+
 size_t fused_lds_bytes(const Model &m) {
     const size_t kmax = std::max(std::max(m.d, m.F), m.H * m.hd);
     const size_t G = m.H / m.KV;
@@ -760,8 +791,26 @@ ead_status fused_step(ead_handle *h, int mi, double keys) {
     a.bar = GridBar{h->bar_mem, h->bar_mem + kBarGroups * 32, h->abort_flag, h->bar_epoch};
     a.fin = make_fin(h, mi, false);
     a.batch = h->batch;
-    void *args[] = {&a};
     ProfScope ps(h, PK_FUSED, mi, m.weight_bytes_nolm + m.lm_bytes + keys * m.kv_bytes_per_pos);
+    if constexpr (std::is_same<WT, bf16_t>::value) {
+        if (m.stream_ok && h->fused_on != 2) {
+            StreamModel sm{};
+            const int NQ = m.H * m.hd, NK = m.KV * m.hd;
+            sm.base = (const bf16_t *)m.arena; sm.layer_stride = m.layer_elems; sm.lm = (const bf16_t *)m.lm_head; sm.L = m.L;
+            for (int j = 0; j < 4; ++j) sm.off[j] = m.mat_off[j];
+            sm.NB[0] = (NQ + 2 * NK) / 16; sm.KC[0] = m.d / 32;
+            sm.NB[1] = m.d / 16; sm.KC[1] = NQ / 32;
+            sm.NB[2] = 2 * m.F / 16; sm.KC[2] = m.d / 32;
+            sm.NB[3] = m.d / 16; sm.KC[3] = m.F / 32;
+            sm.NB[4] = m.V / 16; sm.KC[4] = m.d / 32;
+            void *sargs[] = {&a, &sm};
+            HIP_TRY(h, hipLaunchCooperativeKernel(stream_kernel_for(m), dim3(h->fused_grid), dim3(kStreamThreads), sargs,
+                                                  (unsigned)stream_lds_bytes(m), h->stream));
+            h->bar_epoch += 5u * m.L + 1u;
+            return EAD_OK;
+        }
+    }
+    void *args[] = {&a};
     HIP_TRY(h, hipLaunchCooperativeKernel(fused_kernel_for(m), dim3(h->fused_grid), dim3(kFusedThreads), args,
                                           (unsigned)fused_lds_bytes(m), h->stream));
     h->bar_epoch += 5u * m.L + 1u;
@@ -1452,6 +1501,12 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
                               hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)fused_lds_bytes(md)) == hipSuccess &&
                               hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kFusedThreads, fused_lds_bytes(md)) == hipSuccess &&
                               per_cu >= 1 && md.KV * kFusedMaxSplits <= h->fused_grid;
+                void *sfn = stream_kernel_for(md);
+                per_cu = 0;
+                md.stream_ok = md.fused_ok && sfn && stream_lds_bytes(md) <= h->lds_per_block &&
+                               hipFuncSetAttribute(sfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)stream_lds_bytes(md)) == hipSuccess &&
+                               hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sfn, kStreamThreads, stream_lds_bytes(md)) == hipSuccess &&
+                               per_cu >= 1;
             }
         }
         HIP_TRY(h, hipHostMalloc((void **)&h->h_model, std::max<size_t>((size_t)MB * MS, 64) * sizeof(int), hipHostMallocDefault));
@@ -1656,7 +1711,7 @@ ead_status ead_set_sampling(ead_handle *h, float temperature, uint64_t seed) {
 
 ead_status ead_set_fused(ead_handle *h, int32_t on) {
     if (!h) return EAD_ERR_INVALID_ARG;
-    h->fused_on = on ? 1 : 0;
+    h->fused_on = on == 2 ? 2 : (on ? 1 : 0);     // 2: the register-buffered kernel even where the streamed one is available
     return EAD_OK;
 }
 

@@ -44,9 +44,15 @@ constexpr int kFusedMaxMats = 200;   // 4 per layer + LM head
 // keep using ordinary cached / streaming loads.
 struct GridBar { unsigned *grp, *glob; int *abort_flag; unsigned epoch; };
 
-__device__ __forceinline__ void bar_arrive(GridBar &b) {
+// How the threads that run the phases of a step meet inside their workgroup.  Here: all of them, at
+// the hardware barrier.  The streamed kernel passes a policy of its own, because there the
+// hardware barrier belongs to the weight stream.
+struct BlockSync { __device__ __forceinline__ void operator()() const { __syncthreads(); } };
+
+template <typename Sync>
+__device__ __forceinline__ void bar_arrive(GridBar &b, Sync &sync) {
     wait_stores();
-    __syncthreads();
+    sync();
     b.epoch++;
     if (threadIdx.x == 0) {
         const unsigned g = blockIdx.x % kBarGroups;
@@ -57,7 +63,8 @@ __device__ __forceinline__ void bar_arrive(GridBar &b) {
 }
 
 // returns false when the barrier was abandoned
-__device__ __forceinline__ bool bar_wait(GridBar &b, int *s_ok) {
+template <typename Sync>
+__device__ __forceinline__ bool bar_wait(GridBar &b, int *s_ok, Sync &sync) {
     if (threadIdx.x == 0) {
         const unsigned target = b.epoch * kBarGroups;
         long spins = 0;
@@ -72,7 +79,7 @@ __device__ __forceinline__ bool bar_wait(GridBar &b, int *s_ok) {
         }
         *s_ok = ok;
     }
-    __syncthreads();
+    sync();
     return *s_ok != 0;
 }
 
@@ -106,7 +113,8 @@ struct FusedArgs {
 // written by other workgroups during this kernel are read with ld_coherent.
 constexpr int kStageElems = 32;      // elements per thread: K <= 32 * 512
 
-__device__ __forceinline__ void stage_norm(float *xs, float *s_red, const float *src, int K, const float *gain, float eps) {
+template <typename Sync>
+__device__ __forceinline__ void stage_norm(float *xs, float *s_red, const float *src, int K, const float *gain, float eps, Sync &sync) {
     const int tid = threadIdx.x;
     float v[kStageElems], gn[kStageElems];
 #pragma unroll
@@ -119,7 +127,7 @@ __device__ __forceinline__ void stage_norm(float *xs, float *s_red, const float 
     for (int i = 0; i < kStageElems; ++i) ss += v[i] * v[i];
     ss = wave_sum(ss);
     if ((tid & 63) == 0) s_red[tid >> 6] = ss;
-    __syncthreads();
+    sync();
     float tot = 0.f;
 #pragma unroll
     for (int w = 0; w < kFusedWaves; ++w) tot += s_red[w];
@@ -129,27 +137,28 @@ __device__ __forceinline__ void stage_norm(float *xs, float *s_red, const float 
         const int k = tid + i * kFusedThreads;
         if (k < K) xs[k] = v[i] * (inv * gn[i]);
     }
-    __syncthreads();
+    sync();
 }
 
 // first layer: the residual stream is the embedding row itself
-template <typename ST>
-__device__ __forceinline__ void stage_norm_embed(float *xs, float *s_red, const ST *src, int K, const float *gain, float eps) {
+template <typename ST, typename Sync>
+__device__ __forceinline__ void stage_norm_embed(float *xs, float *s_red, const ST *src, int K, const float *gain, float eps, Sync &sync) {
     const int tid = threadIdx.x;
     float ss = 0.f;
     for (int k = tid; k < K; k += kFusedThreads) { const float v = to_f32(src[k]); xs[k] = v; ss += v * v; }
     ss = wave_sum(ss);
     if ((tid & 63) == 0) s_red[tid >> 6] = ss;
-    __syncthreads();
+    sync();
     float tot = 0.f;
 #pragma unroll
     for (int w = 0; w < kFusedWaves; ++w) tot += s_red[w];
     const float inv = 1.0f / sqrtf(tot / (float)K + eps);
     for (int k = tid; k < K; k += kFusedThreads) xs[k] *= inv * gain[k];
-    __syncthreads();
+    sync();
 }
 
-__device__ __forceinline__ void stage_copy(float *xs, const float *src, int K) {
+template <typename Sync>
+__device__ __forceinline__ void stage_copy(float *xs, const float *src, int K, Sync &sync) {
     const int tid = threadIdx.x;
     float v[kStageElems];
 #pragma unroll
@@ -162,11 +171,12 @@ __device__ __forceinline__ void stage_copy(float *xs, const float *src, int K) {
         const int k = tid + i * kFusedThreads;
         if (k < K) xs[k] = v[i];
     }
-    __syncthreads();
+    sync();
 }
 
 // attention output = merge of the per-split partial results (S <= kFusedMaxSplits)
-__device__ __forceinline__ void stage_attn(float *xs, const float *att_o, const float2 *att_ml, int H, int hd, int S) {
+template <typename Sync>
+__device__ __forceinline__ void stage_attn(float *xs, const float *att_o, const float2 *att_ml, int H, int hd, int S, Sync &sync) {
     for (int k = threadIdx.x; k < H * hd; k += kFusedThreads) {
         const int h = k / hd, dd = k % hd;
         float mm[kFusedMaxSplits], ll[kFusedMaxSplits], o[kFusedMaxSplits];
@@ -190,7 +200,7 @@ __device__ __forceinline__ void stage_attn(float *xs, const float *att_o, const 
         }
         xs[k] = acc / L;
     }
-    __syncthreads();
+    sync();
 }
 
 // ---- one linear phase --------------------------------------------------------------------------
@@ -355,9 +365,9 @@ __device__ __forceinline__ void fused_linear(const LinArgs<WT> &a, int epi, cons
 // of that KV head on one slice of the split's keys (wave w: head w % G, slice w / G), so
 // the per-lane state is one head's worth; the waves' results meet in LDS and the
 // workgroup writes one un-normalised partial per head for stage_attn to merge.
-template <typename KT, int HD, int G>
+template <typename KT, int HD, int G, typename Sync>
 __device__ __forceinline__ void fused_attention(const FusedArgs<KT> &a, const KT *kcache, const KT *vcache, int seq,
-                                                int pos, int S, float *lds) {
+                                                int pos, int S, float *lds, Sync &sync) {
     constexpr int LPK = HD / 8, KPI = 64 / LPK, NI = 4, CH = NI * KPI;
     constexpr int NS = kFusedWaves / G;            // key slices per workgroup
     const int item = blockIdx.x;
@@ -438,7 +448,7 @@ __device__ __forceinline__ void fused_attention(const FusedArgs<KT> &a, const KT
         for (int e = 0; e < 8; ++e) wo[wave * HD + dl * 8 + e] = o[e];
         if (dl == 0) { wm[wave] = active ? m : kNegBig; wl[wave] = active ? l : 0.f; }
     }
-    __syncthreads();
+    sync();
     for (int e = tid; e < G * HD; e += kFusedThreads) {
         const int gg = e / HD, dd = e % HD;
         float M = kNegBig;
@@ -470,6 +480,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_decode_fused(FusedArgs<WT> a)
     __shared__ float s_red[kFusedWaves];
     const int Kmax = max(max(a.d, a.F), a.H * HD);
     float *xs = smem, *red = smem + Kmax, *xzero = red + kFusedRbChunk * kFusedWaves * 16;   // xzero: 64 zeros
+    BlockSync sync;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m = a.fin.model_id, MB = a.fin.s.max_batch;
 
@@ -506,38 +517,38 @@ __global__ __launch_bounds__(kFusedThreads) void k_decode_fused(FusedArgs<WT> a)
     for (int ph = 0; ph < n_phases; ++ph) {
         const int kind = ph < 5 * a.L ? ph % 5 : 5, l = ph / 5;
         if (ph > 0) {
-            bar_arrive(bar);
-            if (!bar_wait(bar, &s_ok)) return;
+            bar_arrive(bar, sync);
+            if (!bar_wait(bar, &s_ok, sync)) return;
         }
         if (kind == 1) {
             const FusedLayer<WT> ly = a.layers[l];
-            fused_attention<WT, HD, G>(a, ly.kcache, ly.vcache, seq, pos, S, smem);
+            fused_attention<WT, HD, G>(a, ly.kcache, ly.vcache, seq, pos, S, smem, sync);
             continue;
         }
         LinArgs<WT> p{};
         int epi;
         if (kind == 0) {                        // RMSNorm + QKV + rotary + KV append
             const FusedLayer<WT> ly = a.layers[l];
-            if (l == 0) stage_norm_embed<WT>(xs, s_red, emb, a.d, ly.g_attn, a.eps);
-            else stage_norm(xs, s_red, a.x, a.d, ly.g_attn, a.eps);
+            if (l == 0) stage_norm_embed<WT>(xs, s_red, emb, a.d, ly.g_attn, a.eps, sync);
+            else stage_norm(xs, s_red, a.x, a.d, ly.g_attn, a.eps, sync);
             epi = EPI_QKV;
             p.Np = NQ + 2 * NK; p.K = a.d; p.out = a.q; p.ldo = NQ; p.kcache = ly.kcache; p.vcache = ly.vcache; p.vtcache = ly.vtcache;
             p.row_seq = &s_plan[0]; p.row_pos = &s_plan[1]; p.rope = a.rope; p.n_heads = a.H; p.n_kv_heads = a.KV;
             p.hd = HD; p.max_seq = a.fin.s.max_seq;
         } else if (kind == 2) {                 // output projection + residual
-            stage_attn(xs, a.att_o, a.att_ml, a.H, HD, S);
+            stage_attn(xs, a.att_o, a.att_ml, a.H, HD, S, sync);
             epi = EPI_RES;
             p.Np = a.d; p.K = NQ; p.out = a.x; p.ldo = a.d; p.res_embed = l == 0 ? emb : nullptr;
         } else if (kind == 3) {                 // RMSNorm + gate/up + SwiGLU
-            stage_norm(xs, s_red, a.x, a.d, a.layers[l].g_ffn, a.eps);
+            stage_norm(xs, s_red, a.x, a.d, a.layers[l].g_ffn, a.eps, sync);
             epi = EPI_SWIGLU;
             p.Np = 2 * a.F; p.K = a.d; p.out = a.hbuf; p.ldo = a.F;
         } else if (kind == 4) {                 // down projection + residual
-            stage_copy(xs, a.hbuf, a.F);
+            stage_copy(xs, a.hbuf, a.F, sync);
             epi = EPI_RES;
             p.Np = a.d; p.K = a.F; p.out = a.x; p.ldo = a.d;
         } else {                                // final RMSNorm + LM head, entropy statistics folded in
-            stage_norm(xs, s_red, a.x, a.d, a.g_final, a.eps);
+            stage_norm(xs, s_red, a.x, a.d, a.g_final, a.eps, sync);
             epi = EPI_LOGITS;
             p.Np = a.V; p.K = a.d; p.partials = a.lm_part;
         }
@@ -551,8 +562,8 @@ __global__ __launch_bounds__(kFusedThreads) void k_decode_fused(FusedArgs<WT> a)
             logits_flush<WT, true>(p, 0, true, st);
         }
     }
-    bar_arrive(bar);
-    if (!bar_wait(bar, &s_ok)) return;
+    bar_arrive(bar, sync);
+    if (!bar_wait(bar, &s_ok, sync)) return;
     if (blockIdx.x == 0 && wave == 0) {
         EntStat r; r.init();
         for (int i = lane; i < (int)gridDim.x * kFusedRbChunk; i += 64) {

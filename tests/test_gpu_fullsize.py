@@ -152,13 +152,14 @@ def test_llama_full_size_catchup_and_paths_agree(llama_full):
     prompt = si.prompt_np(0, "row0", 512, ss.vocab)
     e.set_gate(5, 0.0, 10)
     outs = []
-    for fused in (False, True):
+    for fused in (False, 1, 2):            # per-layer kernels; streamed persistent kernel; register-buffered one
         e.set_fused(fused)
         outs.append(e.generate([prompt], 14))
     e.set_fused(False)
-    a, b = outs
+    a, b, c = outs
     assert list(a["model_id"][0]) == [0] * 10 + [1] * 4
     assert np.abs(a["H"] - b["H"]).max() < TOL_H
+    assert np.abs(a["H"] - c["H"]).max() < TOL_H
     seq = np.concatenate([prompt, a["tokens"][0]])
     sc = e.score(1, seq[:-1], want_logits=False)
     for i in range(10, 14):

@@ -325,12 +325,16 @@ def test_fused_kernel_bf16_truncated(pair):
     tau = float(np.percentile(probe["Hbar"], 50))
     ref = oracle.generate(os_, ol, prompt, 20, 5, tau, d_min=4)
     e.set_gate(5, tau, 4)
-    e.set_fused(True)
-    rp = e.replay([prompt], ref["tokens"], ref["model_id"])
-    print(f"{pair} fused replay H err {np.abs(rp['H'][0] - ref['H']).max():.2e}", flush=True)
-    assert np.abs(rp["H"][0] - ref["H"]).max() < TOL_H
-    assert np.abs(rp["Hbar"][0] - ref["Hbar"]).max() < TOL_H
-    safe = np.abs(ref["Hbar"] - tau) > BAND
-    want_next = np.concatenate([ref["model_id"][1:], rp["next_model"][0][-1:]])
-    assert (rp["next_model"][0][safe] == want_next[safe]).all()
+    # 1: the streamed persistent kernel (weights through an LDS ring); 2: the register-buffered one
+    for fused in (1, 2):
+        e.set_fused(fused)
+        rp = e.replay([prompt], ref["tokens"], ref["model_id"])
+        print(f"{pair} fused={fused} replay H err {np.abs(rp['H'][0] - ref['H']).max():.2e}", flush=True)
+        assert np.abs(rp["H"][0] - ref["H"]).max() < TOL_H
+        assert np.abs(rp["Hbar"][0] - ref["Hbar"]).max() < TOL_H
+        safe = np.abs(ref["Hbar"] - tau) > BAND
+        assert safe.sum() >= len(safe) // 3
+        want_next = np.concatenate([ref["model_id"][1:], rp["next_model"][0][-1:]])
+        assert (rp["next_model"][0][safe] == want_next[safe]).all()
+    e.set_fused(False)
     e.close()
