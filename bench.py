@@ -584,7 +584,11 @@ def main():
         del e
         Ws = Wl = None
         torch.cuda.empty_cache()
-        leg("secondary", lambda: out.update({"secondary": run_secondary(secondary, args)}))
+        try:        # an extra: its failure is reported in place and does not fail the run
+            out["secondary"] = run_secondary(secondary, args)
+        except Exception as ex:  # noqa: BLE001
+            out["secondary"] = {"workload": secondary, "error": f"{type(ex).__name__}: {ex}"}
+            log(f"[bench] secondary workload failed: {out['secondary']['error']}")
     if errors:
         out["errors"] = errors
     print(json.dumps(out), flush=True)
