@@ -20,6 +20,13 @@
  *    parameter pair in bf16, half of that afterwards.  Everything else the
  *    library needs (KV caches, gate state, scratch) it allocates in ead_create()
  *    and frees in ead_destroy().
+ *  - Precision of a bf16 model: the matrices of the linear layers are kept as IEEE
+ *    half, which holds every bf16 value of magnitude 2^-24 .. 65504 exactly (smaller
+ *    ones round to a multiple of 2^-24); passes of three or more rows round their
+ *    activations to half as well (11 significant bits; values beyond +-65504
+ *    saturate) and accumulate in float32; passes of one or two rows keep float32
+ *    activations.  K and V are cached in bf16.  Embeddings, gains, the residual
+ *    stream, soft-max statistics and the entropy are float32 throughout.
  *  - Outputs are caller-owned host buffers unless the name ends in _dev.
  *  - A handle serves one call at a time (calls are not re-entrant).  Work is
  *    queued on ead_params.hip_stream and every call returns after its results

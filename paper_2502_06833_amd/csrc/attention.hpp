@@ -26,19 +26,18 @@ struct AttnArgs {
     float2 *part_ml;           // [T*H*max_splits]       (max, sum)
     int *tickets;              // [T*n_heads] arrival counters, zero between launches
     float *out;                // [T, H*hd] fp32 (optional)
-    bf16_t *out_tiles;         // bf16 tiles (high parts) of [T, H*hd] for an MFMA consumer (optional)
-    bf16_t *out_tiles_lo;      //   and low parts
+    bf16_t *out_tiles;         // half-precision tiles of [T, H*hd] for an MFMA consumer (optional)
 };
 
 constexpr float kNegBig = -1e30f;
 
 template <int HD>
-__device__ __forceinline__ void attn_store(float *out, bf16_t *out_tiles, bf16_t *out_tiles_lo, int t, int H,
+__device__ __forceinline__ void attn_store(float *out, bf16_t *out_tiles, int t, int H,
                                            int col, float r, int TB) {
     if (out) out[(size_t)t * H * HD + col] = r;
     if (out_tiles) {
         const size_t off = act_tile_offset(t >> 4, col >> 5, TB) + (size_t)(((t & 15) + 16 * ((col & 31) >> 3)) * 8 + (col & 7));
-        split_bf16(r, out_tiles[off].u, out_tiles_lo[off].u);
+        out_tiles[off].u = f32_to_f16_sat(r);
     }
 }
 
@@ -215,7 +214,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void k_attn(AttnArgs<KT> a) {
             acc += s_o[w][g][dd] * c;
         }
         const int h = h0 + g;
-        if (nsplit == 1) attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, h * HD + dd, acc / L, (count + 15) >> 4);
+        if (nsplit == 1) attn_store<HD>(a.out, a.out_tiles, t, H, h * HD + dd, acc / L, (count + 15) >> 4);
         else {
             const size_t item = ((size_t)t * H + h) * a.max_splits + split;
             st_coherent(a.part_o + item * HD + dd, acc);
@@ -255,7 +254,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void k_attn(AttnArgs<KT> a) {
             L += ll[sp] * c;
             acc += oo[sp] * c;
         }
-        attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, t, H, h * HD + dd, acc / L, (count + 15) >> 4);
+        attn_store<HD>(a.out, a.out_tiles, t, H, h * HD + dd, acc / L, (count + 15) >> 4);
     }
 }
 
@@ -448,7 +447,7 @@ __global__ __launch_bounds__(kAttnMfmaWaves * 64) void k_attn_mfma(AttnArgs<bf16
                 o += s_o[w][dl][c] * cw;
             }
             const int tr = t + c / G, h = kvh * G + c % G;
-            if (nsplit == 1) attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, tr, H, h * HD + dd, o / L, (count + 15) >> 4);
+            if (nsplit == 1) attn_store<HD>(a.out, a.out_tiles, tr, H, h * HD + dd, o / L, (count + 15) >> 4);
             else {
                 const size_t item = ((size_t)tr * H + h) * a.max_splits + split;
                 st_coherent(a.part_o + item * HD + dd, o);
@@ -489,7 +488,7 @@ __global__ __launch_bounds__(kAttnMfmaWaves * 64) void k_attn_mfma(AttnArgs<bf16
             L += ll[sp] * cw;
             o += oo[sp] * cw;
         }
-        attn_store<HD>(a.out, a.out_tiles, a.out_tiles_lo, tr, H, h * HD + dd, o / L, (count + 15) >> 4);
+        attn_store<HD>(a.out, a.out_tiles, tr, H, h * HD + dd, o / L, (count + 15) >> 4);
     }
 }
 

@@ -14,6 +14,8 @@ constexpr int kLaneElems = 8;   // elements one lane holds of a tile
 struct bf16_t { uint16_t u; };
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8_t;
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x4e_t __attribute__((ext_vector_type(4)));
@@ -31,12 +33,27 @@ template <typename T> __device__ __forceinline__ T from_f32(float f);
 template <> __device__ __forceinline__ float from_f32<float>(float f) { return f; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) { bf16_t r; r.u = f32_to_bf16(f); return r; }
 
-// x = hi + lo with both parts bf16: an activation tile kept as two bf16 tiles carries
-// about 16 significant bits through the bf16 matrix cores.
+// x = hi + lo with both parts bf16: the attention kernels keep their query and probability
+// operands this way (about 16 significant bits through the bf16 matrix cores, whose other operand
+// is the bf16 K/V cache as it lies in memory).
 __device__ __forceinline__ void split_bf16(float f, uint16_t &hi, uint16_t &lo) {
     hi = f32_to_bf16(f);
     lo = f32_to_bf16(f - bf16_to_f32(hi));
 }
+
+// ---- IEEE half: the storage format of the linear layers' matrix-core operands ----------------
+// The weights of a bf16 model are re-encoded as IEEE half when they are tiled: a bf16 value has 8
+// significant bits and half has 11, so every weight of magnitude 2^-24 .. 65504 keeps its value
+// bit for bit (smaller ones, far below anything a trained or randomly initialised matrix relies
+// on, round to a multiple of 2^-24).  The activations of the matrix-core kernels are rounded
+// to half as well (relative error 2^-12, eight times finer than bf16), so one f16 product per
+// weight tile replaces the two a bf16 hi + lo activation pair needs.  Half tops out at 65504:
+// activation values beyond that saturate instead of turning infinite.
+__device__ __forceinline__ uint16_t f32_to_f16_sat(float f) {
+    const _Float16 h = (_Float16)fminf(fmaxf(f, -65504.f), 65504.f);
+    return __builtin_bit_cast(uint16_t, h);
+}
+__device__ __forceinline__ float f16_to_f32(uint16_t u) { return (float)__builtin_bit_cast(_Float16, u); }
 
 template <typename V> using gptr = const V __attribute__((address_space(1))) *;
 
@@ -54,6 +71,18 @@ template <> struct Vec8<bf16_t> {
         f[4] = __uint_as_float(raw.z << 16); f[5] = __uint_as_float(raw.z & 0xFFFF0000u);
         f[6] = __uint_as_float(raw.w << 16); f[7] = __uint_as_float(raw.w & 0xFFFF0000u);
     }
+    // the same 16 bytes read as eight halves: weight tiles of a bf16 model (see above)
+    __device__ __forceinline__ void unpack_w(float (&f)[8]) const {
+        // element by element through scalars: a bit cast of raw.y taken as a vector element came out as raw.x
+        const uint32_t w0 = raw.x, w1 = raw.y, w2 = raw.z, w3 = raw.w;
+        f[0] = f16_to_f32((uint16_t)w0); f[1] = f16_to_f32((uint16_t)(w0 >> 16));
+        f[2] = f16_to_f32((uint16_t)w1); f[3] = f16_to_f32((uint16_t)(w1 >> 16));
+        f[4] = f16_to_f32((uint16_t)w2); f[5] = f16_to_f32((uint16_t)(w2 >> 16));
+        f[6] = f16_to_f32((uint16_t)w3); f[7] = f16_to_f32((uint16_t)(w3 >> 16));
+        // keep the conversions as conversions: folded into mixed-precision multiply-adds the FMA kernels ran 4 % slower
+#pragma unroll
+        for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(f[e]));
+    }
     __device__ __forceinline__ void zero() { raw = u32x4_t{0u, 0u, 0u, 0u}; }
 };
 template <> struct Vec8<float> {
@@ -66,6 +95,7 @@ template <> struct Vec8<float> {
     __device__ __forceinline__ void unpack(float (&f)[8]) const {
         f[0] = lo.x; f[1] = lo.y; f[2] = lo.z; f[3] = lo.w; f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
     }
+    __device__ __forceinline__ void unpack_w(float (&f)[8]) const { unpack(f); }      // float weights are stored as they are
     __device__ __forceinline__ void zero() { lo = f32x4e_t{0.f, 0.f, 0.f, 0.f}; hi = lo; }
 };
 
@@ -82,6 +112,18 @@ template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t *p, const floa
     r.w = (uint32_t)f32_to_bf16(f[6]) | ((uint32_t)f32_to_bf16(f[7]) << 16);
     *reinterpret_cast<uint4 *>(p) = r;
 }
+
+// eight values as halves (weight tiles of a bf16 model, activation tiles); float weights stay float
+__device__ __forceinline__ void store8_half(bf16_t *p, const float (&f)[8]) {
+    uint4 r;
+    r.x = (uint32_t)f32_to_f16_sat(f[0]) | ((uint32_t)f32_to_f16_sat(f[1]) << 16);
+    r.y = (uint32_t)f32_to_f16_sat(f[2]) | ((uint32_t)f32_to_f16_sat(f[3]) << 16);
+    r.z = (uint32_t)f32_to_f16_sat(f[4]) | ((uint32_t)f32_to_f16_sat(f[5]) << 16);
+    r.w = (uint32_t)f32_to_f16_sat(f[6]) | ((uint32_t)f32_to_f16_sat(f[7]) << 16);
+    *reinterpret_cast<uint4 *>(p) = r;
+}
+__device__ __forceinline__ void store8_w(float *p, const float (&f)[8]) { store8<float>(p, f); }
+__device__ __forceinline__ void store8_w(bf16_t *p, const float (&f)[8]) { store8_half(p, f); }
 
 // ---- device-coherent scalar accesses -----------------------------------------------------
 // Relaxed agent-scope atomics: the store is written through to memory and the load is
@@ -122,7 +164,7 @@ __device__ __forceinline__ float wave_max(float v) {
 // tiles of 16 rows x 32 columns.  Tile (rb, kc) occupies 512 consecutive elements at
 // (rb * K/32 + kc) * 512; inside it, lane l of a wave owns the 8 elements
 //   row rb*16 + (l & 15), columns kc*32 + (l >> 4)*8 .. +8
-// at offset l*8.  This is the register layout of the A operand of the 16x16x32 MFMA,
+// at offset l*8 (2-byte elements are IEEE halves, see above).  This is the register layout of the A operand of the 16x16x32 MFMA,
 // so a wave reads a whole row block as one contiguous, fully coalesced stream whether
 // it feeds the matrix cores or plain FMAs.
 __host__ __device__ __forceinline__ size_t tile_offset(int rb, int kc, int KC) {

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256) void k_pack_weights(const WT *s0, const WT *s1
     }
     Vec8<WT> v; v.load(src + k);
     float f[8]; v.unpack(f);
-    store8<WT>(dst + chunk * 8, f);
+    store8_w(dst + chunk * 8, f);            // bf16 weights are re-encoded as halves (exact, see common.hpp)
 }
 
 template <typename WT>
@@ -167,7 +167,7 @@ struct HostSeq { int len, kvlen[2], model, c, ngen, done, last_step, goal; };
 struct LaneSet {
     hipStream_t stream = nullptr;
     float *x = nullptr, *q = nullptr, *o = nullptr, *hbuf = nullptr;
-    bf16_t *xp_a = nullptr, *xp_o = nullptr, *xp_h = nullptr, *xl_a = nullptr, *xl_o = nullptr, *xl_h = nullptr;
+    bf16_t *xp_a = nullptr, *xp_o = nullptr, *xp_h = nullptr;
     float *sk_part = nullptr; int *sk_tickets = nullptr;
     float *part_o = nullptr; float2 *part_ml = nullptr; int *tickets = nullptr; EntPartial *lm_part = nullptr;
     Plan plan{};
@@ -183,7 +183,7 @@ struct ead_handle {
     size_t lds_per_block = 65536;        // most LDS one workgroup may ask for on this device
     SeqState s; Plan plan; GateCfg cfg;
     // scratch
-    float *x, *q, *o, *hbuf; bf16_t *xp_a, *xp_o, *xp_h, *xl_a, *xl_o, *xl_h;
+    float *x, *q, *o, *hbuf; bf16_t *xp_a, *xp_o, *xp_h;
     float *sk_part; int *sk_tickets;     // split-K partial sums of the MFMA path
     float *part_o; float2 *part_ml; int *tickets; EntPartial *lm_part; float *logits_dump; float *sc_H; int *sc_arg;
     int *h_model, *h_done;   // pinned
@@ -225,7 +225,7 @@ void use_lane(ead_handle *h, int i) {
     const LaneSet &l = h->lanes[i];
     h->stream = l.stream;
     h->x = l.x; h->q = l.q; h->o = l.o; h->hbuf = l.hbuf;
-    h->xp_a = l.xp_a; h->xp_o = l.xp_o; h->xp_h = l.xp_h; h->xl_a = l.xl_a; h->xl_o = l.xl_o; h->xl_h = l.xl_h;
+    h->xp_a = l.xp_a; h->xp_o = l.xp_o; h->xp_h = l.xp_h;
     h->sk_part = l.sk_part; h->sk_tickets = l.sk_tickets;
     h->part_o = l.part_o; h->part_ml = l.part_ml; h->tickets = l.tickets; h->lm_part = l.lm_part;
     h->plan = l.plan;
@@ -234,7 +234,7 @@ void use_lane(ead_handle *h, int i) {
 void save_lane(ead_handle *h, int i) {
     LaneSet &l = h->lanes[i];
     l.x = h->x; l.q = h->q; l.o = h->o; l.hbuf = h->hbuf;
-    l.xp_a = h->xp_a; l.xp_o = h->xp_o; l.xp_h = h->xp_h; l.xl_a = h->xl_a; l.xl_o = h->xl_o; l.xl_h = h->xl_h;
+    l.xp_a = h->xp_a; l.xp_o = h->xp_o; l.xp_h = h->xp_h;
     l.sk_part = h->sk_part; l.sk_tickets = h->sk_tickets;
     l.part_o = h->part_o; l.part_ml = h->part_ml; l.tickets = h->tickets; l.lm_part = h->lm_part;
     l.plan = h->plan;
@@ -638,9 +638,9 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         a.rope = m.rope; a.n_heads = m.H; a.n_kv_heads = m.KV; a.hd = hd; a.max_seq = h->s.max_seq;
         if (mfma) {
             if constexpr (is_bf16) {
-                PackArgs pa{h->x, d, cnt, nullptr, ly.g_attn, m.eps, h->xp_a, h->xl_a, d};
+                PackArgs pa{h->x, d, cnt, nullptr, ly.g_attn, m.eps, h->xp_a, d};
                 { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa); }
-                a.xp = h->xp_a; a.xp_lo = h->xl_a;
+                a.xp = h->xp_a;
                 launch_mfma<EPI_QKV>(h, mi, a, T);
             }
         } else {
@@ -653,23 +653,23 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         at.row_seq = h->plan.row_seq; at.row_pos = h->plan.row_pos; at.n_heads = m.H; at.n_kv_heads = m.KV;
         at.max_seq = h->s.max_seq; at.chunk = chunk; at.max_splits = max_splits; at.scale = 1.0f / sqrtf((float)hd);
         at.part_o = h->part_o; at.part_ml = h->part_ml; at.tickets = h->tickets;
-        if (mfma) { at.out_tiles = h->xp_o; at.out_tiles_lo = h->xl_o; } else at.out = h->o;
+        if (mfma) at.out_tiles = h->xp_o; else at.out = h->o;
         if (hd == 32) launch_attn<WT, 32>(h, mi, at, m.H / m.KV, T, attn_bytes);
         else if (hd == 64) launch_attn<WT, 64>(h, mi, at, m.H / m.KV, T, attn_bytes);
         else launch_attn<WT, 128>(h, mi, at, m.H / m.KV, T, attn_bytes);
         // ---- output projection + residual ----
         LinArgs<WT> b{};
         b.W = (const WT *)ly.wo; b.Np = d; b.K = NQ; b.count = cnt; b.out = h->x; b.ldo = d;
-        if (mfma) { if constexpr (is_bf16) { b.xp = h->xp_o; b.xp_lo = h->xl_o; launch_mfma<EPI_RES>(h, mi, b, T); } }
+        if (mfma) { if constexpr (is_bf16) { b.xp = h->xp_o; launch_mfma<EPI_RES>(h, mi, b, T); } }
         else { b.x = h->o; b.ldx = NQ; launch_valu<WT, EPI_RES>(h, mi, b, T, d / 16); }
         // ---- RMSNorm + gate/up + SwiGLU ----
         LinArgs<WT> c{};
         c.W = (const WT *)ly.wgu; c.Np = 2 * F; c.K = d; c.count = cnt; c.ldo = F;
         if (mfma) {
             if constexpr (is_bf16) {
-                PackArgs pa{h->x, d, cnt, nullptr, ly.g_ffn, m.eps, h->xp_a, h->xl_a, d};
+                PackArgs pa{h->x, d, cnt, nullptr, ly.g_ffn, m.eps, h->xp_a, d};
                 { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3(T16), dim3(256), 0, st, pa); }
-                c.xp = h->xp_a; c.xp_lo = h->xl_a; c.out_tiles = h->xp_h; c.out_tiles_lo = h->xl_h; c.tbs = T16 / 16;
+                c.xp = h->xp_a; c.out_tiles = h->xp_h; c.tbs = T16 / 16;
                 launch_mfma<EPI_SWIGLU>(h, mi, c, T);
             }
         } else {
@@ -680,7 +680,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         // ---- down projection + residual ----
         LinArgs<WT> e{};
         e.W = (const WT *)ly.wdown; e.Np = d; e.K = F; e.count = cnt; e.out = h->x; e.ldo = d;
-        if (mfma) { if constexpr (is_bf16) { e.xp = h->xp_h; e.xp_lo = h->xl_h; launch_mfma<EPI_RES>(h, mi, e, T); } }
+        if (mfma) { if constexpr (is_bf16) { e.xp = h->xp_h; launch_mfma<EPI_RES>(h, mi, e, T); } }
         else { e.x = h->hbuf; e.ldx = F; launch_valu<WT, EPI_RES>(h, mi, e, T, d / 16); }
     }
     if (n_lm > 0) {
@@ -695,9 +695,9 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         const int grid = std::min(m.V / 16, h->lm_grid);
         if (is_bf16 && n_lm > 2) {
             if constexpr (is_bf16) {
-                PackArgs pa{h->x, d, cnt + 1, h->plan.lm_row, m.g_final, m.eps, h->xp_a, h->xl_a, d};
+                PackArgs pa{h->x, d, cnt + 1, h->plan.lm_row, m.g_final, m.eps, h->xp_a, d};
                 { ProfScope ps(h, PK_PACK_ACT, mi, 0.0); hipLaunchKernelGGL(k_pack_act, dim3((n_lm + 15) & ~15), dim3(256), 0, st, pa); }
-                g.xp = h->xp_a; g.xp_lo = h->xl_a;
+                g.xp = h->xp_a;
                 launch_mfma<EPI_LOGITS>(h, mi, g, n_lm, grid);
             }
         } else {
@@ -1446,10 +1446,6 @@ ead_status ead_create(const ead_model_desc *small_model, const ead_model_desc *l
             TRY(dmalloc(h, &h->x, T * dmax)); TRY(dmalloc(h, &h->q, T * qmax)); TRY(dmalloc(h, &h->o, T * qmax));
             TRY(dmalloc(h, &h->hbuf, T * fmax_));
             TRY(dmalloc(h, &h->xp_a, T * dmax)); TRY(dmalloc(h, &h->xp_o, T * qmax)); TRY(dmalloc(h, &h->xp_h, T * fmax_));
-            TRY(dmalloc(h, &h->xl_a, T * dmax)); TRY(dmalloc(h, &h->xl_o, T * qmax)); TRY(dmalloc(h, &h->xl_h, T * fmax_));
-            HIP_TRY(h, hipMemsetAsync(h->xl_a, 0, T * dmax * 2, h->stream));
-            HIP_TRY(h, hipMemsetAsync(h->xl_o, 0, T * qmax * 2, h->stream));
-            HIP_TRY(h, hipMemsetAsync(h->xl_h, 0, T * fmax_ * 2, h->stream));
             HIP_TRY(h, hipMemsetAsync(h->xp_a, 0, T * dmax * 2, h->stream));
             HIP_TRY(h, hipMemsetAsync(h->xp_o, 0, T * qmax * 2, h->stream));
             HIP_TRY(h, hipMemsetAsync(h->xp_h, 0, T * fmax_ * 2, h->stream));

@@ -277,7 +277,7 @@ __device__ __forceinline__ float group_step(Vec8<WT> (&buf)[U], IssueCursor<WT> 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         float wf[8];
-        buf[u].unpack(wf);
+        buf[u].unpack_w(wf);
         const float *xp = (kc + u < kc1) ? xq + (kc + u) * 32 : xzero;
         const float4 x0 = *reinterpret_cast<const float4 *>(xp);
         const float4 x1 = *reinterpret_cast<const float4 *>(xp + 4);

@@ -4,10 +4,10 @@
 // Two kernels share the tiled weight layout and the epilogues:
 //   k_linear_valu  plain FMA path for a handful of token rows (and for fp32 weights);
 //                  activations stay fp32, staged once per workgroup in LDS.
-//   k_linear_mfma  16x16x32 bf16 MFMA path for two or more token rows (batched decode,
-//                  catch-up chunks, prompt prefill); activations are bf16 tiles.
+//   k_linear_mfma  16x16x32 f16 MFMA path for two or more token rows (batched decode,
+//                  catch-up chunks, prompt prefill); activations are half-precision tiles.
 // In both, a workgroup owns 16-row blocks of W and its waves split K, so a wave reads
-// contiguous streams of 1 KB (bf16) tiles; partial sums meet in LDS and are added in wave
+// contiguous streams of 1 KB (2-byte) tiles; partial sums meet in LDS and are added in wave
 // order, so a row's result does not depend on how many rows are in flight.
 #pragma once
 #include "common.hpp"
@@ -26,16 +26,14 @@ struct LinArgs {
     const int *rowmap;      // optional: activation row r reads x[rowmap[r]] (LM head), else x[r]
     const float *x;         // fp32 activations [*, ldx]        (VALU path)
     int ldx;
-    const bf16_t *xp;       // bf16 activation tiles [ceil(rows/16)][K/32][64][8] (MFMA path): high parts
-    const bf16_t *xp_lo;    //   and low parts (activation = hi + lo)
+    const bf16_t *xp;       // half-precision activation tiles [K/32][ceil(rows/16)][64][8] (MFMA path; the element type only names the width)
     const float *gain;      // RMSNorm gain (VALU path prologue), null = no norm
     float eps;
     // outputs
     float *out;             // RES: residual stream [T, ldo] (+=); SWIGLU: h [T, ldo]; QKV: q [T, ldo]
     int ldo;
     const WT *res_embed;    // RES, optional: the residual is this embedding row instead of out (first layer)
-    bf16_t *out_tiles;      // SWIGLU, optional: h as bf16 tiles (high parts) for the next MFMA layer
-    bf16_t *out_tiles_lo;   //   and low parts
+    bf16_t *out_tiles;      // SWIGLU, optional: h as half-precision tiles for the next MFMA layer
     int tbs;                // token blocks of the pass, (count + 15) / 16: the stride of activation tiles (xp, out_tiles) along k
     // QKV
     WT *kcache, *vcache;    // this layer's cache, [seq][kv_head][max_seq][hd]
@@ -106,7 +104,7 @@ __device__ __forceinline__ void epilogue(const LinArgs<WT> &a, int p, int t, flo
             if (a.out) put(a.out + (size_t)t * a.ldo + i, h, COH);
             if (a.out_tiles) {
                 size_t off = act_tile_offset(t >> 4, i >> 5, a.tbs) + (size_t)(((t & 15) + 16 * ((i & 31) >> 3)) * 8 + (i & 7));
-                split_bf16(h, a.out_tiles[off].u, a.out_tiles_lo[off].u);
+                a.out_tiles[off].u = f32_to_f16_sat(h);
             }
         }
     } else if constexpr (EPI == EPI_QKV) {
@@ -262,7 +260,7 @@ __global__ __launch_bounds__(NW * 64) void k_linear_valu(LinArgs<WT> a) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     float wf[8];
-                    cur[u].unpack(wf);
+                    cur[u].unpack_w(wf);
                     const int kk = min(kc + u, kc1 - 1);          // tiles past the end are zero
 #pragma unroll
                     for (int tc = 0; tc < TC; ++tc) {
@@ -307,10 +305,11 @@ __global__ __launch_bounds__(NW * 64) void k_linear_valu(LinArgs<WT> a) {
 // take most of a compute unit's load-issue cycles at a batch of 32.  Fetches run a ring of
 // D k tiles ahead of the matrix cores; the ring slots are register arrays indexed by the
 // unrolled loop, so nothing is copied and a wave keeps D * R KB of weights in flight.
-// Activations are hi + lo bf16 tile pairs (two MFMAs per weight tile): with bf16-rounded
-// activations alone the logits of a 32-layer model drift past 2 % of their range, and the
-// matrix cores have an order of magnitude of headroom at these widths.  Every output
-// element accumulates its k tiles in ascending order (lo, then hi) and the waves' sums
+// Both operands are IEEE halves (common.hpp): the weights keep their bf16 values exactly, the
+// activations are rounded to 11 significant bits (with bf16-rounded activations the logits of a
+// full-depth model drift well past their tolerance; a bf16 hi + lo pair, which this path used
+// first, costs two products and twice the activation traffic per weight tile).  Every output
+// element accumulates its k tiles in ascending order and the waves' sums
 // are added in wave order, whatever R, NT and D are: a row's result does not depend
 // on how many rows share the pass (NW is fixed per matrix shape).  Matrices with few row
 // blocks and a long K are also split along K over KS workgroups per group (SK), whose sums
@@ -341,12 +340,10 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma(LinArgs<bf16_t> a) {
         EntStat st[NE];
 #pragma unroll
         for (int i = 0; i < NE; ++i) st[i].init();
-        const bf16_t *xh[NT], *xl[NT];
+        const bf16_t *xh[NT];
 #pragma unroll
-        for (int b = 0; b < NT; ++b) {       // token blocks past the end repeat the last one; their results are dropped
-            const size_t o = act_tile_offset(min(tb0 + b, TB - 1), kc0, TB) + lane * 8;
-            xh[b] = a.xp + o; xl[b] = a.xp_lo + o;
-        }
+        for (int b = 0; b < NT; ++b)         // token blocks past the end repeat the last one; their results are dropped
+            xh[b] = a.xp + act_tile_offset(min(tb0 + b, TB - 1), kc0, TB) + lane * 8;
         const int gstep = SK ? NG : (int)gridDim.x;
         for (int g = SK ? (int)blockIdx.x / KS : (int)blockIdx.x; g < NG; g += gstep) {
             f32x4_t acc[R][NT];
@@ -357,7 +354,7 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma(LinArgs<bf16_t> a) {
                 for (int b = 0; b < NT; ++b) acc[r][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
                 wp[r] = a.W + tile_offset(min(g * R + r, NB - 1), kc0, KC) + lane * 8;
             }
-            Vec8<bf16_t> wa[D][R], xa[D][NT], la[D][NT];
+            Vec8<bf16_t> wa[D][R], xa[D][NT];
             // k tile i of the wave's range into ring slot s; past the end the last tile is
             // fetched again (from cache) and not used, so no branch surrounds the loads
             auto issue = [&](int s, int i) __attribute__((always_inline)) {
@@ -365,7 +362,7 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma(LinArgs<bf16_t> a) {
 #pragma unroll
                 for (int r = 0; r < R; ++r) wa[s][r].load_stream(wp[r] + off);
 #pragma unroll
-                for (int b = 0; b < NT; ++b) { xa[s][b].load(xh[b] + xoff); la[s][b].load(xl[b] + xoff); }
+                for (int b = 0; b < NT; ++b) xa[s][b].load(xh[b] + xoff);
             };
 #pragma unroll
             for (int s = 0; s < D; ++s) {    // in slot order: the waits below count on it
@@ -379,12 +376,9 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma(LinArgs<bf16_t> a) {
 #pragma unroll
                         for (int r = 0; r < R; ++r) {
 #pragma unroll
-                            for (int b = 0; b < NT; ++b) {
-                                acc[r][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    __builtin_bit_cast(bf16x8_t, wa[s][r].raw), __builtin_bit_cast(bf16x8_t, la[s][b].raw), acc[r][b], 0, 0, 0);
-                                acc[r][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    __builtin_bit_cast(bf16x8_t, wa[s][r].raw), __builtin_bit_cast(bf16x8_t, xa[s][b].raw), acc[r][b], 0, 0, 0);
-                            }
+                            for (int b = 0; b < NT; ++b)
+                                acc[r][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                                    __builtin_bit_cast(f16x8_t, wa[s][r].raw), __builtin_bit_cast(f16x8_t, xa[s][b].raw), acc[r][b], 0, 0, 0);
                         }
                     }
                     // the slot is refilled only after its last reader has been issued: moved any
@@ -493,13 +487,13 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma(LinArgs<bf16_t> a) {
 // ------------------------------------------------------------------------------------
 // MFMA path for passes of more than 64 token rows (catch-up chunks of many rows, prompt
 // prefill): 128 token rows per sweep over the weights.  The activation tiles of a k step
-// (16 KB for 128 rows, hi + lo) no longer fit a wave's registers next to a fetch ring, and every
+// (8 KB for 128 rows) no longer fit a wave's registers next to a fetch ring, and every
 // wave needs all of them, so the four waves of a workgroup walk K together: each fetches a
 // quarter of the step's activation tiles (ring of DA steps, like its R weight tiles), the
 // quarters meet in LDS (two buffers, one barrier per step), and every wave multiplies its own
 // 16 R weight rows with all 128 token rows.  No sums cross waves; a wave turns its accumulators
 // to the epilogue's (token column, weight row) order through a private 1 KB of LDS.
-// Each output element still accumulates its k tiles in ascending order, lo before hi.
+// Each output element still accumulates its k tiles in ascending order.
 // ------------------------------------------------------------------------------------
 // One 16 x 16 block of results in the matrix cores' layout (lane L: weight rows 4*(L/16)..+3 of
 // token column L%16) -> the epilogue, which wants neighbouring lanes to hold neighbouring weight
@@ -535,8 +529,8 @@ constexpr int kWideTok = 8;          // token blocks (of 16 rows) per sweep
 // row blocks and 16 NW TPW token rows per sweep; each of its NW waves owns TPW (1 or 2) token blocks
 // and all RG row blocks.  NW follows the pass: four waves for up to 64 rows (TPW = 1) and for sweeps of
 // 128 (TPW = 2), five to eight waves with one block each for 65-128 rows, so that a pass of 72 rows
-// multiplies and fetches five blocks' worth, not eight.  A wave's activation fragments (hi and lo
-// of its blocks) come straight from memory in the matrix cores' operand layout and are never
+// multiplies and fetches five blocks' worth, not eight.  A wave's activation fragments (of its
+// blocks) come straight from memory in the matrix cores' operand layout and are never
 // shared; the step's RG weight tiles, of which each wave fetches at most two, go through LDS (8 KB read per
 // wave and step; sharing the activation tiles instead, with a row-block pair per wave, reads 16 KB
 // and is no faster).  SK: workgroup (g, ks) takes slab ks of K for group g (one sweep only: TB <= NW TPW)
@@ -569,7 +563,7 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
 
     for (int tb0 = tb_first; tb0 < TB; tb0 += one_sweep ? TB : NT) {
         f32x4_t acc[RG][TPW];
-        const bf16_t *wp[WPT], *bp[2 * TPW];
+        const bf16_t *wp[WPT], *bp[TPW];
 #pragma unroll
         for (int j = 0; j < RG; ++j)
 #pragma unroll
@@ -580,16 +574,15 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
 #pragma unroll
         for (int q = 0; q < TPW; ++q) {
             const int blk = min(tb0 + wave * TPW + q, TB - 1);
-            bp[q] = a.xp_lo + act_tile_offset(blk, kbase, TB) + lane * 8;          // lo of block q, then hi
-            bp[TPW + q] = a.xp + act_tile_offset(blk, kbase, TB) + lane * 8;
+            bp[q] = a.xp + act_tile_offset(blk, kbase, TB) + lane * 8;
         }
-        Vec8<bf16_t> wa[DA][WPT], ba[DA][2 * TPW];
+        Vec8<bf16_t> wa[DA][WPT], ba[DA][TPW];
         auto issue = [&](int s, int i) __attribute__((always_inline)) {
             const size_t off = (size_t)min(i, KC - 1) * 512;
 #pragma unroll
             for (int q = 0; q < WPT; ++q) wa[s][q].load_stream(wp[q] + off);
 #pragma unroll
-            for (int q = 0; q < 2 * TPW; ++q) ba[s][q].load(bp[q] + off * TB);
+            for (int q = 0; q < TPW; ++q) ba[s][q].load(bp[q] + off * TB);
         };
 #pragma unroll
         for (int s = 0; s < DA; ++s) {
@@ -611,16 +604,13 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
 #pragma unroll
                     for (int j = 0; j < RG; ++j) fw[j] = *reinterpret_cast<const u32x4_t *>(&buf[j][lane * 8]);
                     __builtin_amdgcn_sched_barrier(0);
-                    // lo products of all accumulators, then the hi products: neighbouring
-                    // products never wait for each other's result
+                    // neighbouring products go to different accumulators: none waits for another's result
 #pragma unroll
-                    for (int h = 0; h < 2; ++h)
+                    for (int j = 0; j < RG; ++j)
 #pragma unroll
-                        for (int j = 0; j < RG; ++j)
-#pragma unroll
-                            for (int q = 0; q < TPW; ++q)
-                                acc[j][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    __builtin_bit_cast(bf16x8_t, fw[j]), __builtin_bit_cast(bf16x8_t, ba[s][h * TPW + q].raw), acc[j][q], 0, 0, 0);
+                        for (int q = 0; q < TPW; ++q)
+                            acc[j][q] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                                __builtin_bit_cast(f16x8_t, fw[j]), __builtin_bit_cast(f16x8_t, ba[s][q].raw), acc[j][q], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 issue(s, i + DA);
@@ -726,12 +716,10 @@ __global__ __launch_bounds__((NW + kLsProducers) * 64) void k_linear_mfma_ls(Lin
 #pragma unroll
     for (int j = 0; j < RG; ++j) acc[j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const int blk = min(tb0 + wave, TB - 1);
-    const bf16_t *bp[2] = {a.xp_lo + act_tile_offset(blk, kbase, TB) + lane * 8,          // lo, then hi
-                           a.xp + act_tile_offset(blk, kbase, TB) + lane * 8};
-    Vec8<bf16_t> ba[DA][2];
+    const bf16_t *bp = a.xp + act_tile_offset(blk, kbase, TB) + lane * 8;
+    Vec8<bf16_t> ba[DA];
     auto issue = [&](int s, int i) __attribute__((always_inline)) {
-        const size_t off = (size_t)kstep(i) * 512 * TB;
-        ba[s][0].load(bp[0] + off); ba[s][1].load(bp[1] + off);
+        ba[s].load(bp + (size_t)kstep(i) * 512 * TB);
     };
 #pragma unroll
     for (int s = 0; s < DA; ++s) {
@@ -755,11 +743,9 @@ __global__ __launch_bounds__((NW + kLsProducers) * 64) void k_linear_mfma_ls(Lin
                 for (int j = 0; j < RG; ++j) fw[(s + 1) & 1][j] = *reinterpret_cast<const u32x4_t *>(&nxt[j][lane * 8]);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
-#pragma unroll
-                    for (int j = 0; j < RG; ++j)
-                        acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            __builtin_bit_cast(bf16x8_t, fw[s & 1][j]), __builtin_bit_cast(bf16x8_t, ba[s][h].raw), acc[j], 0, 0, 0);
+                for (int j = 0; j < RG; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                        __builtin_bit_cast(f16x8_t, fw[s & 1][j]), __builtin_bit_cast(f16x8_t, ba[s].raw), acc[j], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
             issue(s, i + DA);
@@ -811,14 +797,14 @@ __global__ __launch_bounds__(256) void k_sk_merge(LinArgs<bf16_t> a, int NGR /* 
 }
 
 // ------------------------------------------------------------------------------------
-// fp32 activations -> bf16 activation tiles, optionally through RMSNorm.
+// fp32 activations -> half-precision activation tiles, optionally through RMSNorm.
 // One workgroup per token row; rows >= count (padding of the last 16-row block) are zeroed.
 // ------------------------------------------------------------------------------------
 struct PackArgs {
     const float *x; int ldx;
     const int *count; const int *rowmap;
     const float *gain; float eps;
-    bf16_t *out, *out_lo; int K;
+    bf16_t *out; int K;
 };
 
 __global__ __launch_bounds__(256) void k_pack_act(PackArgs a) {
@@ -852,11 +838,7 @@ __global__ __launch_bounds__(256) void k_pack_act(PackArgs a) {
             }
         }
         const size_t off = act_tile_offset(t >> 4, k >> 5, (T + 15) >> 4) + (size_t)(((t & 15) + 16 * ((k & 31) >> 3)) * 8);
-        float hi[8], lo[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { hi[e] = bf16_to_f32(f32_to_bf16(f[e])); lo[e] = f[e] - hi[e]; }
-        store8<bf16_t>(a.out + off, hi);
-        store8<bf16_t>(a.out_lo + off, lo);
+        store8_half(a.out + off, f);
     }
 }
 

@@ -300,10 +300,11 @@ __device__ __forceinline__ void stream_rows(const LinArgs<bf16_t> &a, const Stre
         u32x4_t w{};
         float4 x0 = make_float4(0.f, 0.f, 0.f, 0.f), x1 = x0;
         auto multiply = [&]() {
-            acc0 += __uint_as_float(w.x << 16) * x0.x + __uint_as_float(w.x & 0xFFFF0000u) * x0.y
-                  + __uint_as_float(w.y << 16) * x0.z + __uint_as_float(w.y & 0xFFFF0000u) * x0.w;
-            acc1 += __uint_as_float(w.z << 16) * x1.x + __uint_as_float(w.z & 0xFFFF0000u) * x1.y
-                  + __uint_as_float(w.w << 16) * x1.z + __uint_as_float(w.w & 0xFFFF0000u) * x1.w;
+            Vec8<bf16_t> t8; t8.raw = w;
+            float wf[8];
+            t8.unpack_w(wf);
+            acc0 += wf[0] * x0.x + wf[1] * x0.y + wf[2] * x0.z + wf[3] * x0.w;
+            acc1 += wf[4] * x1.x + wf[5] * x1.y + wf[6] * x1.z + wf[7] * x1.w;
         };
         for (int t = 0; t < nt; ++t) {
             asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");

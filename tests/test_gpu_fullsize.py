@@ -103,8 +103,9 @@ def test_qwen_full_depth_wide_passes_and_what_the_bf16_cache_costs():
 
     What holds at every position: the entropy within 1e-2 nats, and the same logits whichever pass computed
     them (passes served by one kernel family agree bit for bit; families differ by the order of their fp32
-    sums, amplified by 48 layers to 4e-3 of the row maximum, an order of magnitude below the error against
-    the oracle).  The logits themselves stay within 2e-2 of
+    sums and by where the half-precision rounding of the matrix-core kernels' activations falls, amplified by
+    48 layers to 7e-3 of the row maximum, several times below the error against the oracle).  The logits
+    themselves stay within 2e-2 of
     the row maximum only for the first positions: the kernels keep K and V in bf16 (the oracle in fp32), each
     cached element carries a relative rounding error of up to 2^-9 (1.1e-3 rms), a layer's attention output
     inherits about 2.5e-3 of that through scores and values, and 48 layers of a randomly initialised network
@@ -138,7 +139,7 @@ def test_qwen_full_depth_wide_passes_and_what_the_bf16_cache_costs():
     for n in (40, 5, 2):                                       # the same logits whichever pass computed them
         d = np.abs(outs[72]["logits"][:n] - outs[n]["logits"]).max(axis=1) / top[:n]
         print(f"  72-row pass against {n}-row pass: {d.max():.2e} of the row maximum", flush=True)
-        assert d.max() < 6e-3
+        assert d.max() < 1e-2
     e.close()
 
 
@@ -172,11 +173,19 @@ def test_llama_full_size_batch_rows_independent(llama_full):
     e, _, _ = llama_full
     ss, _ = si.PAIRS["llama"]
     prompts = [si.prompt_np(0, "row0", 300, ss.vocab), si.prompt_np(1, "row1", 77, ss.vocab)]
-    e.set_gate(5, 11.3526, 3)
+    tau = 11.3526
+    e.set_gate(5, tau, 3)
     both = e.generate(prompts, 12)
+    assert both["model_id"].min() == 0 and both["model_id"].max() == 1          # rows switch, at different steps
+    # each row alone along the trajectory it took in the batch (a free-running single run may take the
+    # other branch where a window mean falls on the threshold to the last bit): the same entropies,
+    # and the same decisions wherever the mean is not within rounding of the threshold
     for b, p in enumerate(prompts):
-        one = e.generate([p], 12)
+        one = e.replay([p], both["tokens"][b], both["model_id"][b])
         assert np.abs(one["H"][0] - both["H"][b]).max() < TOL_H
+        assert np.abs(one["Hbar"][0] - both["Hbar"][b]).max() < TOL_H
+        clear = np.abs(both["Hbar"][b] - tau)[:-1] > 1e-3
+        assert (one["next_model"][0][:-1][clear] == both["model_id"][b][1:][clear]).all()
 
 
 def test_qwen_truncated_batch_with_ragged_prompts_and_catchups():
