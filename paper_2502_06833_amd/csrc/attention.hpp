@@ -27,7 +27,13 @@ struct AttnArgs {
     int *tickets;              // [T*n_heads] arrival counters, zero between launches
     float *out;                // [T, H*hd] fp32 (optional)
     bf16_t *out_tiles;         // half-precision tiles of [T, H*hd] for an MFMA consumer (optional)
+    // k_attn_mfma, passes of up to kAttnOrderMax rows: the launch's z index -> row, longest context first.
+    // A workgroup's time follows its row's context; workgroups are dispatched in index order, so the long
+    // ones start first and the short ones fill in behind them instead of the other way round.
+    int use_order;
+    unsigned char order[128];
 };
+constexpr int kAttnOrderMax = 128;
 
 constexpr float kNegBig = -1e30f;
 
@@ -289,7 +295,7 @@ __global__ __launch_bounds__(kAttnMfmaWaves * 64) void k_attn_mfma(AttnArgs<bf16
     __shared__ float s_o[kAttnMfmaWaves][HD / 2][17];     // the waves' sums meet here, one half of hd at a time
     __shared__ float s_m[kAttnMfmaWaves][16], s_l[kAttnMfmaWaves][16];
     __shared__ int s_ticket;
-    const int t = blockIdx.z, tz = gridDim.z;
+    const int t = a.use_order ? (int)a.order[blockIdx.z] : (int)blockIdx.z, tz = gridDim.z;
     // everything the grouping needs is requested at once (indices clamped to the launch's rows)
     const int count = *a.count, pos = a.row_pos[t], prev = a.row_seq[max(t - 1, 0)];
     int rs[RQ];

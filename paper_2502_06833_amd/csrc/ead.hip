@@ -196,6 +196,7 @@ struct ead_handle {
     int prefilled = 0;                   // both caches hold the prompts of the last ead_begin and nothing has clobbered them
     std::vector<int> prompt_len;
     int sched_grouped = 0, sched_phase = 0; float sched_hi = 0.5f, sched_lo = 0.25f;
+    unsigned char attn_order[kAttnOrderMax]; int attn_order_n = 0;      // run_pass -> forward_pass: rows by falling context
     float samp_temp = 0.f; uint64_t samp_seed = 0;        // temperature 0: greedy
     int scoring = 0;                                       // inside ead_score: logits of given tokens, nothing is sampled
     ead_stats stats;
@@ -654,6 +655,7 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
         at.max_seq = h->s.max_seq; at.chunk = chunk; at.max_splits = max_splits; at.scale = 1.0f / sqrtf((float)hd);
         at.part_o = h->part_o; at.part_ml = h->part_ml; at.tickets = h->tickets;
         if (mfma) at.out_tiles = h->xp_o; else at.out = h->o;
+        if (h->attn_order_n == T) { at.use_order = 1; memcpy(at.order, h->attn_order, (size_t)T); }
         if (hd == 32) launch_attn<WT, 32>(h, mi, at, m.H / m.KV, T, attn_bytes);
         else if (hd == 64) launch_attn<WT, 64>(h, mi, at, m.H / m.KV, T, attn_bytes);
         else launch_attn<WT, 128>(h, mi, at, m.H / m.KV, T, attn_bytes);
@@ -720,6 +722,19 @@ double keys_in_pass(ead_handle *h, int mi, const std::vector<int> &rows) {
 
 ead_status run_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, bool dump, const std::vector<int> &rows) {
     const double keys = keys_in_pass(h, mi, rows);
+    // the pass's rows by falling context (plan order: sequences in index order, a sequence's rows in a row)
+    h->attn_order_n = 0;
+    if (T > 2 && T <= kAttnOrderMax) {
+        std::pair<int, int> pr[kAttnOrderMax];      // (position, row)
+        int t = 0;
+        for (int b = 0; b < h->batch; ++b)
+            for (int i = 0; i < rows[b]; ++i, ++t) pr[t] = {h->hs[b].kvlen[mi] + i, t};
+        if (t == T) {
+            std::stable_sort(pr, pr + T, [](const std::pair<int, int> &x, const std::pair<int, int> &y) { return x.first > y.first; });
+            for (int i = 0; i < T; ++i) h->attn_order[i] = (unsigned char)pr[i].second;
+            h->attn_order_n = T;
+        }
+    }
     return h->mdl[mi].dtype == EAD_BF16 ? forward_pass<bf16_t>(h, mi, T, n_lm, ctx_max, dump, keys)
                                         : forward_pass<float>(h, mi, T, n_lm, ctx_max, dump, keys);
 }
