@@ -269,7 +269,7 @@ __global__ __launch_bounds__(kAttnWaves * 64) void k_attn(AttnArgs<KT> a) {
 // KV head the kernel above spends about 5 G arithmetic instructions per byte of K/V and is
 // bound by them from G = 4 up; here scores and weighted sums are 16x16x32 products.
 //
-// A workgroup (8 waves) takes one (group of rows, KV head, key split).  A group is up to
+// A workgroup (kAttnMfmaWaves waves) takes one (group of rows, KV head, key split).  A group is up to
 // RQ = 16 / G consecutive rows of one sequence (a catch-up chunk, cut at positions that are
 // multiples of RQ): their RQ * G query vectors are the 16 columns of every product, so the
 // sequence's K and V are streamed once for all of them.  Row t leads a group unless row
@@ -285,10 +285,14 @@ __global__ __launch_bounds__(kAttnWaves * 64) void k_attn(AttnArgs<KT> a) {
 // lane % 16 in S^T and in O^T alike, so the rescale stays inside the lane.  Waves, then key
 // splits, are merged as in k_attn.
 // ------------------------------------------------------------------------------------
-constexpr int kAttnMfmaWaves = 8;
+// Four waves of about 240 registers: two workgroups share a compute unit.  With eight waves (one workgroup
+// per unit) a pass of 96 ragged rows took 62 instead of 56.5 us per layer: a wave then gets only two or three
+// key blocks at these contexts, too few for its two fetch buffers to overlap anything, and the unit idles while its
+// one workgroup merges and stores.
+constexpr int kAttnMfmaWaves = 4;
 
 template <int HD, int G>
-__global__ __launch_bounds__(kAttnMfmaWaves * 64) void k_attn_mfma(AttnArgs<bf16_t> a) {
+__global__ __launch_bounds__(kAttnMfmaWaves * 64, 2) void k_attn_mfma(AttnArgs<bf16_t> a) {
     constexpr int RQ = 16 / G;            // rows per group
     constexpr int KC = HD / 32;           // k steps of the score product
     constexpr int HB = HD / 16;           // row tiles of O^T

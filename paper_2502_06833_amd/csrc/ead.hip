@@ -624,8 +624,8 @@ ead_status forward_pass(ead_handle *h, int mi, int T, int n_lm, int ctx_max, boo
     while ((long)T * m.KV * ((ctx_max + chunk - 1) / chunk) > 1024 && chunk < 65536) chunk <<= 1;
     while ((ctx_max + chunk - 1) / chunk > kAttnMaxSplits) chunk <<= 1;
     while ((long)T * ((ctx_max + chunk - 1) / chunk) > h->items_max) chunk <<= 1;
-    // the matrix-core kernel (many rows) is bound by the latency of its short chains of loads, one
-    // workgroup per compute unit at a time: fewer, longer workgroups
+    // the matrix-core kernel (many rows) is bound by the latency of its short chains of loads, two
+    // workgroups per compute unit at a time: fewer, longer workgroups
     if (is_bf16 && m.layers[0].vtcache && T > 2 && (long)T * m.KV * ((ctx_max + chunk - 1) / chunk) > 64)
         while ((long)T * m.KV * ((ctx_max + chunk - 1) / chunk) > 2 * h->n_cu && chunk < 65536) chunk <<= 1;
     const int max_splits = (ctx_max + chunk - 1) / chunk;

@@ -807,38 +807,50 @@ struct PackArgs {
     bf16_t *out; int K;
 };
 
+constexpr int kPackVecs = 15;        // 16-byte pieces of a row per thread: K <= 15 * 4 * 256
+
 __global__ __launch_bounds__(256) void k_pack_act(PackArgs a) {
     __shared__ float s_ss[4];
     const int T = *a.count;
     const int t = blockIdx.x;
     if (t >= ((T + 15) & ~15)) return;
-    const int K = a.K, KC = K >> 5, tid = threadIdx.x;
-    float inv = 1.f;
+    const int K = a.K, tid = threadIdx.x, TB = (T + 15) >> 4;
     const float *src = t < T ? a.x + (size_t)(a.rowmap ? a.rowmap[t] : t) * a.ldx : nullptr;
-    if (a.gain && src) {
-        float ss = 0.f;
-        for (int k = tid * 4; k < K; k += 1024) {
-            float4 v = *reinterpret_cast<const float4 *>(src + k);
-            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    // the row is read once: thread tid keeps elements 4 tid + 1024 i .. + 3, i = 0, 1, ..; the gains are
+    // requested with it, so that one round trip to memory covers everything the row needs
+    float4 v[kPackVecs], g[kPackVecs];
+#pragma unroll
+    for (int i = 0; i < kPackVecs; ++i) {
+        const int k = tid * 4 + 1024 * i;
+        v[i] = make_float4(0.f, 0.f, 0.f, 0.f); g[i] = make_float4(1.f, 1.f, 1.f, 1.f);
+        if (k < K) {
+            if (src) v[i] = *reinterpret_cast<const float4 *>(src + k);
+            if (a.gain) g[i] = *reinterpret_cast<const float4 *>(a.gain + k);
         }
+    }
+    float inv = 1.f;
+    if (a.gain) {
+        float ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < kPackVecs; ++i) ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
         ss = wave_sum(ss);
         if ((tid & 63) == 0) s_ss[tid >> 6] = ss;
         __syncthreads();
         inv = 1.0f / sqrtf((s_ss[0] + s_ss[1] + s_ss[2] + s_ss[3]) / (float)K + a.eps);
     }
-    for (int k = tid * 8; k < K; k += 2048) {
-        float f[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (src) {
-            float4 v0 = *reinterpret_cast<const float4 *>(src + k), v1 = *reinterpret_cast<const float4 *>(src + k + 4);
-            f[0] = v0.x; f[1] = v0.y; f[2] = v0.z; f[3] = v0.w; f[4] = v1.x; f[5] = v1.y; f[6] = v1.z; f[7] = v1.w;
-            if (a.gain) {
-                float4 g0 = *reinterpret_cast<const float4 *>(a.gain + k), g1 = *reinterpret_cast<const float4 *>(a.gain + k + 4);
-                f[0] *= inv * g0.x; f[1] *= inv * g0.y; f[2] *= inv * g0.z; f[3] *= inv * g0.w;
-                f[4] *= inv * g1.x; f[5] *= inv * g1.y; f[6] *= inv * g1.z; f[7] *= inv * g1.w;
-            }
+#pragma unroll
+    for (int i = 0; i < kPackVecs; ++i) {
+        const int k = tid * 4 + 1024 * i;
+        if (k < K) {
+            float f[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+            if (a.gain) { f[0] *= inv * g[i].x; f[1] *= inv * g[i].y; f[2] *= inv * g[i].z; f[3] *= inv * g[i].w; }
+            // four of the eight elements a lane of the consuming product holds: 8 bytes, side by side with the neighbouring thread's
+            const size_t off = act_tile_offset(t >> 4, k >> 5, TB) + (size_t)(((t & 15) + 16 * ((k & 31) >> 3)) * 8 + (k & 7));
+            uint2 r;
+            r.x = (uint32_t)f32_to_f16_sat(f[0]) | ((uint32_t)f32_to_f16_sat(f[1]) << 16);
+            r.y = (uint32_t)f32_to_f16_sat(f[2]) | ((uint32_t)f32_to_f16_sat(f[3]) << 16);
+            *reinterpret_cast<uint2 *>(a.out + off) = r;
         }
-        const size_t off = act_tile_offset(t >> 4, k >> 5, (T + 15) >> 4) + (size_t)(((t & 15) + 16 * ((k & 31) >> 3)) * 8);
-        store8_half(a.out + off, f);
     }
 }
 
