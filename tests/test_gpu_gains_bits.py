@@ -143,3 +143,25 @@ def test_bits_through_a_handle_bf16_truncated():
     free = e.generate(prompts, 20)
     assert abs(free["H"].mean() / math.log2(ss.vocab) - 1) < 0.2    # entropies of the order of log2 V bits, not ln V nats
     e.close()
+
+
+def test_half_precision_activations_saturate_instead_of_overflowing():
+    """The matrix-core kernels round their activations to IEEE half, which ends at 65504.  A final-norm gain of
+    1e5 pushes the LM head's input past that: passes of three or more rows must saturate (finite logits and
+    entropies, arg max still defined), not produce infinities; passes of one or two rows keep float32 activations
+    and follow the oracle as always."""
+    ead = _ead()
+    ss, sl = (s.truncated(1) for s in si.PAIRS["llama"])
+    Ws = si.model_weights_torch(ss, 5, "cuda")
+    Wl = si.model_weights_torch(sl, 5, "cuda")
+    Ws["norm_final"] = Ws["norm_final"] * 1e5
+    e = ead.EAD(ss, Ws, sl, Wl, window=5, tau=0.0, d_min=4, max_batch=1, max_seq=64)
+    toks = si.prompt_np(5, "sat", 6, ss.vocab)
+    wide = e.score(0, toks)                      # 6 rows: activation tiles in half precision
+    assert np.isfinite(wide["logits"]).all() and np.isfinite(wide["H"]).all()
+    assert np.abs(wide["logits"]).max() > 1e3    # the gain did reach the logits
+    om = oracle.Model(ss, {k: v.float().cpu().numpy() for k, v in Ws.items()})
+    ref = om.forward_dense(toks[:2])
+    narrow = e.score(0, toks[:2])                # 2 rows: float32 activations, no saturation
+    check_logits(narrow["logits"], ref, TOL_LOGIT)
+    e.close()
