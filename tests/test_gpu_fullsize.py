@@ -293,3 +293,55 @@ def test_qwen_truncated_long_prefill_agrees_with_scoring():
         for i in rng:
             assert abs(sc["H"][600 + i - 1] - out["H"][0, i]) < TOL_H, (which, i)
     e.close()
+
+
+def test_qwen_full_depth_batch64_grouped_rows_follow_the_oracle():
+    """The default benchmark's launch configuration at full size: the Qwen-0.5B / Qwen-14B shaped pair at full
+    depth (24 and 48 layers), 64 ragged rows, grouped two-lane schedule.  The prompts are short (5-12 tokens) so
+    that the oracle can follow three rows through the 14B shape token by token; those rows are teacher-forced
+    along the oracle's trajectories (entropy, window mean, switch decision, arg max), the other 61 replay the
+    library's own free run.  Gains 1 + N(0, 0.3^2) and wide LM heads spread the entropies enough for most
+    decisions to fall outside the exemption band."""
+    from gpu_helpers import check_replay_row, make_pair, trajectory_logit_stats
+    ead = _ead()
+    ss, sl = si.PAIRS["qwen"]
+    n_new, d_min, w, batch, checked = 12, 3, 5, 64, (0, 21, 47)
+    print("full-depth batch 64: weights and oracle models", flush=True)
+    Ws, Wl, os_, ol = make_pair(ss, sl, seed=4, gain_std=0.3, lm_sigma=1.5)
+    lens = si.prompt_lengths(4, batch, 5, 12)
+    prompts = [si.prompt_np(4, f"fb{b}", int(lens[b]), ss.vocab) for b in range(batch)]
+    hb = np.concatenate([oracle.generate(os_, ol, prompts[b], n_new, w, 1e30, d_min=d_min)["Hbar"] for b in checked])
+    tau = float(np.percentile(hb, 55))
+    refs, stats = {}, {}
+    for b in checked:
+        print(f"full-depth batch 64: oracle row {b} (prompt of {len(prompts[b])})", flush=True)
+        refs[b] = oracle.generate(os_, ol, prompts[b], n_new, w, tau, d_min=d_min)
+        stats[b] = trajectory_logit_stats(os_, ol, prompts[b], refs[b]["tokens"], refs[b]["model_id"])
+    shares = [float(refs[b]["model_id"].mean()) for b in checked]
+    print(f"tau {tau:.4f}; large share per checked row {shares}", flush=True)
+    assert 0.0 < np.mean(shares) < 1.0
+    del os_, ol
+    e = ead.EAD(ss, Ws, sl, Wl, window=w, tau=tau, d_min=d_min, max_batch=batch, max_seq=32)
+    del Ws, Wl
+    torch.cuda.empty_cache()
+    e.set_schedule(True, 0.5, 0.25)
+    free = e.generate(prompts, n_new)
+    st = e.stats()
+    assert (free["lens"] == n_new).all() and st["switches"] > 0 and st["catchup_rows_large"] > 0
+    print(f"  free run: passes large/small {st['steps_large']}/{st['steps_small']}, large share {st['large_share']:.2f}", flush=True)
+    ft, fm = free["tokens"].copy(), free["model_id"].copy()
+    for b in checked:
+        ft[b], fm[b] = refs[b]["tokens"], refs[b]["model_id"]
+    rp = e.replay(prompts, ft, fm)
+    n_dec = n_arg = 0
+    for b in checked:
+        print(f"  row {b}: H err {np.abs(rp['H'][b] - refs[b]['H']).max():.2e}, window mean err {np.abs(rp['Hbar'][b] - refs[b]['Hbar']).max():.2e}", flush=True)
+        d, a = check_replay_row(rp, b, refs[b], tau, n_new, stats[b], tol_logit=6e-2)
+        n_dec += d; n_arg += a
+    total = len(checked) * n_new
+    print(f"  decisions checked outside the band {n_dec}/{total}, arg maxes with a clear gap {n_arg}/{total}", flush=True)
+    assert n_dec >= total // 3
+    others = [b for b in range(batch) if b not in checked]
+    assert np.abs(rp["H"][others] - free["H"][others]).max() < TOL_H
+    e.set_schedule(False)
+    e.close()
