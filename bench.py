@@ -129,6 +129,17 @@ def host_cpu():
     return name, (len(cores) or None)
 
 
+def host_mem_available():
+    """Bytes of host memory that can still be taken (MemAvailable), or None where that cannot be read."""
+    try:
+        for line in open("/proc/meminfo"):
+            if line.startswith("MemAvailable:"):
+                return 1024.0 * float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(pair_shapes, Ws, Wl, prompts, w, tau, d_min, n_prompt, n_new, budget_s=20.0, max_rows=8):
     """The oracle as it stands, timed on this host: Algorithm 1 on a bounded sample of the workload -- the
     first rows of the batch one after the other (the oracle has no batching), each with its prompt cut to
@@ -138,6 +149,12 @@ def cpu_baseline(pair_shapes, Ws, Wl, prompts, w, tau, d_min, n_prompt, n_new, b
     so the sample's rate depends on how many of its rows switch: the share is reported with it."""
     import oracle
     ss, sl = pair_shapes
+    # the oracle keeps both models in float32 on the host: refuse (the leg is then reported as failed, the
+    # JSON line is still printed) rather than be killed for memory half way through
+    need = 4.0 * (ss.n_params() + sl.n_params()) * 1.25 + 4e9
+    avail = host_mem_available()
+    if avail is not None and avail < need:
+        raise MemoryError(f"the oracle needs about {need / 1e9:.0f} GB of host memory for this pair, {avail / 1e9:.0f} GB are available")
     t0 = time.time()
     os_ = oracle.Model(ss, {k: v.float().cpu().numpy() for k, v in Ws.items()})
     ol = oracle.Model(sl, {k: v.float().cpu().numpy() for k, v in Wl.items()})

@@ -41,3 +41,8 @@ def test_host_cpu_reads_cpuinfo():
     name, cores = bench.host_cpu()
     assert name is None or isinstance(name, str)
     assert cores is None or cores >= 1
+
+
+def test_host_memory_reading():
+    avail = bench.host_mem_available()
+    assert avail is None or avail > 1e8
