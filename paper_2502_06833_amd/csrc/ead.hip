@@ -507,7 +507,7 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
 #define EAD_WT(TPW_, NW_) do { if (rg == 7) hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, TPW_, 7, NW_>), dim3(grid_wt), dim3(NW_ * 64), 0, h->stream, a); \
                                else hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, false, TPW_, 8, NW_>), dim3(grid_wt), dim3(NW_ * 64), 0, h->stream, a); } while (0)
 #define EAD_LS(NW_) (rg == 7 ? launch_ls<EPI, false, NW_, 7>(h, a, grid_wt) : launch_ls<EPI, false, NW_, 8>(h, a, grid_wt))
-                if (multi) EAD_WT(2, 4);
+                if (multi) { if (!EAD_LS(8)) EAD_WT(2, 4); }
                 else switch (nt) {      // weight tiles straight into LDS by fetching waves; the register-ring kernel where LDS does not allow it
                     case 4: if (!EAD_LS(4)) EAD_WT(1, 4); break; case 5: if (!EAD_LS(5)) EAD_WT(1, 5); break;
                     case 6: if (!EAD_LS(6)) EAD_WT(1, 6); break; case 7: if (!EAD_LS(7)) EAD_WT(1, 7); break;
@@ -515,6 +515,24 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
 #undef EAD_LS
 #undef EAD_WT
                 return;
+            }
+            // long passes (four sweeps or more) of a matrix with few row blocks: still one workgroup per
+            // (group, sweep) and no split of K -- a launch pair per sweep would stream the matrix from
+            // memory once per sweep.  Row blocks per workgroup: what fills whole rounds of the
+            // compute units best (a k step costs about 260 + 64 rg cycles)
+            if (multi && TB >= 4 * kWideTok) {
+                const int sw = (TB + nt - 1) / nt;
+                int rg = 8; long best = -1;
+                for (int r = 8; r >= 5; --r) {
+                    const long rounds = ((long)((NB + r - 1) / r) * sw + h->n_cu - 1) / h->n_cu, cost = rounds * (260 + 64 * r);
+                    if (best < 0 || cost < best) { best = cost; rg = r; }
+                }
+                const int ng = (NB + rg - 1) / rg, grid_sw = (ng + 7) / 8 * 8 * sw;
+                a.sweeps = sw;
+                const bool ok = rg == 5 ? launch_ls<EPI, false, 8, 5>(h, a, grid_sw) : rg == 6 ? launch_ls<EPI, false, 8, 6>(h, a, grid_sw)
+                              : rg == 7 ? launch_ls<EPI, false, 8, 7>(h, a, grid_sw) : launch_ls<EPI, false, 8, 8>(h, a, grid_sw);
+                if (ok) return;
+                a.sweeps = 0;
             }
             // one workgroup per compute unit at most: a second round would double the time
             int KS = std::min(kSplitKMax, std::max(1, h->n_cu / NG));
@@ -525,7 +543,7 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
                                    hipLaunchKernelGGL((k_linear_mfma_wt<6, EPI, true, TPW_, 8, NW_>), dim3(NG * KS), dim3(NW_ * 64), 0, h->stream, a); \
                                hipLaunchKernelGGL((k_sk_merge<EPI, TPW_ * NW_>), dim3((NB * TPW_ * NW_ + 3) / 4), dim3(256), 0, h->stream, a, NG * 8); } while (0)
                 for (a.tb_base = 0; a.tb_base < TB; a.tb_base += nt) {
-                    if (multi) EAD_SK(2, 4);
+                    if (multi) EAD_SK(1, 8);      // sweeps of 128 rows: eight multiplying waves, one token block each
                     else switch (nt) { case 4: EAD_SK(1, 4); break; case 5: EAD_SK(1, 5); break; case 6: EAD_SK(1, 6); break;
                                        case 7: EAD_SK(1, 7); break; default: EAD_SK(1, 8); break; }
                 }

@@ -677,8 +677,15 @@ __global__ __launch_bounds__((NW + kLsProducers) * 64) void k_linear_mfma_ls(Lin
     const int TB = (T + 15) >> 4;
     if (TB == 0) return;
     const int KS = SK ? a.KS : 1;
-    const int g = SK ? (int)blockIdx.x / KS : (int)blockIdx.x, ks = SK ? (int)blockIdx.x % KS : 0;
-    const int tb0 = SK ? a.tb_base : 0;
+    int g = SK ? (int)blockIdx.x / KS : (int)blockIdx.x, tb0 = SK ? a.tb_base : 0;
+    const int ks = SK ? (int)blockIdx.x % KS : 0;
+    if (!SK && a.sweeps > 1) {
+        // passes of more than 128 rows: one workgroup per (group, 128-row sweep), numbered as in
+        // k_linear_mfma_wt so that the sweeps of one group run at about the same time on one XCD
+        const int q = (int)blockIdx.x >> 3, r = (int)blockIdx.x & 7;
+        g = (q / a.sweeps) * 8 + r; tb0 = (q % a.sweeps) * NW;
+        if (g >= NG || tb0 >= TB) return;
+    }
     const int kbase = (ks * KCfull) / KS, KC = ((ks + 1) * KCfull) / KS - kbase;     // this workgroup's k tiles
     auto kstep = [&](int j) __attribute__((always_inline)) { return min(j, KC - 1); };      // past the end: the last step again
 
