@@ -493,7 +493,7 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
         // runs the epilogue.  Longer passes (prefill, teacher-forced scoring) take one launch pair per
         // sweep, or one workgroup per (group, sweep) where K is not split.
         // (17-32 rows: measured better for the split-K matrices, 32 against 34 us, not for gate/up, 72 against 69)
-        if (big && (TB > 2 || (TB == 2 && EPI != EPI_SWIGLU))) {
+        if ((big && (TB > 2 || (TB == 2 && EPI != EPI_SWIGLU))) || TB >= 4 * kWideTok) {
             // token blocks per sweep: four up to 64 rows; the pass's own five to eight for 65-128 rows, one
             // wave per block; eight (two per wave) for the sweeps of longer passes
             const bool multi = TB > kWideTok;
@@ -516,8 +516,8 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
 #undef EAD_WT
                 return;
             }
-            // long passes (four sweeps or more) of a matrix with few row blocks: still one workgroup per
-            // (group, sweep) and no split of K -- a launch pair per sweep would stream the matrix from
+            // long passes (four sweeps or more) of a matrix with few row blocks, or of a small matrix: still
+            // one workgroup per (group, sweep) and no split of K -- a launch pair per sweep would stream the matrix from
             // memory once per sweep.  Row blocks per workgroup: what fills whole rounds of the
             // compute units best (a k step costs about 260 + 64 rg cycles)
             if (multi && TB >= 4 * kWideTok) {
@@ -535,7 +535,7 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
                 a.sweeps = 0;
             }
             // one workgroup per compute unit at most: a second round would double the time
-            int KS = std::min(kSplitKMax, std::max(1, h->n_cu / NG));
+            int KS = big ? std::min(kSplitKMax, std::max(1, h->n_cu / NG)) : 1;
             while (KS > 1 && (a.K / 32) / KS < 16) --KS;
             if (KS > 1 && (size_t)KS * NG * 8 * nt * 256 <= kSplitKFloats) {
                 a.KS = KS; a.sk_part = h->sk_part;
