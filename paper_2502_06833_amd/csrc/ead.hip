@@ -498,6 +498,28 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
             // wave per block; eight (two per wave) for the sweeps of longer passes
             const bool multi = TB > kWideTok;
             const int NG = (NB + 7) / 8, nt = TB <= 4 ? 4 : (multi ? kWideTok : TB);
+            // passes of four sweeps or more: one workgroup per (group, sweep) for every matrix.  Cost of a
+            // launch in cycles per k tile: rounds of workgroups over the compute units times the time of a k
+            // step (measured: about 260 + 64 rg cycles with rg row blocks x 128 rows, about 1150 for the
+            // 128 x 256 tiles, which move twice the rows per step but are bound by what a compute unit
+            // can fetch); the 128 x 256 tiles win where their groups still fill the chip
+            const bool longpass = TB >= 4 * kWideTok;
+            int rg_long = 8;
+            if (longpass) {
+                const int sw = (TB + kWideTok - 1) / kWideTok, n_cu = h->n_cu;
+                auto cost_of = [&](int r) { return (((long)((NB + r - 1) / r) * sw + n_cu - 1) / n_cu) * (260 + 64 * r); };
+                long cost = -1;
+                if (EPI != EPI_QKV && cfg == 4) { rg_long = (NB + 6) / 7 <= n_cu ? 7 : 8; cost = cost_of(rg_long); }
+                else for (int r = 8; r >= 5; --r) if (cost < 0 || cost_of(r) < cost) { cost = cost_of(r); rg_long = r; }
+                const int sg = (TB + kGemmTok - 1) / kGemmTok;
+                const long cost_gemm = (((long)NG * sg + n_cu - 1) / n_cu) * 1150;
+                const void *kern = (const void *)k_linear_mfma_gemm<EPI>;
+                if (big && cost_gemm < cost && kGemmLdsBytes <= h->lds_per_block && allow_big_lds(kern, kGemmLdsBytes)) {
+                    a.sweeps = sg;
+                    hipLaunchKernelGGL((k_linear_mfma_gemm<EPI>), dim3((NG + 7) / 8 * 8 * sg), dim3(640), kGemmLdsBytes, h->stream, a);
+                    return;
+                }
+            }
             if constexpr (EPI != EPI_QKV) if (cfg == 4) {
                 // seven row blocks per workgroup where that still fits one workgroup per compute unit
                 // (1728 row blocks: 247 workgroups instead of 216 on 256 units)
@@ -516,18 +538,10 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
 #undef EAD_WT
                 return;
             }
-            // long passes (four sweeps or more) of a matrix with few row blocks, or of a small matrix: still
-            // one workgroup per (group, sweep) and no split of K -- a launch pair per sweep would stream the matrix from
-            // memory once per sweep.  Row blocks per workgroup: what fills whole rounds of the
-            // compute units best (a k step costs about 260 + 64 rg cycles)
-            if (multi && TB >= 4 * kWideTok) {
-                const int sw = (TB + nt - 1) / nt;
-                int rg = 8; long best = -1;
-                for (int r = 8; r >= 5; --r) {
-                    const long rounds = ((long)((NB + r - 1) / r) * sw + h->n_cu - 1) / h->n_cu, cost = rounds * (260 + 64 * r);
-                    if (best < 0 || cost < best) { best = cost; rg = r; }
-                }
-                const int ng = (NB + rg - 1) / rg, grid_sw = (ng + 7) / 8 * 8 * sw;
+            // long passes of a matrix with few row blocks, or of a small matrix: no split of K -- a launch pair
+            // per sweep would stream the matrix from memory once per sweep
+            if (longpass) {
+                const int sw = (TB + nt - 1) / nt, rg = rg_long, ng = (NB + rg - 1) / rg, grid_sw = (ng + 7) / 8 * 8 * sw;
                 a.sweeps = sw;
                 const bool ok = rg == 5 ? launch_ls<EPI, false, 8, 5>(h, a, grid_sw) : rg == 6 ? launch_ls<EPI, false, 8, 6>(h, a, grid_sw)
                               : rg == 7 ? launch_ls<EPI, false, 8, 7>(h, a, grid_sw) : launch_ls<EPI, false, 8, 8>(h, a, grid_sw);

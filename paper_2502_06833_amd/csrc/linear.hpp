@@ -779,6 +779,116 @@ __global__ __launch_bounds__((NW + kLsProducers) * 64) void k_linear_mfma_ls(Lin
     }
 }
 
+// ------------------------------------------------------------------------------------
+// Passes of about 500 rows and more (prompt prefill) through a large matrix.  With 128 rows per
+// workgroup every wave of k_linear_mfma_ls reads all of a step's weight tiles from LDS for one
+// token block: 8 KB of LDS reads per 8 products, which is LDS-bound at half the matrix cores'
+// rate, and every workgroup fetches its activation tiles itself.  Here a workgroup covers
+// 8 row blocks x 16 token blocks (128 output rows x 256 token rows); its two fetching waves bring
+// both the step's 8 weight tiles and its 16 activation tiles into LDS (24 KB per k step,
+// kGemmDepth steps), and each of the eight multiplying waves owns 4 row blocks x 4 token blocks:
+// 8 KB of LDS reads per 16 products.  Hand-over, slot reuse and the order of the sums of an
+// output element (k tiles in ascending order, one accumulator) are those of k_linear_mfma_ls.
+// ------------------------------------------------------------------------------------
+constexpr int kGemmDepth = 6;                        // k steps of tiles LDS holds
+constexpr int kGemmRows = 8, kGemmTok = 16;          // row blocks and token blocks per workgroup
+constexpr int kGemmTiles = kGemmRows + kGemmTok;     // 1 KB tiles per k step; each fetching wave brings half of them
+constexpr size_t kGemmLdsBytes = (size_t)kGemmDepth * kGemmTiles * 1024 + (size_t)8 * 64 * 4 * sizeof(float);
+
+template <int EPI>
+__global__ __launch_bounds__(640) void k_linear_mfma_gemm(LinArgs<bf16_t> a) {
+    constexpr int PL = kGemmTiles / 2;                 // loads per fetching wave and k step
+    static_assert(PL * (kGemmDepth - 1) <= 63, "the load counter holds 63");
+    extern __shared__ __attribute__((aligned(16))) unsigned char ls_smem[];
+    bf16_t (*s_w)[kGemmTiles][512] = reinterpret_cast<bf16_t (*)[kGemmTiles][512]>(ls_smem);    // [kGemmDepth]: weight tiles, then activation tiles
+    float (*s_t)[64][4] = reinterpret_cast<float (*)[64][4]>(ls_smem + (size_t)kGemmDepth * kGemmTiles * 1024);
+    const int KC = a.K >> 5, NB = a.Np >> 4, NG = (NB + kGemmRows - 1) / kGemmRows;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int T = *a.count;
+    const int TB = (T + 15) >> 4;
+    if (TB == 0) return;
+    // workgroup id -> (group, sweep): the sweeps of one group run at about the same time on one XCD (id % 8)
+    const int q = (int)blockIdx.x >> 3, r = (int)blockIdx.x & 7;
+    const int g = (q / a.sweeps) * 8 + r, tb0 = (q % a.sweeps) * kGemmTok;
+    if (g >= NG || tb0 >= TB) return;
+    auto kstep = [&](int j) __attribute__((always_inline)) { return min(j, KC - 1); };      // past the end: the last step again
+
+    if (wave >= 8) {
+        // ---- fetching wave p: weight tiles p, p + 2, .. and activation tiles p, p + 2, .. of every step ----
+        const int p = wave - 8;
+        const bf16_t *wp[kGemmRows / 2], *xp[kGemmTok / 2];
+#pragma unroll
+        for (int j = 0; j < kGemmRows / 2; ++j) wp[j] = a.W + tile_offset(min(g * kGemmRows + p + 2 * j, NB - 1), 0, KC) + lane * 8;
+#pragma unroll
+        for (int j = 0; j < kGemmTok / 2; ++j) xp[j] = a.xp + act_tile_offset(min(tb0 + p + 2 * j, TB - 1), 0, TB) + lane * 8;
+        auto issue = [&](int j) __attribute__((always_inline)) {      // step j (past the end: the last step again, never read)
+            const size_t woff = (size_t)kstep(j) * 512, xoff = woff * TB;
+            bf16_t (*slot)[512] = s_w[j % kGemmDepth];
+#pragma unroll
+            for (int i = 0; i < kGemmRows / 2; ++i)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wp[i] + woff),
+                                                 (__attribute__((address_space(3))) void *)&slot[p + 2 * i][0], 16, 0, 0);
+#pragma unroll
+            for (int i = 0; i < kGemmTok / 2; ++i)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xp[i] + xoff),
+                                                 (__attribute__((address_space(3))) void *)&slot[kGemmRows + p + 2 * i][0], 16, 0, 0);
+        };
+        for (int j = 0; j < kGemmDepth - 1; ++j) issue(j);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PL * (kGemmDepth - 2)) : "memory");      // step 0 has landed
+        __builtin_amdgcn_s_barrier();
+        for (int i = 0; i < KC; ++i) {
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PL * (kGemmDepth - 3)) : "memory");  // step i + 1 has landed
+            __builtin_amdgcn_s_barrier();
+            issue(i + kGemmDepth - 1);                // into the slot of step i - 1, which every wave has read by now
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // nothing may land in LDS after the workgroup has gone
+        return;
+    }
+
+    // ---- multiplying wave: row blocks 4 wr .. + 3 of the group, token blocks 4 wt .. + 3 of the sweep ----
+    const int wr = wave & 1, wt = wave >> 1;
+    f32x4_t acc[4][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[j][b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    u32x4_t fw[2][4], fx[2][4];                       // fragments of step i + 1 are read while step i is multiplied
+    auto fetch = [&](int set, int slot) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fw[set][j] = *reinterpret_cast<const u32x4_t *>(&s_w[slot][4 * wr + j][lane * 8]);
+#pragma unroll
+        for (int b = 0; b < 4; ++b) fx[set][b] = *reinterpret_cast<const u32x4_t *>(&s_w[slot][kGemmRows + 4 * wt + b][lane * 8]);
+    };
+    __syncthreads();
+    fetch(0, 0);
+    for (int i0 = 0; i0 < KC; i0 += 2) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int i = i0 + s;
+            if (i < KC) {                                  // uniform over the workgroup
+                __syncthreads();
+                fetch((s + 1) & 1, (i + 1) % kGemmDepth);  // past the last step: a slot nobody uses
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        acc[j][b] = __builtin_amdgcn_mfma_f32_16x16x32_f16(
+                            __builtin_bit_cast(f16x8_t, fw[s][j]), __builtin_bit_cast(f16x8_t, fx[s][b]), acc[j][b], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int rb = g * kGemmRows + 4 * wr + j, tb = tb0 + 4 * wt + b;
+            block_epilogue<EPI>(a, s_t[wave], rb, tb, acc[j][b], rb < NB && tb < TB, T, lane);
+        }
+}
+
 // Sum of the K slabs that k_linear_mfma_wt<..., SK = true, TPW> left in memory, in slab order, then
 // the epilogue.  One wave per 16 x 16 block; grid = ceil(row blocks * NT / 4) workgroups, NT = 4 TPW.
 template <int EPI, int NT = kWideTok>
