@@ -439,9 +439,12 @@ void launch_valu(ead_handle *h, int mi, LinArgs<WT> &a, int T, int grid) {
 }
 
 // T: the host's count of token rows.  The shape of the matrix and ceil(T / 16) pick the kernel:
-//  * large matrices, more than 32 rows (QKV and residual projections: more than 16): k_linear_mfma_wt, 64 or 128 rows per
-//    sweep, eight row blocks per workgroup; where that gives fewer workgroups than compute units,
-//    K is split over workgroups and k_sk_merge adds the slabs;
+//  * large matrices, more than 32 rows (QKV and residual projections: more than 16): k_linear_mfma_ls, 64 to 128
+//    rows per sweep, eight (gate/up: seven) row blocks per workgroup; where that gives fewer workgroups than
+//    compute units, K is split over workgroups and k_sk_merge adds the slabs.  k_linear_mfma_wt is the
+//    fallback should the device not grant the LDS k_linear_mfma_ls asks for;
+//  * passes of 32 token blocks or more (prefill): no split of K; every matrix takes one workgroup per
+//    (row-block group, sweep), the large ones in 128 x 256 tiles (k_linear_mfma_gemm) where those fill the chip;
 //  * large matrices at fewer rows, and the LM head: k_linear_mfma with four waves
 //    of four row blocks each (an activation tile is fetched once for four weight tiles) where
 //    there are many row blocks, else with K split over KS workgroups per group of four row blocks
@@ -488,14 +491,14 @@ void launch_mfma(ead_handle *h, int mi, LinArgs<bf16_t> &a, int T, int grid_cap 
     const int rpw = cfg == 3 ? 2 : cfg;                  // row blocks per workgroup
     int grid = (NB + rpw - 1) / rpw;
     if constexpr (EPI != EPI_LOGITS) {
-        // more than 32 rows: 64 or 128 rows per sweep, weight tiles shared through LDS.  Matrices with few
+        // more than 32 rows: 64 to 128 rows per sweep, weight tiles shared through LDS.  Matrices with few
         // row blocks are split along K over workgroups; a second kernel adds the slabs in order and
-        // runs the epilogue.  Longer passes (prefill, teacher-forced scoring) take one launch pair per
-        // sweep, or one workgroup per (group, sweep) where K is not split.
+        // runs the epilogue.  Passes of two or three sweeps (teacher-forced scoring) take one launch pair per
+        // sweep, or one workgroup per (group, sweep) where K is not split; longer ones (prefill) see below.
         // (17-32 rows: measured better for the split-K matrices, 32 against 34 us, not for gate/up, 72 against 69)
         if ((big && (TB > 2 || (TB == 2 && EPI != EPI_SWIGLU))) || TB >= 4 * kWideTok) {
             // token blocks per sweep: four up to 64 rows; the pass's own five to eight for 65-128 rows, one
-            // wave per block; eight (two per wave) for the sweeps of longer passes
+            // wave per block; eight for the sweeps of longer passes
             const bool multi = TB > kWideTok;
             const int NG = (NB + 7) / 8, nt = TB <= 4 ? 4 : (multi ? kWideTok : TB);
             // passes of four sweeps or more: one workgroup per (group, sweep) for every matrix.  Cost of a

@@ -50,7 +50,7 @@ struct LinArgs {
     const int *samp_seq, *samp_ngen;
     // MFMA path with K split over KS workgroups per row-block group
     int tb_base;            // k_linear_mfma_wt with split K, k_sk_merge: first token block of the sweep this launch takes
-    int sweeps;             // k_linear_mfma_wt without split K: > 1 = one workgroup per (row-block group, 128-row sweep)
+    int sweeps;             // without split K: > 1 = one workgroup per (row-block group, sweep of 128 rows; k_linear_mfma_gemm: 256)
     int KS;
     float *sk_part;         // [KS][groups][R][NT][256] partial sums
     int *sk_tickets;        // [groups] arrival counters, zero between launches
@@ -644,7 +644,7 @@ __global__ __launch_bounds__(NW * 64) void k_linear_mfma_wt(LinArgs<bf16_t> a) {
 }
 
 // ------------------------------------------------------------------------------------
-// Single-sweep passes of 33-128 rows with the weight stream decoupled from the arithmetic.
+// Passes of 33-128 rows, and the 128-row sweeps of longer passes, with the weight stream decoupled from the arithmetic.
 // In k_linear_mfma_wt every wave fetches weights (from HBM), fetches activations (from L2) and
 // multiplies; a wave's loads complete in order, so its slow weight fetches and its fast
 // activation fetches wait for each other, and what a wave can keep in flight is bounded by its
