@@ -250,7 +250,8 @@ def test_qwen_truncated_batch_with_ragged_prompts_and_catchups():
 
 def test_qwen_truncated_1024_row_prefill_against_oracle():
     """Qwen-shaped widths (2 layers each, gains 1 + N(0, 0.3^2)): a 1025-token prompt is prefilled in one pass of
-    1024 rows per model (eight 128-row sweeps per matrix, attention over up to 1024 keys in row groups); then
+    1024 rows per model (four sweeps of the 128 x 256 tiles through the large matrices, eight 128-row sweeps through
+    the small model's; attention over up to 1024 keys in row groups); then
     Algorithm 1 runs along the oracle's own trajectory: ten small-model tokens, the large model's catch-up of
     eleven rows on top of its 1024 cached positions, two large-model tokens.  Entropies, window means and clear
     arg maxes of all twelve tokens against the oracle."""
@@ -274,11 +275,36 @@ def test_qwen_truncated_1024_row_prefill_against_oracle():
     e.close()
 
 
+def test_ragged_row_block_counts_in_a_1024_row_prefill_against_oracle():
+    """Widths whose row-block counts are not multiples of what a workgroup takes (gate/up of the large model: 740
+    row blocks in groups of 8 through the 128 x 256 tiles; its down projection: 128 row blocks in groups of 5
+    through the 128-row sweeps; the small model's gate/up: 372 row blocks): the last group of every such launch
+    holds row blocks that do not exist.  A 1025-token prompt is prefilled in one pass of 1024 rows per model and
+    Algorithm 1 then runs along the oracle's trajectory (ten small-model tokens, the large model's catch-up,
+    two large-model tokens); entropies, window means and clear arg maxes against the oracle."""
+    from gpu_helpers import check_replay_row, make_pair, trajectory_logit_stats
+    ead = _ead()
+    ss = si.ModelShape("ragged-s", 2, 1024, 8, 2, 2976, 4096, 1e-5, 1e4)
+    sl = si.ModelShape("ragged-l", 2, 2048, 16, 4, 5920, 4096, 1e-5, 1e4)
+    Ws, Wl, os_, ol = make_pair(ss, sl, seed=8, gain_std=0.3, lm_sigma=1.5)
+    prompt = si.prompt_np(8, "r1025", 1025, ss.vocab)
+    ref = oracle.generate(os_, ol, prompt, 12, 5, 0.0, d_min=10)
+    assert list(ref["model_id"]) == [0] * 10 + [1] * 2
+    stats = trajectory_logit_stats(os_, ol, prompt, ref["tokens"], ref["model_id"])
+    e = ead.EAD(ss, Ws, sl, Wl, window=5, tau=0.0, d_min=10, max_batch=1, max_seq=1056)
+    rp = e.replay([prompt], ref["tokens"], ref["model_id"])
+    n_dec, n_arg = check_replay_row(rp, 0, ref, 0.0, 12, stats)
+    print(f"  H err {np.abs(rp['H'][0] - ref['H']).max():.2e}; decisions checked {n_dec}/12, clear arg maxes {n_arg}/12", flush=True)
+    assert n_dec == 12
+    e.close()
+
+
 def test_qwen_truncated_long_prefill_agrees_with_scoring():
     """Qwen-shaped widths (2 layers each): a 600-token prompt is prefilled in one pass of 599 rows
-    (five 128-row sweeps per matrix, one launch pair per sweep where K is split, row groups of 2 and
-    3 in the attention); the entropies of the following tokens -- small model, then the large one
-    after a 10-row catch-up -- equal those of scoring the same tokens in passes of 160 rows."""
+    (38 token blocks: three sweeps of the 128 x 256 tiles or five 128-row sweeps per matrix, the last of them
+    partly empty; row groups of 2 and 3 in the attention); the entropies of the following tokens -- small
+    model, then the large one after a 10-row catch-up -- equal those of scoring the same tokens in passes of
+    160 rows (two sweeps, one launch pair per sweep where K is split)."""
     ead = _ead()
     ss, sl = (s.truncated(2) for s in si.PAIRS["qwen"])
     Ws = si.model_weights_torch(ss, 0, "cuda")
